@@ -1,0 +1,149 @@
+/*
+ * q4kv.h -- C ABI of libq4kv: batched attention over many agents' paged, 4-bit
+ * group-quantized KV caches on one AMD MI355X (gfx950), plus the Q4 pack/unpack
+ * codec used when a cache is saved or restored.
+ *
+ * Conventions that hold for every entry point
+ *   - "device" pointers are GPU global memory owned by the caller (for example the
+ *     storage of a torch tensor).  The library allocates no device memory and keeps
+ *     no state between calls.  "host" pointers are ordinary process memory.
+ *   - Calls only enqueue work on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and return without synchronising.
+ *   - Return value: Q4KV_OK (0) or a negative q4kv_status.  Argument errors are found
+ *     on the host before anything is launched; q4kv_last_error() then gives a message
+ *     (thread-local, valid until the same thread's next failing call).
+ *   - binary16 values travel as uint16_t bit patterns.  Inputs must be finite.
+ *   - Calls that overlap in time on different streams are safe as long as their
+ *     output and workspace buffers do not overlap.
+ *
+ * The Q4 format (Sec. 3.2 "Q4 Quantization Pipeline" of the paper; arithmetic fixed
+ * by the project brief where the paper defers to its framework): a row of `dim`
+ * elements is cut into groups of 64 consecutive elements along head_dim.  Per group:
+ *     bias  = min x                          stored as binary16 (exact)
+ *     scale = (max x - min x) / 15           computed in binary32, stored as binary16 (RNE)
+ *     code  = clamp(rint((x - min) / scale_stored), 0, 15)   binary32 division, ties to even;
+ *             all codes 0 when scale_stored == 0
+ * Element d of a row lives in 32-bit word d/8, bits 4*(d%8) .. 4*(d%8)+3.
+ * Bytes per row: dim/2 (codes) + 2*dim/64 (scale) + 2*dim/64 (bias), i.e. K+V of a
+ * layer take h*d*n*(1 + 8/64) bytes, the paper's count.
+ */
+#ifndef Q4KV_H
+#define Q4KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    Q4KV_OK = 0,
+    Q4KV_EINVAL = -1,     /* null / misaligned pointer, negative count, bad layer range */
+    Q4KV_ESHAPE = -2,     /* unsupported dims: dim % 64, q_heads % kv_heads, head widths, group/block size */
+    Q4KV_ERANGE = -3,     /* max_seq_len exceeds what the block table can address */
+    Q4KV_EWORKSPACE = -4, /* workspace too small or missing */
+    Q4KV_EHIP = -5        /* the HIP runtime refused a launch */
+} q4kv_status;
+
+/* Shape descriptor of one model's cache: the paper's ModelCacheSpec (Sec. 3.1, and
+ * Sec. 3.6 for v_dim != k_dim).  The library reads nothing model-specific beyond it. */
+typedef struct {
+    int32_t num_layers;
+    int32_t num_q_heads;
+    int32_t num_kv_heads;   /* divides num_q_heads; query head h reads KV head h / (num_q_heads/num_kv_heads) */
+    int32_t k_dim;          /* multiple of 64 */
+    int32_t v_dim;          /* multiple of 64 */
+    int32_t v_aliases_k;    /* 1: a token's V row is the first v_dim elements of its K row (one shared
+                               latent per token); the V pool argument must then be NULL */
+    int32_t block_tokens;   /* 256, the paper's block size (Sec. 3.1) */
+    int32_t group_size;     /* 64 */
+} q4kv_spec;
+
+/* One paged Q4 pool (K or V) for all layers, device memory, row-major:
+ *   codes [num_layers][num_blocks][num_kv_heads][block_tokens][dim/8]   uint32
+ *   scale [num_layers][num_blocks][num_kv_heads][block_tokens][dim/64]  binary16 bits
+ *   bias  same shape as scale
+ * All three base pointers must be 16-byte aligned.  A block id indexes the second axis;
+ * an agent owns the blocks its block-table row lists (Sec. 3.1, per-agent isolation). */
+typedef struct {
+    uint32_t *codes;
+    uint16_t *scale;
+    uint16_t *bias;
+    int32_t num_blocks;
+} q4kv_pool;
+
+/* Sec. 3.2, the "save" half of the codec.  Quantize `rows` rows of `dim` binary16 values.
+ *   x      device, [rows][dim], 16-byte aligned
+ *   codes  device out, [rows][dim/8]; scale, bias device out, [rows][dim/64]
+ * Bit-exact with the definition above.  rows == 0 is a no-op.  dim % 64 != 0 -> Q4KV_ESHAPE. */
+int q4kv_quantize(const uint16_t *x, int64_t rows, int32_t dim, uint32_t *codes, uint16_t *scale, uint16_t *bias,
+                  void *hip_stream);
+
+/* Sec. 3.2 / Sec. 4.4 (the dequantization cost on restore): x_hat = code*scale + bias in
+ * binary32, rounded to binary16.  Arguments mirror q4kv_quantize; x is the device output. */
+int q4kv_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows, int32_t dim,
+                    uint16_t *x, void *hip_stream);
+
+/* Sec. 3.4, first half of update_and_fetch: quantize new K/V rows and store them behind
+ * each agent's cached tokens.
+ *   k_new, v_new    device, [layer_end-layer_begin][num_agents][chunk_len][num_kv_heads][dim] binary16
+ *                   (v_new and v must be NULL when spec->v_aliases_k)
+ *   block_table     device int32 [num_agents][max_blocks]; entry i of a row is the physical block that
+ *                   holds tokens 256*i .. 256*i+255 of that agent; it must already list the blocks the
+ *                   new tokens fall into
+ *   seq_len_before  device int32 [num_agents], tokens cached before this call
+ * Token seq_len_before[a]+c of agent a receives chunk row c.  A token whose table slot is beyond
+ * max_blocks or whose block id is outside the pool is skipped (nothing is written for it). */
+int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *k_new,
+                const uint16_t *v_new, const int32_t *block_table, int32_t max_blocks,
+                const int32_t *seq_len_before, int32_t num_agents, int32_t chunk_len, int32_t layer_begin,
+                int32_t layer_end, void *hip_stream);
+
+/* Sec. 3.4, second half of update_and_fetch, and Sec. 3.6 (GQA grouping, causal chunk masks):
+ * out = softmax(sm_scale * q K_hat^T) V_hat per agent, layer and query head, directly on the Q4
+ * pools (nothing is dequantized to memory).
+ *   q            device, [layer_end-layer_begin][num_agents][q_len][num_q_heads][k_dim] binary16
+ *   out          device out, same leading shape, v_dim wide, binary16
+ *   seq_len      device int32 [num_agents]: keys visible to the LAST query row of each agent, the
+ *                appended chunk included; row r sees the first seq_len[a] - (q_len-1-r) tokens
+ *                (q_len == 1: decode).  A row with no visible key yields zeros.
+ *   max_seq_len  host upper bound of seq_len[]; it sizes the launch.  seq_len values above it are
+ *                clamped to it on the device.  max_seq_len > max_blocks*256 -> Q4KV_ERANGE.
+ *   window       <= 0: global attention.  > 0: row at position p also requires t > p - window
+ *                (sliding-window layers, Sec. 3.6).
+ *   split_tokens tokens per split-K work item (multiple of 256), 0 = library picks; must equal the
+ *                value given to q4kv_attention_workspace_bytes.
+ *   workspace    device scratch of at least q4kv_attention_workspace_bytes(...) bytes, 16-byte aligned;
+ *                contents before and after the call are unspecified.
+ * Block ids outside [0, num_blocks) are skipped on the device (their tokens count as masked).
+ * Outputs are run-to-run bit-identical for identical arguments. */
+int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                           uint16_t *out, const int32_t *block_table, int32_t max_blocks, const int32_t *seq_len,
+                           int32_t num_agents, int32_t q_len, int32_t max_seq_len, float sm_scale, int32_t window,
+                           int32_t split_tokens, int32_t layer_begin, int32_t layer_end, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of workspace q4kv_batched_attention needs for these arguments (0 on bad arguments). */
+size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                      int32_t split_tokens, int32_t num_layers_in_call);
+
+/* The split size the library would pick for split_tokens == 0 (0 on bad arguments). */
+int32_t q4kv_default_split_tokens(const q4kv_spec *spec, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                  int32_t num_layers_in_call);
+
+/* Sec. 3.2 closed form: Q4 bytes (K and V, all layers) of `tokens` cached tokens:
+ * layers * kv_heads * (k_dim + v_dim) * tokens * (1/2 + 4/64); v_dim counts 0 when V aliases K.
+ * Negative on bad arguments. */
+int64_t q4kv_cache_bytes(const q4kv_spec *spec, int64_t tokens);
+
+/* Message of this thread's most recent failing call ("" if none). */
+const char *q4kv_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int q4kv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* Q4KV_H */

@@ -10,7 +10,7 @@ import os
 
 import numpy as np
 
-from .build import LIB, build
+from .build import LIB, build as _build_oracle
 
 GROUP = 64
 
@@ -31,7 +31,7 @@ class _Pool(C.Structure):
 def lib():
     global _lib
     if _lib is None:
-        build(force=False)
+        _build_oracle(force=False)
         _lib = C.CDLL(LIB)
         _lib.oracle_h2f.restype = C.c_float
         _lib.oracle_h2f.argtypes = [C.c_uint16]

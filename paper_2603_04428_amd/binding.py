@@ -1,0 +1,185 @@
+"""ctypes binding of libq4kv.so: the same entry points as include/q4kv.h, taking torch tensors.
+
+Argument marshalling only -- pointers, sizes and the current HIP stream are handed to the C ABI;
+every step of the path runs in the library's kernels.  There is no fallback: if the shared
+library is missing or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libq4kv.so")
+
+EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_append", "q4kv_batched_attention",
+           "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_last_error",
+           "q4kv_version"]
+
+
+class Q4KVError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libq4kv error {code}: {msg}")
+        self.code = code
+
+
+class Spec(C.Structure):
+    """q4kv_spec"""
+    _fields_ = [("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
+                ("k_dim", C.c_int32), ("v_dim", C.c_int32), ("v_aliases_k", C.c_int32),
+                ("block_tokens", C.c_int32), ("group_size", C.c_int32)]
+
+
+class _CPool(C.Structure):
+    """q4kv_pool"""
+    _fields_ = [("codes", C.c_void_p), ("scale", C.c_void_p), ("bias", C.c_void_p), ("num_blocks", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libq4kv.so (built in-tree by paper_2603_04428_amd/build.py); raise if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(there is no fallback path)")
+        l = C.CDLL(LIB_PATH)
+        vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        l.q4kv_quantize.argtypes = [vp, i64, i32, vp, vp, vp, vp]
+        l.q4kv_dequantize.argtypes = [vp, vp, vp, i64, i32, vp, vp]
+        l.q4kv_append.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32, vp, i32, i32,
+                                  i32, i32, vp]
+        l.q4kv_batched_attention.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32, vp,
+                                             i32, i32, i32, C.c_float, i32, i32, i32, i32, vp, C.c_size_t, vp]
+        l.q4kv_attention_workspace_bytes.restype = C.c_size_t
+        l.q4kv_attention_workspace_bytes.argtypes = [C.POINTER(Spec), i32, i32, i32, i32, i32]
+        l.q4kv_default_split_tokens.restype = i32
+        l.q4kv_default_split_tokens.argtypes = [C.POINTER(Spec), i32, i32, i32, i32]
+        l.q4kv_cache_bytes.restype = i64
+        l.q4kv_cache_bytes.argtypes = [C.POINTER(Spec), i64]
+        l.q4kv_last_error.restype = C.c_char_p
+        l.q4kv_version.restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise Q4KVError(rc, lib().q4kv_last_error().decode())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name}: need a contiguous {dtype} tensor on the GPU, got {t.dtype} on {t.device}")
+    return C.c_void_p(t.data_ptr())
+
+
+def make_spec(num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, block_tokens=256):
+    return Spec(num_layers, num_q_heads, num_kv_heads, k_dim, k_dim if v_dim is None else v_dim,
+                1 if v_aliases_k else 0, block_tokens, 64)
+
+
+class Pool:
+    """Device arrays of one paged Q4 pool: [layers][blocks][kv_heads][256][dim/8 | dim/64]."""
+
+    def __init__(self, spec, dim, num_blocks, device="cuda", poison=False):
+        shp = (spec.num_layers, num_blocks, spec.num_kv_heads, spec.block_tokens)
+        self.dim, self.num_blocks = dim, num_blocks
+        # torch has no uint32/uint16 arithmetic, and none is needed: int32 / int16 storage of the same bits
+        self.codes = torch.zeros(shp + (dim // 8,), dtype=torch.int32, device=device)
+        self.scale = torch.zeros(shp + (dim // 64,), dtype=torch.int16, device=device)
+        self.bias = torch.zeros(shp + (dim // 64,), dtype=torch.int16, device=device)
+        if poison:                      # every slot decodes to NaN until it is written
+            self.codes.fill_(-1)
+            self.scale.fill_(0x7E00)
+            self.bias.fill_(0x7E00)
+
+    def c(self):
+        return _CPool(self.codes.data_ptr(), self.scale.data_ptr(), self.bias.data_ptr(), self.num_blocks)
+
+
+def q4kv_version():
+    return lib().q4kv_version()
+
+
+def q4kv_cache_bytes(spec, tokens):
+    r = lib().q4kv_cache_bytes(C.byref(spec), tokens)
+    if r < 0:
+        _check(-1)
+    return r
+
+
+def q4kv_quantize(x, codes=None, scale=None, bias=None):
+    """x: fp16 [..., dim] on the GPU -> (codes int32 [..., dim/8], scale int16 [..., dim/64], bias same)."""
+    dim = x.shape[-1]
+    rows = x.numel() // dim if dim else 0
+    lead = tuple(x.shape[:-1])
+    if codes is None:
+        codes = torch.empty(lead + (dim // 8,), dtype=torch.int32, device=x.device)
+        scale = torch.empty(lead + (dim // 64,), dtype=torch.int16, device=x.device)
+        bias = torch.empty(lead + (dim // 64,), dtype=torch.int16, device=x.device)
+    _check(lib().q4kv_quantize(_dev(x, torch.float16, "x"), rows, dim, _dev(codes, torch.int32, "codes"),
+                               _dev(scale, torch.int16, "scale"), _dev(bias, torch.int16, "bias"), _stream()))
+    return codes, scale, bias
+
+
+def q4kv_dequantize(codes, scale, bias, out=None):
+    dim = codes.shape[-1] * 8
+    rows = codes.numel() // codes.shape[-1] if codes.shape[-1] else 0
+    if out is None:
+        out = torch.empty(tuple(codes.shape[:-1]) + (dim,), dtype=torch.float16, device=codes.device)
+    _check(lib().q4kv_dequantize(_dev(codes, torch.int32, "codes"), _dev(scale, torch.int16, "scale"),
+                                 _dev(bias, torch.int16, "bias"), rows, dim, _dev(out, torch.float16, "out"),
+                                 _stream()))
+    return out
+
+
+def q4kv_append(spec, kpool, vpool, k_new, v_new, block_table, seq_len_before, layer_begin=0, layer_end=None):
+    """k_new / v_new: fp16 [layers_in_call][A][C][kv_heads][dim]; block_table int32 [A][max_blocks] (device)."""
+    layer_end = spec.num_layers if layer_end is None else layer_end
+    A, Cn = k_new.shape[1], k_new.shape[2]
+    kp = kpool.c()
+    vp = None if spec.v_aliases_k else vpool.c()
+    _check(lib().q4kv_append(C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp),
+                             _dev(k_new, torch.float16, "k_new"), _dev(v_new, torch.float16, "v_new"),
+                             _dev(block_table, torch.int32, "block_table"), block_table.shape[1],
+                             _dev(seq_len_before, torch.int32, "seq_len_before"), A, Cn, layer_begin, layer_end,
+                             _stream()))
+
+
+def q4kv_default_split_tokens(spec, num_agents, q_len, max_seq_len, layers_in_call):
+    return lib().q4kv_default_split_tokens(C.byref(spec), num_agents, q_len, max_seq_len, layers_in_call)
+
+
+def q4kv_attention_workspace_bytes(spec, num_agents, q_len, max_seq_len, split_tokens, layers_in_call):
+    return lib().q4kv_attention_workspace_bytes(C.byref(spec), num_agents, q_len, max_seq_len, split_tokens,
+                                                layers_in_call)
+
+
+def q4kv_batched_attention(spec, kpool, vpool, q, block_table, seq_len, max_seq_len, sm_scale, window=0,
+                           split_tokens=0, layer_begin=0, layer_end=None, out=None, workspace=None):
+    """q: fp16 [layers_in_call][A][q_len][q_heads][k_dim] -> fp16 out of the same leading shape, v_dim wide."""
+    layer_end = spec.num_layers if layer_end is None else layer_end
+    Lr, A, q_len = q.shape[0], q.shape[1], q.shape[2]
+    if out is None:
+        out = torch.empty((Lr, A, q_len, spec.num_q_heads, spec.v_dim), dtype=torch.float16, device=q.device)
+    need = q4kv_attention_workspace_bytes(spec, max(A, 1), q_len, max_seq_len, split_tokens, max(Lr, 1))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    kp = kpool.c()
+    vp = None if spec.v_aliases_k else vpool.c()
+    _check(lib().q4kv_batched_attention(C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp),
+                                        _dev(q, torch.float16, "q"), _dev(out, torch.float16, "out"),
+                                        _dev(block_table, torch.int32, "block_table"), block_table.shape[1],
+                                        _dev(seq_len, torch.int32, "seq_len"), A, q_len, max_seq_len, float(sm_scale),
+                                        int(window), int(split_tokens), layer_begin, layer_end,
+                                        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()))
+    return out

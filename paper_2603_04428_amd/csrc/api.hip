@@ -1,0 +1,231 @@
+// The C ABI of libq4kv (include/q4kv.h): argument validation on the host, launch planning
+// (split-K schedule), and nothing else -- every step of the path runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "q4kv_internal.h"
+
+namespace {
+
+thread_local char g_error[256] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_spec(const q4kv_spec *s)
+{
+    if (!s) return fail(Q4KV_EINVAL, "spec is NULL");
+    if (s->num_layers <= 0 || s->num_q_heads <= 0 || s->num_kv_heads <= 0)
+        return fail(Q4KV_ESHAPE, "layer/head counts must be positive");
+    if (s->num_q_heads % s->num_kv_heads) return fail(Q4KV_ESHAPE, "num_q_heads %% num_kv_heads != 0");
+    if (s->group_size != 64) return fail(Q4KV_ESHAPE, "group_size must be 64");
+    if (s->block_tokens != 256) return fail(Q4KV_ESHAPE, "block_tokens must be 256");
+    if (s->k_dim <= 0 || s->v_dim <= 0 || s->k_dim % 64 || s->v_dim % 64)
+        return fail(Q4KV_ESHAPE, "k_dim and v_dim must be positive multiples of 64");
+    if (s->v_aliases_k && s->v_dim > s->k_dim) return fail(Q4KV_ESHAPE, "v_aliases_k needs v_dim <= k_dim");
+    return Q4KV_OK;
+}
+
+int check_pool(const q4kv_pool *p, const char *name)
+{
+    if (!p) return fail(Q4KV_EINVAL, "%s pool is NULL", name);
+    if (!p->codes || !p->scale || !p->bias) return fail(Q4KV_EINVAL, "%s pool has a NULL array", name);
+    if (!aligned16(p->codes) || !aligned16(p->scale) || !aligned16(p->bias))
+        return fail(Q4KV_EINVAL, "%s pool arrays must be 16-byte aligned", name);
+    if (p->num_blocks <= 0) return fail(Q4KV_EINVAL, "%s pool has no blocks", name);
+    return Q4KV_OK;
+}
+
+int round_up(int x, int m) { return (x + m - 1) / m * m; }
+
+// Split size when the caller leaves the choice to the library: enough work items to give every
+// CU several workgroups, but no smaller than one block.
+int pick_split_tokens(const q4kv_spec &s, int num_agents, int max_seq_len, int layers)
+{
+    const int64_t units = (int64_t)layers * num_agents * s.num_kv_heads;
+    const int64_t want_items = 256 * 2 * 16; // CUs * resident workgroups * rounds
+    int64_t splits_per_unit = units > 0 ? (want_items + units - 1) / units : 1;
+    if (splits_per_unit < 1) splits_per_unit = 1;
+    int64_t tokens = (max_seq_len + splits_per_unit - 1) / splits_per_unit;
+    if (tokens < 256) tokens = 256;
+    return round_up((int)tokens, 256);
+}
+
+} // namespace
+
+extern "C" {
+
+int q4kv_version(void) { return 100; }
+
+const char *q4kv_last_error(void) { return g_error; }
+
+int64_t q4kv_cache_bytes(const q4kv_spec *spec, int64_t tokens)
+{
+    if (check_spec(spec) != Q4KV_OK) return -1;
+    if (tokens < 0) {
+        fail(Q4KV_EINVAL, "tokens < 0");
+        return -1;
+    }
+    const int64_t width = spec->k_dim + (spec->v_aliases_k ? 0 : spec->v_dim);
+    const int64_t elems = (int64_t)spec->num_layers * spec->num_kv_heads * width * tokens;
+    return elems / 2 + 4 * (elems / 64);
+}
+
+int q4kv_quantize(const uint16_t *x, int64_t rows, int32_t dim, uint32_t *codes, uint16_t *scale, uint16_t *bias,
+                  void *hip_stream)
+{
+    if (dim <= 0 || dim % 64) return fail(Q4KV_ESHAPE, "dim must be a positive multiple of 64");
+    if (rows < 0) return fail(Q4KV_EINVAL, "rows < 0");
+    if (rows == 0) return Q4KV_OK;
+    if (!x || !codes || !scale || !bias) return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!aligned16(x) || !aligned16(codes)) return fail(Q4KV_EINVAL, "x and codes must be 16-byte aligned");
+    hipError_t e = q4kv::launch_quantize(x, rows, dim, codes, scale, bias, (hipStream_t)hip_stream);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "quantize launch: %s", hipGetErrorString(e));
+}
+
+int q4kv_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows, int32_t dim,
+                    uint16_t *x, void *hip_stream)
+{
+    if (dim <= 0 || dim % 64) return fail(Q4KV_ESHAPE, "dim must be a positive multiple of 64");
+    if (rows < 0) return fail(Q4KV_EINVAL, "rows < 0");
+    if (rows == 0) return Q4KV_OK;
+    if (!x || !codes || !scale || !bias) return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!aligned16(x) || !aligned16(codes)) return fail(Q4KV_EINVAL, "x and codes must be 16-byte aligned");
+    hipError_t e = q4kv::launch_dequantize(codes, scale, bias, rows, dim, x, (hipStream_t)hip_stream);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "dequantize launch: %s", hipGetErrorString(e));
+}
+
+int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *k_new,
+                const uint16_t *v_new, const int32_t *block_table, int32_t max_blocks,
+                const int32_t *seq_len_before, int32_t num_agents, int32_t chunk_len, int32_t layer_begin,
+                int32_t layer_end, void *hip_stream)
+{
+    int rc = check_spec(spec);
+    if (rc) return rc;
+    if ((rc = check_pool(k, "K"))) return rc;
+    if (spec->v_aliases_k) {
+        if (v || v_new) return fail(Q4KV_EINVAL, "v and v_new must be NULL when v_aliases_k");
+    } else {
+        if ((rc = check_pool(v, "V"))) return rc;
+        if (v->num_blocks != k->num_blocks) return fail(Q4KV_EINVAL, "K and V pools differ in num_blocks");
+    }
+    if (layer_begin < 0 || layer_end > spec->num_layers || layer_begin > layer_end)
+        return fail(Q4KV_EINVAL, "bad layer range [%d, %d)", layer_begin, layer_end);
+    if (num_agents < 0 || chunk_len < 0 || max_blocks <= 0) return fail(Q4KV_EINVAL, "negative count");
+    if (num_agents == 0 || chunk_len == 0 || layer_begin == layer_end) return Q4KV_OK;
+    if (!k_new || (!spec->v_aliases_k && !v_new) || !block_table || !seq_len_before)
+        return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!aligned16(k_new) || (v_new && !aligned16(v_new))) return fail(Q4KV_EINVAL, "k_new/v_new must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = q4kv::launch_append(*spec, *k, spec->k_dim, k_new, block_table, max_blocks, seq_len_before,
+                                       num_agents, chunk_len, layer_begin, layer_end, st);
+    if (e == hipSuccess && !spec->v_aliases_k)
+        e = q4kv::launch_append(*spec, *v, spec->v_dim, v_new, block_table, max_blocks, seq_len_before, num_agents,
+                                chunk_len, layer_begin, layer_end, st);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "append launch: %s", hipGetErrorString(e));
+}
+
+int32_t q4kv_default_split_tokens(const q4kv_spec *spec, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                  int32_t num_layers_in_call)
+{
+    if (check_spec(spec) != Q4KV_OK) return 0;
+    if (num_agents <= 0 || q_len <= 0 || max_seq_len < 0 || num_layers_in_call <= 0) {
+        fail(Q4KV_EINVAL, "bad counts");
+        return 0;
+    }
+    return pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
+}
+
+size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                      int32_t split_tokens, int32_t num_layers_in_call)
+{
+    if (check_spec(spec) != Q4KV_OK) return 0;
+    if (num_agents <= 0 || q_len <= 0 || max_seq_len < 0 || num_layers_in_call <= 0 || split_tokens < 0 ||
+        split_tokens % 256) {
+        fail(Q4KV_EINVAL, "bad counts");
+        return 0;
+    }
+    const int st = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
+    const int64_t splits = max_seq_len > 0 ? (max_seq_len + st - 1) / st : 1;
+    const int64_t units = (int64_t)num_layers_in_call * num_agents * q_len * spec->num_q_heads;
+    return (size_t)(units * splits * (spec->v_dim + 2) * (int64_t)sizeof(float));
+}
+
+int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                           uint16_t *out, const int32_t *block_table, int32_t max_blocks, const int32_t *seq_len,
+                           int32_t num_agents, int32_t q_len, int32_t max_seq_len, float sm_scale, int32_t window,
+                           int32_t split_tokens, int32_t layer_begin, int32_t layer_end, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_spec(spec);
+    if (rc) return rc;
+    if ((rc = check_pool(k, "K"))) return rc;
+    if (spec->v_aliases_k) {
+        if (v) return fail(Q4KV_EINVAL, "v must be NULL when v_aliases_k");
+    } else {
+        if ((rc = check_pool(v, "V"))) return rc;
+        if (v->num_blocks != k->num_blocks) return fail(Q4KV_EINVAL, "K and V pools differ in num_blocks");
+    }
+    if (layer_begin < 0 || layer_end > spec->num_layers || layer_begin > layer_end)
+        return fail(Q4KV_EINVAL, "bad layer range [%d, %d)", layer_begin, layer_end);
+    if (num_agents < 0 || q_len < 1 || max_blocks <= 0 || max_seq_len < 0) return fail(Q4KV_EINVAL, "bad counts");
+    if (split_tokens < 0 || split_tokens % 256) return fail(Q4KV_EINVAL, "split_tokens must be a multiple of 256");
+    if ((int64_t)max_seq_len > (int64_t)max_blocks * 256)
+        return fail(Q4KV_ERANGE, "max_seq_len %d exceeds max_blocks*256 = %lld", max_seq_len,
+                    (long long)max_blocks * 256);
+    if (num_agents == 0 || layer_begin == layer_end) return Q4KV_OK;
+    if (!q || !out || !block_table || !seq_len) return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!aligned16(q) || !aligned16(out)) return fail(Q4KV_EINVAL, "q and out must be 16-byte aligned");
+    const int layers = layer_end - layer_begin;
+    if ((int64_t)num_agents * spec->num_kv_heads > 65535 || layers > 65535)
+        return fail(Q4KV_ESHAPE, "num_agents*num_kv_heads and layers per call must be <= 65535");
+
+    q4kv::AttentionArgs a;
+    a.spec = *spec;
+    a.k = *k;
+    a.v = spec->v_aliases_k ? *k : *v;
+    a.q = q;
+    a.out = out;
+    a.block_table = block_table;
+    a.seq_len = seq_len;
+    a.max_blocks = max_blocks;
+    a.num_agents = num_agents;
+    a.q_len = q_len;
+    a.max_seq_len = max_seq_len;
+    a.window = window;
+    a.split_tokens = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, layers);
+    a.num_splits = max_seq_len > 0 ? (max_seq_len + a.split_tokens - 1) / a.split_tokens : 1;
+    a.layer_begin = layer_begin;
+    a.layers_in_call = layers;
+    a.sm_scale = sm_scale;
+
+    if (q_len != 1) return fail(Q4KV_ESHAPE, "q_len > 1 (chunked append) is not available in this build");
+    if (!q4kv::decode_supported(*spec))
+        return fail(Q4KV_ESHAPE, "no decode kernel for k_dim=%d v_dim=%d n_rep=%d alias=%d", spec->k_dim, spec->v_dim,
+                    spec->num_q_heads / spec->num_kv_heads, spec->v_aliases_k);
+
+    const size_t need = q4kv_attention_workspace_bytes(spec, num_agents, q_len, max_seq_len, a.split_tokens, layers);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace))
+        return fail(Q4KV_EWORKSPACE, "workspace needs %zu bytes (16-byte aligned), got %zu", need, workspace_bytes);
+    const int64_t units = (int64_t)layers * num_agents * q_len * spec->num_q_heads;
+    a.part_acc = static_cast<float *>(workspace);
+    a.part_ml = a.part_acc + units * a.num_splits * spec->v_dim;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipError_t e = q4kv::launch_decode_attention(a, st);
+    if (e == hipSuccess) e = q4kv::launch_combine(a, st);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));
+}
+
+} // extern "C"

@@ -1,0 +1,196 @@
+// Q4 pack / unpack kernels (Sec. 3.2 "Q4 Quantization Pipeline"): the flat codec used when an
+// agent's cache is saved or restored, and the paged form that appends new tokens to a cache
+// (Sec. 3.4, update_and_fetch).  All three stream rows through once and are HBM-bound:
+// 2 bytes in and 0.5625 bytes out per quantized element, the reverse for dequantize.
+//
+// Work layout: one group of 64 elements is handled by 8 consecutive lanes; each lane moves
+// 16 bytes of binary16 input (8 elements) and one 32-bit word of codes, so both the loads and
+// the stores of a wavefront are contiguous.
+#include "q4_device.h"
+#include "q4kv_internal.h"
+
+namespace q4kv {
+namespace {
+
+constexpr int kThreads = 256;
+
+#pragma clang fp contract(off)
+
+// Quantize the 8 elements held by this lane; the 8 lanes of an octet form one group.
+// Returns the packed word; *scale_bits / *bias_bits are the group's stored parameters.
+__device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet, uint16_t *scale_bits,
+                                                   uint16_t *bias_bits)
+{
+    const uint32_t wds[4] = {raw.x, raw.y, raw.z, raw.w};
+    float x[8];
+    uint16_t xb[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        xb[2 * i] = (uint16_t)(wds[i] & 0xffffu);
+        xb[2 * i + 1] = (uint16_t)(wds[i] >> 16);
+        x[2 * i] = half_bits_to_float(xb[2 * i]);
+        x[2 * i + 1] = half_bits_to_float(xb[2 * i + 1]);
+    }
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+        mn = fminf(mn, x[i]);
+        mx = fmaxf(mx, x[i]);
+    }
+    // octet-wide min / max: partner lanes 7-j, j^2, j^1 (three DPP-able exchanges)
+#pragma unroll
+    for (int off = 4; off >= 1; off >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, off, 8));
+        mx = fmaxf(mx, __shfl_xor(mx, off, 8));
+    }
+    // The stored bias is the bit pattern of the first minimal element.  Only a zero minimum has two
+    // encodings; then the sign of the first zero in the group decides.
+    uint16_t bb = float_to_half_bits(mn);
+    if (mn == 0.0f) {
+        uint32_t key = 0xffffffffu; // (position << 1) | sign of the first zero seen by this lane
+#pragma unroll
+        for (int i = 7; i >= 0; --i)
+            if (x[i] == 0.0f) key = ((uint32_t)(lane_in_octet * 8 + i) << 1) | (uint32_t)(xb[i] >> 15);
+#pragma unroll
+        for (int off = 4; off >= 1; off >>= 1) key = min(key, (uint32_t)__shfl_xor((int)key, off, 8));
+        bb = (key & 1u) ? 0x8000u : 0x0000u;
+    }
+    const float scale32 = (mx - mn) / 15.0f;      // IEEE binary32 division
+    const uint16_t sb = float_to_half_bits(scale32);
+    const float s = half_bits_to_float(sb);
+    uint32_t word = 0;
+    if (s != 0.0f) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float r = __builtin_rintf((x[i] - mn) / s); // ties to even
+            r = fminf(fmaxf(r, 0.0f), 15.0f);
+            word |= (uint32_t)r << (4 * i);
+        }
+    }
+    *scale_bits = sb;
+    *bias_bits = bb;
+    return word;
+}
+
+// rows are addressed through `map`, which turns a source row index into a destination row index
+// (or -1 to skip the row).
+struct FlatRows {
+    __device__ __forceinline__ int64_t operator()(int64_t row) const { return row; }
+};
+
+struct PagedRows { // source rows [layers_in_call][A][C][H] -> pool rows [layer][block][H][slot]
+    const int32_t *block_table;
+    const int32_t *seq_len_before;
+    int max_blocks, num_agents, chunk_len, heads, layer_begin, num_blocks;
+    __device__ __forceinline__ int64_t operator()(int64_t row) const
+    {
+        const int h = (int)(row % heads);
+        int64_t r = row / heads;
+        const int c = (int)(r % chunk_len);
+        r /= chunk_len;
+        const int a = (int)(r % num_agents);
+        const int li = (int)(r / num_agents);
+        const int t = seq_len_before[a] + c;
+        const int bi = t / kBlockTokens;
+        if (t < 0 || bi >= max_blocks) return -1;
+        const int blk = block_table[(int64_t)a * max_blocks + bi];
+        if (blk < 0 || blk >= num_blocks) return -1;
+        return (((int64_t)(layer_begin + li) * num_blocks + blk) * heads + h) * kBlockTokens + (t % kBlockTokens);
+    }
+};
+
+template <class RowMap>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__restrict__ x, int64_t total_groups,
+                                                            int groups_per_row, uint32_t *__restrict__ codes,
+                                                            uint16_t *__restrict__ scale,
+                                                            uint16_t *__restrict__ bias, RowMap map)
+{
+    const int sub = threadIdx.x & 7;
+    const int64_t stride = (int64_t)gridDim.x * (kThreads / 8);
+    for (int64_t grp = (int64_t)blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); grp < total_groups; grp += stride) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(x + grp * kGroup + sub * 8);
+        uint16_t sb, bb;
+        const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
+        const int64_t row = grp / groups_per_row;
+        const int g = (int)(grp % groups_per_row);
+        const int64_t drow = map(row);
+        if (drow < 0) continue;
+        const int64_t dgrp = drow * groups_per_row + g;
+        codes[dgrp * 8 + sub] = word;
+        if (sub == 0) {
+            scale[dgrp] = sb;
+            bias[dgrp] = bb;
+        }
+    }
+}
+
+// One lane per word: 8 codes -> 8 binary16 values (16 bytes).
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__restrict__ codes,
+                                                              const uint16_t *__restrict__ scale,
+                                                              const uint16_t *__restrict__ bias, int64_t total_words,
+                                                              uint16_t *__restrict__ x)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x; w < total_words; w += stride) {
+        const uint32_t word = codes[w];
+        const float s = half_bits_to_float(scale[w >> 3]);
+        const float b = half_bits_to_float(bias[w >> 3]);
+        uint32_t o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float lo = (float)((word >> (8 * i)) & 0xfu) * s + b;      // product exact in binary32
+            const float hi = (float)((word >> (8 * i + 4)) & 0xfu) * s + b;
+            o[i] = (uint32_t)float_to_half_bits(lo) | ((uint32_t)float_to_half_bits(hi) << 16);
+        }
+        *reinterpret_cast<uint4 *>(x + w * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+int grid_for(int64_t items, int per_block)
+{
+    int64_t blocks = (items + per_block - 1) / per_block;
+    const int64_t cap = 256 * 32; // 256 CUs, plenty of resident workgroups each; the kernels grid-stride
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return (int)blocks;
+}
+
+} // namespace
+
+hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, uint32_t *codes, uint16_t *scale,
+                           uint16_t *bias, hipStream_t stream)
+{
+    const int G = dim / kGroup;
+    const int64_t groups = rows * G;
+    if (groups == 0) return hipSuccess;
+    hipLaunchKernelGGL(quantize_kernel<FlatRows>, dim3(grid_for(groups, kThreads / 8)), dim3(kThreads), 0, stream, x,
+                       groups, G, codes, scale, bias, FlatRows{});
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
+                             int dim, uint16_t *x, hipStream_t stream)
+{
+    const int64_t words = rows * (dim / 8);
+    if (words == 0) return hipSuccess;
+    hipLaunchKernelGGL(dequantize_kernel, dim3(grid_for(words, kThreads)), dim3(kThreads), 0, stream, codes, scale,
+                       bias, words, x);
+    return hipGetLastError();
+}
+
+hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &pool, int dim, const uint16_t *x_new,
+                         const int32_t *block_table, int max_blocks, const int32_t *seq_len_before, int num_agents,
+                         int chunk_len, int layer_begin, int layer_end, hipStream_t stream)
+{
+    const int G = dim / kGroup;
+    const int64_t rows = (int64_t)(layer_end - layer_begin) * num_agents * chunk_len * spec.num_kv_heads;
+    const int64_t groups = rows * G;
+    if (groups == 0) return hipSuccess;
+    PagedRows map{block_table, seq_len_before, max_blocks, num_agents, chunk_len, spec.num_kv_heads, layer_begin,
+                  pool.num_blocks};
+    hipLaunchKernelGGL(quantize_kernel<PagedRows>, dim3(grid_for(groups, kThreads / 8)), dim3(kThreads), 0, stream,
+                       x_new, groups, G, pool.codes, pool.scale, pool.bias, map);
+    return hipGetLastError();
+}
+
+} // namespace q4kv

@@ -1,0 +1,450 @@
+// Batched decode attention (one query token per agent) over paged Q4 KV caches, GQA form:
+//   out[l][a][h] = softmax(sm * q K_hat^T) V_hat   over the agent's cached tokens,
+// K_hat / V_hat = code*scale + bias, never materialised (Sec. 3.2 item 3, Sec. 3.4, Sec. 3.6).
+//
+// The step is a single pass over the cache and is HBM-bound: per cached token and KV head it reads
+// DK/2 + DV/2 bytes of codes and 4 bytes of scale/bias per 64-wide group, once, for all n_rep
+// query heads of the group.  The design follows from keeping the vector ALUs under that stream:
+//
+//  * split-K: a workgroup owns (layer, agent, KV head, split of `split_tokens` tokens) and emits an
+//    un-normalised partial (acc[DV], running max m, denominator l) per query head; a small combine
+//    kernel merges the splits in a fixed order, so results are run-to-run identical.
+//  * inside a workgroup each of the 4 waves walks its own 64-token tiles (slots 64w..64w+63 of every
+//    256-token block) with private online-softmax state; waves meet only once, at the end.
+//  * codes never become integers or binary32: a nibble masked in place is a binary16 subnormal
+//    (c*2^-24 or c*2^-20), fed straight to v_dot2_f32_f16 (K side) or v_fma_mix (V side).
+//  * the affine part of the dequantization is factored out of the inner loops:
+//        q . K_hat[t]   = sum_g  s[t,g] * (q_g . c[t,g])  +  b[t,g] * sum(q_g)
+//        sum_t p_t V_hat[t,e] = sum_t (p_t s[t,g(e)]) c[t,e]  +  sum_t p_t b[t,g(e)]
+//    so scale and bias are touched once per (token, group), by the lane that owns the token.
+//  * K side: KLPT lanes share a token (each holds 16 bytes = 32 dims of its row), their partial dot
+//    products meet in LDS where the lane owning the token applies scale/bias and does the softmax
+//    bookkeeping; V side: each lane owns 8*VW output dims and walks tokens, reading p*s from LDS.
+#include "q4_device.h"
+#include "q4kv_internal.h"
+
+namespace q4kv {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr float kNegBig = -1.0e30f; // "minus infinity" that survives subtraction
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct DecodeParams {
+    const uint32_t *k_codes, *v_codes;
+    const uint16_t *k_scale, *k_bias, *v_scale, *v_bias;
+    const uint16_t *q;
+    const int32_t *block_table, *seq_len;
+    float *part_acc, *part_ml;
+    int num_blocks, kv_heads, q_heads, num_agents, max_blocks, max_seq_len, window, split_tokens, num_splits;
+    int layer_begin;
+    int v_row_words, v_row_groups; // row pitch of the V pool in words / groups (K's pitch when V aliases K)
+    float score_scale;             // sm_scale * log2(e): scores are kept in log2 units
+};
+
+template <int N>
+struct GroupVec { // N binary16 values = one token's scales or biases
+    uint16_t v[N];
+};
+
+template <int N>
+__device__ __forceinline__ void load_groups(const uint16_t *p, bool valid, float (&out)[N])
+{
+    // N is 1, 2 or 4: one 2-, 4- or 8-byte load
+    if constexpr (N == 1) {
+        uint16_t r = valid ? *p : (uint16_t)0;
+        out[0] = half_bits_to_float(r);
+    } else if constexpr (N == 2) {
+        uint32_t r = valid ? *reinterpret_cast<const uint32_t *>(p) : 0u;
+        out[0] = half_bits_to_float((uint16_t)(r & 0xffffu));
+        out[1] = half_bits_to_float((uint16_t)(r >> 16));
+    } else {
+        static_assert(N % 4 == 0, "group count");
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) {
+            uint2 r = valid ? reinterpret_cast<const uint2 *>(p)[i] : make_uint2(0u, 0u);
+            out[4 * i + 0] = half_bits_to_float((uint16_t)(r.x & 0xffffu));
+            out[4 * i + 1] = half_bits_to_float((uint16_t)(r.x >> 16));
+            out[4 * i + 2] = half_bits_to_float((uint16_t)(r.y & 0xffffu));
+            out[4 * i + 3] = half_bits_to_float((uint16_t)(r.y >> 16));
+        }
+    }
+}
+
+template <int W>
+struct Words {
+    uint32_t w[W];
+};
+
+template <int W>
+__device__ __forceinline__ Words<W> load_words(const uint32_t *p, bool valid)
+{
+    Words<W> r;
+    if constexpr (W == 4) {
+        uint4 t = valid ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0u, 0u, 0u, 0u);
+        r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
+    } else if constexpr (W == 2) {
+        uint2 t = valid ? *reinterpret_cast<const uint2 *>(p) : make_uint2(0u, 0u);
+        r.w[0] = t.x; r.w[1] = t.y;
+    } else {
+        r.w[0] = valid ? *p : 0u;
+    }
+    return r;
+}
+
+// DK, DV: head widths (multiples of 64, DK/8 and DV/8 divisible by KW and VW); NREP query heads per KV head.
+// KW / VW: 32-bit words of codes a lane takes per load on the K / V side.
+template <int DK, int DV, int NREP, int KW, int VW>
+__global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodeParams p)
+{
+    constexpr int GK = DK / kGroup, GV = DV / kGroup;
+    constexpr int KLPT = DK / (8 * KW);      // lanes sharing one token's K row
+    constexpr int KTPS = kWave / KLPT;       // tokens per K load step
+    constexpr int KSTEPS = kWave / KTPS;     // == KLPT
+    constexpr int KLPG = kGroup / (8 * KW);  // lanes per 64-wide group (>= 1)
+    constexpr int VLPT = DV / (8 * VW);
+    constexpr int VTPS = kWave / VLPT;
+    constexpr int VSTEPS = kWave / VTPS;
+    constexpr int VLPG = kGroup / (8 * VW);
+    static_assert(KLPT <= kWave && VLPT <= kWave && KLPG >= 1 && VLPG >= 1, "lane layout");
+
+    // per wave: K partial dots [NREP][64][KLPT] and p*scale [NREP][64][GV]
+    constexpr int kPartFloats = NREP * kWave * KLPT;
+    constexpr int kPsFloats = NREP * kWave * GV;
+    constexpr int kWaveFloats = kPartFloats + kPsFloats;
+    constexpr int kFinalFloats = kWaves * NREP * DV + kWaves * NREP * GV + 2 * kWaves * NREP;
+    constexpr int kLdsFloats = (kWaves * kWaveFloats > kFinalFloats ? kWaves * kWaveFloats : kFinalFloats) + NREP * GK;
+    __shared__ float lds[kLdsFloats];
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int split = blockIdx.x;
+    const int kvh = blockIdx.y % p.kv_heads, agent = blockIdx.y / p.kv_heads;
+    const int li = blockIdx.z, layer = p.layer_begin + li;
+
+    int n = p.seq_len[agent];
+    n = n < p.max_seq_len ? n : p.max_seq_len;
+    const int first = (p.window > 0 && n > p.window) ? n - p.window : 0;
+    const int t_begin = split * p.split_tokens;
+    if (t_begin >= n) return; // the combine kernel never looks at splits past the agent's length
+    const int t_end = min(n, t_begin + p.split_tokens);
+
+    const int64_t unit0 = ((int64_t)li * p.num_agents + agent) * p.q_heads + (int64_t)kvh * NREP;
+    if (t_end <= first) { // split lies wholly before the window: an empty partial
+        if (tid < NREP) {
+            float *ml = p.part_ml + ((unit0 + tid) * p.num_splits + split) * 2;
+            ml[0] = kNegBig;
+            ml[1] = 0.0f;
+        }
+        return;
+    }
+
+    float *qsum_lds = lds + (kLdsFloats - NREP * GK); // sum of q over each 64-wide group, [NREP][GK]
+    const uint16_t *qrow = p.q + unit0 * DK;           // NREP consecutive query heads
+    if (tid < NREP * GK) {
+        const uint16_t *src = qrow + (tid / GK) * DK + (tid % GK) * kGroup;
+        float s = 0.0f;
+        for (int d = 0; d < kGroup; ++d) s += half_bits_to_float(src[d]);
+        qsum_lds[tid] = s;
+    }
+
+    // query registers of this lane: its 8*KW dims of every head, paired the way unpack_codes pairs codes
+    const int kj = lane % KLPT, ko = lane / KLPT;
+    half2_t qa[NREP][2 * KW], qb[NREP][2 * KW];
+#pragma unroll
+    for (int r = 0; r < NREP; ++r) {
+        const uint16_t *src = qrow + r * DK + kj * 8 * KW;
+#pragma unroll
+        for (int w = 0; w < KW; ++w) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(src + 8 * w);
+            const uint32_t e01 = raw.x, e23 = raw.y, e45 = raw.z, e67 = raw.w;
+            qa[r][2 * w] = bits_to_half2((e01 & 0xffffu) | (e45 << 16));         // (q0, q4)
+            qb[r][2 * w] = bits_to_half2((e01 >> 16) | (e45 & 0xffff0000u));     // (q1, q5)
+            qa[r][2 * w + 1] = bits_to_half2((e23 & 0xffffu) | (e67 << 16));     // (q2, q6)
+            qb[r][2 * w + 1] = bits_to_half2((e23 >> 16) | (e67 & 0xffff0000u)); // (q3, q7)
+        }
+    }
+    __syncthreads();
+    float qsum[NREP][GK];
+#pragma unroll
+    for (int r = 0; r < NREP; ++r)
+#pragma unroll
+        for (int g = 0; g < GK; ++g) qsum[r][g] = qsum_lds[r * GK + g];
+
+    float *part = lds + wave * kWaveFloats; // [NREP][64][KLPT]
+    float *ps = part + kPartFloats;         // [NREP][64][GV]
+
+    const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / VLPG;
+    float acc[NREP][8 * VW];
+#pragma unroll
+    for (int r = 0; r < NREP; ++r)
+#pragma unroll
+        for (int e = 0; e < 8 * VW; ++e) acc[r][e] = 0.0f;
+    float m_run[NREP], l_run[NREP], pb[NREP][GV]; // l_run, pb: this lane's tokens only
+#pragma unroll
+    for (int r = 0; r < NREP; ++r) {
+        m_run[r] = kNegBig;
+        l_run[r] = 0.0f;
+#pragma unroll
+        for (int g = 0; g < GV; ++g) pb[r][g] = 0.0f;
+    }
+
+    const int32_t *table = p.block_table + (int64_t)agent * p.max_blocks;
+    const int b_begin = t_begin / kBlockTokens, b_end = (t_end + kBlockTokens - 1) / kBlockTokens;
+    for (int bi = b_begin; bi < b_end; ++bi) {
+        const int t0 = bi * kBlockTokens + wave * kWave; // first token of this wave's tile
+        if (t0 >= t_end || t0 + kWave <= first) continue;
+        const int blk = table[bi];
+        if (blk < 0 || blk >= p.num_blocks) continue;
+        const int64_t row0 = (((int64_t)layer * p.num_blocks + blk) * p.kv_heads + kvh) * kBlockTokens + wave * kWave;
+
+        // ---- issue every load of the tile up front
+        Words<KW> kc[KSTEPS];
+#pragma unroll
+        for (int i = 0; i < KSTEPS; ++i) {
+            const int local = i * KTPS + ko, t = t0 + local;
+            kc[i] = load_words<KW>(p.k_codes + (row0 + local) * (DK / 8) + kj * KW, t >= first && t < t_end);
+        }
+        const bool tok_valid = (t0 + lane >= first) && (t0 + lane < t_end);
+        float ks[GK], kb[GK], vs[GV], vb[GV];
+        load_groups<GK>(p.k_scale + (row0 + lane) * GK, tok_valid, ks);
+        load_groups<GK>(p.k_bias + (row0 + lane) * GK, tok_valid, kb);
+        load_groups<GV>(p.v_scale + (row0 + lane) * p.v_row_groups, tok_valid, vs);
+        load_groups<GV>(p.v_bias + (row0 + lane) * p.v_row_groups, tok_valid, vb);
+        Words<VW> vc[VSTEPS];
+#pragma unroll
+        for (int i = 0; i < VSTEPS; ++i) {
+            const int local = i * VTPS + vo, t = t0 + local;
+            vc[i] = load_words<VW>(p.v_codes + (row0 + local) * p.v_row_words + vj * VW, t >= first && t < t_end);
+        }
+
+        // ---- K side: partial q.c over this lane's dims, for each of its tokens
+#pragma unroll
+        for (int i = 0; i < KSTEPS; ++i) {
+            float ra[NREP], rb[NREP];
+#pragma unroll
+            for (int r = 0; r < NREP; ++r) ra[r] = rb[r] = 0.0f;
+#pragma unroll
+            for (int w = 0; w < KW; ++w) {
+                const CodePairs c = unpack_codes(kc[i].w[w]);
+#pragma unroll
+                for (int r = 0; r < NREP; ++r) {
+                    ra[r] = dot2(qa[r][2 * w], c.a0, ra[r]);
+                    rb[r] = dot2(qb[r][2 * w], c.b0, rb[r]);
+                    ra[r] = dot2(qa[r][2 * w + 1], c.a1, ra[r]);
+                    rb[r] = dot2(qb[r][2 * w + 1], c.b1, rb[r]);
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < NREP; ++r)
+                part[(r * kWave + i * KTPS + ko) * KLPT + kj] = fmaf(ra[r], kCodeScaleA, rb[r] * kCodeScaleB);
+        }
+        wave_lds_sync();
+
+        // ---- the lane that owns token `lane`: finish its scores, online softmax, publish p*s
+        float alpha[NREP];
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+            float z = 0.0f;
+#pragma unroll
+            for (int g = 0; g < GK; ++g) {
+                float d = 0.0f;
+#pragma unroll
+                for (int j = 0; j < KLPG; ++j) d += part[(r * kWave + lane) * KLPT + g * KLPG + j];
+                z = fmaf(ks[g], d, z);
+                z = fmaf(kb[g], qsum[r][g], z);
+            }
+            z = tok_valid ? z * p.score_scale : kNegBig;
+            const float m_new = fmaxf(m_run[r], wave_max(z));
+            alpha[r] = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+            m_run[r] = m_new;
+            const float pr = tok_valid ? __builtin_amdgcn_exp2f(z - m_new) : 0.0f;
+            l_run[r] = fmaf(l_run[r], alpha[r], pr);
+#pragma unroll
+            for (int g = 0; g < GV; ++g) {
+                ps[(r * kWave + lane) * GV + g] = pr * vs[g] * kCodeScaleA;
+                pb[r][g] = fmaf(pb[r][g], alpha[r], pr * vb[g]);
+            }
+        }
+        wave_lds_sync();
+
+        // ---- V side: acc[r][e] += (p s)[t] * c[t][e] over this lane's tokens
+#pragma unroll
+        for (int r = 0; r < NREP; ++r)
+            if (alpha[r] != 1.0f) { // wave-uniform
+#pragma unroll
+                for (int e = 0; e < 8 * VW; ++e) acc[r][e] *= alpha[r];
+            }
+#pragma unroll
+        for (int i = 0; i < VSTEPS; ++i) {
+            float pa[NREP], pbv[NREP];
+#pragma unroll
+            for (int r = 0; r < NREP; ++r) {
+                pa[r] = ps[(r * kWave + i * VTPS + vo) * GV + vg];
+                pbv[r] = pa[r] * (kCodeScaleB / kCodeScaleA);
+            }
+#pragma unroll
+            for (int w = 0; w < VW; ++w) {
+                const CodePairs c = unpack_codes(vc[i].w[w]);
+#pragma unroll
+                for (int r = 0; r < NREP; ++r) {
+                    acc[r][8 * w + 0] = fmaf((float)c.a0.x, pa[r], acc[r][8 * w + 0]);
+                    acc[r][8 * w + 4] = fmaf((float)c.a0.y, pa[r], acc[r][8 * w + 4]);
+                    acc[r][8 * w + 1] = fmaf((float)c.b0.x, pbv[r], acc[r][8 * w + 1]);
+                    acc[r][8 * w + 5] = fmaf((float)c.b0.y, pbv[r], acc[r][8 * w + 5]);
+                    acc[r][8 * w + 2] = fmaf((float)c.a1.x, pa[r], acc[r][8 * w + 2]);
+                    acc[r][8 * w + 6] = fmaf((float)c.a1.y, pa[r], acc[r][8 * w + 6]);
+                    acc[r][8 * w + 3] = fmaf((float)c.b1.x, pbv[r], acc[r][8 * w + 3]);
+                    acc[r][8 * w + 7] = fmaf((float)c.b1.y, pbv[r], acc[r][8 * w + 7]);
+                }
+            }
+        }
+        wave_lds_sync(); // the next tile overwrites part / ps
+    }
+
+    // ---- merge the lanes of each wave, then the waves, in a fixed order
+    __syncthreads(); // every wave is done with its part / ps region
+    float *fin_acc = lds;                              // [kWaves][NREP][DV]
+    float *fin_pb = fin_acc + kWaves * NREP * DV;      // [kWaves][NREP][GV]
+    float *fin_m = fin_pb + kWaves * NREP * GV;        // [kWaves][NREP]
+    float *fin_l = fin_m + kWaves * NREP;              // [kWaves][NREP]
+#pragma unroll
+    for (int r = 0; r < NREP; ++r) {
+        // lanes that share dims differ in lane / VLPT: fold them with xor-shuffles over the token-slot bits
+#pragma unroll
+        for (int e = 0; e < 8 * VW; ++e) {
+            float v = acc[r][e];
+#pragma unroll
+            for (int off = VLPT; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+            acc[r][e] = v;
+        }
+        const float lsum = wave_sum(l_run[r]);
+        if (lane < VLPT) {
+#pragma unroll
+            for (int e = 0; e < 8 * VW; ++e) fin_acc[(wave * NREP + r) * DV + vj * 8 * VW + e] = acc[r][e];
+        }
+#pragma unroll
+        for (int g = 0; g < GV; ++g) {
+            const float s = wave_sum(pb[r][g]);
+            if (lane == 0) fin_pb[(wave * NREP + r) * GV + g] = s;
+        }
+        if (lane == 0) {
+            fin_m[wave * NREP + r] = m_run[r];
+            fin_l[wave * NREP + r] = lsum;
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < NREP * DV; idx += kThreads) {
+        const int r = idx / DV, e = idx % DV;
+        float m = kNegBig;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) m = fmaxf(m, fin_m[w * NREP + r]);
+        float o = 0.0f, l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float f = __builtin_amdgcn_exp2f(fin_m[w * NREP + r] - m);
+            o = fmaf(f, fin_acc[(w * NREP + r) * DV + e] + fin_pb[(w * NREP + r) * GV + e / kGroup], o);
+            l = fmaf(f, fin_l[w * NREP + r], l);
+        }
+        const int64_t rec = (unit0 + r) * p.num_splits + split;
+        p.part_acc[rec * DV + e] = o;
+        if (e == 0) {
+            p.part_ml[rec * 2] = m;
+            p.part_ml[rec * 2 + 1] = l;
+        }
+    }
+}
+
+// Merge the split partials of one (layer, agent, query head): fixed order, binary32, output binary16.
+__global__ __launch_bounds__(kWave) void combine_kernel(const float *__restrict__ part_acc,
+                                                        const float *__restrict__ part_ml,
+                                                        const int32_t *__restrict__ seq_len, uint16_t *__restrict__ out,
+                                                        int q_heads, int num_agents, int v_dim, int num_splits,
+                                                        int split_tokens, int max_seq_len)
+{
+    const int64_t unit = blockIdx.x;
+    const int agent = (int)((unit / q_heads) % num_agents);
+    int n = seq_len[agent];
+    n = n < max_seq_len ? n : max_seq_len;
+    const int live = n > 0 ? (n + split_tokens - 1) / split_tokens : 0;
+    const float *ml = part_ml + unit * num_splits * 2;
+    float m = kNegBig;
+    for (int s = 0; s < live; ++s)
+        if (ml[2 * s + 1] > 0.0f) m = fmaxf(m, ml[2 * s]);
+    float denom = 0.0f;
+    for (int s = 0; s < live; ++s)
+        if (ml[2 * s + 1] > 0.0f) denom = fmaf(__builtin_amdgcn_exp2f(ml[2 * s] - m), ml[2 * s + 1], denom);
+    const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
+    for (int e = threadIdx.x; e < v_dim; e += kWave) {
+        float o = 0.0f;
+        for (int s = 0; s < live; ++s)
+            if (ml[2 * s + 1] > 0.0f) o = fmaf(__builtin_amdgcn_exp2f(ml[2 * s] - m), part_acc[(unit * num_splits + s) * v_dim + e], o);
+        out[unit * v_dim + e] = float_to_half_bits(o * inv);
+    }
+}
+
+template <int DK, int DV, int NREP>
+hipError_t launch_decode_t(const AttentionArgs &a, hipStream_t stream)
+{
+    DecodeParams p;
+    p.k_codes = a.k.codes; p.k_scale = a.k.scale; p.k_bias = a.k.bias;
+    p.v_codes = a.v.codes; p.v_scale = a.v.scale; p.v_bias = a.v.bias;
+    p.q = a.q; p.block_table = a.block_table; p.seq_len = a.seq_len;
+    p.part_acc = a.part_acc; p.part_ml = a.part_ml;
+    p.num_blocks = a.k.num_blocks; p.kv_heads = a.spec.num_kv_heads; p.q_heads = a.spec.num_q_heads;
+    p.num_agents = a.num_agents; p.max_blocks = a.max_blocks; p.max_seq_len = a.max_seq_len;
+    p.window = a.window; p.split_tokens = a.split_tokens; p.num_splits = a.num_splits;
+    p.layer_begin = a.layer_begin;
+    const int v_row_dim = a.spec.v_aliases_k ? a.spec.k_dim : a.spec.v_dim;
+    p.v_row_words = v_row_dim / 8; p.v_row_groups = v_row_dim / kGroup;
+    p.score_scale = a.sm_scale * kLog2e;
+    dim3 grid(a.num_splits, a.num_agents * a.spec.num_kv_heads, a.layers_in_call);
+    constexpr int KW = 4;
+    constexpr int VW = NREP >= 4 ? 2 : 4; // keeps the NREP * 8 * VW accumulators in registers
+    hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, KW, VW>), grid, dim3(kThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+template <int DK, int DV>
+hipError_t launch_decode_d(const AttentionArgs &a, int n_rep, hipStream_t stream)
+{
+    switch (n_rep) {
+    case 1: return launch_decode_t<DK, DV, 1>(a, stream);
+    case 2: return launch_decode_t<DK, DV, 2>(a, stream);
+    case 4: return launch_decode_t<DK, DV, 4>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+} // namespace
+
+bool decode_supported(const q4kv_spec &s)
+{
+    const int n_rep = s.num_q_heads / s.num_kv_heads;
+    const bool rep_ok = n_rep == 1 || n_rep == 2 || n_rep == 4;
+    const bool dims_ok = (s.k_dim == 64 || s.k_dim == 128 || s.k_dim == 256) && s.v_dim == s.k_dim && !s.v_aliases_k;
+    return rep_ok && dims_ok;
+}
+
+hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
+{
+    const int n_rep = a.spec.num_q_heads / a.spec.num_kv_heads;
+    switch (a.spec.k_dim) {
+    case 64: return launch_decode_d<64, 64>(a, n_rep, stream);
+    case 128: return launch_decode_d<128, 128>(a, n_rep, stream);
+    case 256: return launch_decode_d<256, 256>(a, n_rep, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream)
+{
+    const int64_t units = (int64_t)a.layers_in_call * a.num_agents * a.q_len * a.spec.num_q_heads;
+    if (units == 0) return hipSuccess;
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)units), dim3(kWave), 0, stream, a.part_acc, a.part_ml, a.seq_len,
+                       a.out, a.spec.num_q_heads, a.num_agents, a.spec.v_dim, a.num_splits, a.split_tokens,
+                       a.max_seq_len);
+    return hipGetLastError();
+}
+
+} // namespace q4kv

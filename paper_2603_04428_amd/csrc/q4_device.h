@@ -1,0 +1,75 @@
+// Device-side helpers shared by the gfx950 kernels of libq4kv: binary16 access,
+// nibble unpacking into packed binary16 pairs, wave-level reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace q4kv {
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kGroup = 64;        // elements per quantization group (Sec. 3.2: g = 64)
+constexpr int kBlockTokens = 256; // tokens per cache block (Sec. 3.1)
+constexpr int kWave = 64;         // CDNA wavefront width
+
+__device__ __forceinline__ half2_t bits_to_half2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+__device__ __forceinline__ uint32_t half2_to_bits(half2_t h) { return __builtin_bit_cast(uint32_t, h); }
+__device__ __forceinline__ float half_bits_to_float(uint16_t b) { return (float)__builtin_bit_cast(half_t, b); }
+__device__ __forceinline__ uint16_t float_to_half_bits(float f)
+{
+    return __builtin_bit_cast(uint16_t, (half_t)f); // v_cvt_f16_f32, round to nearest even
+}
+
+// Eight 4-bit codes of one word as four packed binary16 pairs.  A code c placed in the low
+// mantissa bits of a binary16 with zero exponent is the subnormal c * 2^-24 (bits 0..3) or
+// c * 2^-20 (bits 4..7), so no integer-to-float conversion is needed:
+//   a0 = (c0, c4) * 2^-24   b0 = (c1, c5) * 2^-20   a1 = (c2, c6) * 2^-24   b1 = (c3, c7) * 2^-20
+// The consumers multiply by kCodeScaleA / kCodeScaleB afterwards (in binary32, exact).
+struct CodePairs {
+    half2_t a0, b0, a1, b1;
+};
+constexpr float kCodeScaleA = 16777216.0f; // 2^24
+constexpr float kCodeScaleB = 1048576.0f;  // 2^20
+
+__device__ __forceinline__ CodePairs unpack_codes(uint32_t w)
+{
+    CodePairs p;
+    const uint32_t w8 = w >> 8;
+    p.a0 = bits_to_half2(w & 0x000F000Fu);
+    p.b0 = bits_to_half2(w & 0x00F000F0u);
+    p.a1 = bits_to_half2(w8 & 0x000F000Fu);
+    p.b1 = bits_to_half2(w8 & 0x00F000F0u);
+    return p;
+}
+
+// acc + a.x*b.x + a.y*b.y with a binary32 accumulator (v_dot2_f32_f16)
+__device__ __forceinline__ float dot2(half2_t a, half2_t b, float acc)
+{
+    return __builtin_amdgcn_fdot2(a, b, acc, false);
+}
+
+// Orders LDS traffic between the lanes of one wavefront: what lanes wrote before is visible to
+// every lane after.  Waves of a workgroup that do not share LDS regions need nothing stronger.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+} // namespace q4kv

@@ -1,0 +1,38 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel files.
+// Every function only enqueues kernels on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/q4kv.h"
+
+namespace q4kv {
+
+hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, uint32_t *codes, uint16_t *scale,
+                           uint16_t *bias, hipStream_t stream);
+hipError_t launch_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
+                             int dim, uint16_t *x, hipStream_t stream);
+hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &pool, int dim, const uint16_t *x_new,
+                         const int32_t *block_table, int max_blocks, const int32_t *seq_len_before, int num_agents,
+                         int chunk_len, int layer_begin, int layer_end, hipStream_t stream);
+
+struct AttentionArgs {
+    q4kv_spec spec;
+    q4kv_pool k, v;             // v == k when the V rows alias the K rows
+    const uint16_t *q;
+    uint16_t *out;
+    const int32_t *block_table;
+    const int32_t *seq_len;
+    int max_blocks, num_agents, q_len, max_seq_len, window, split_tokens, num_splits;
+    int layer_begin, layers_in_call;
+    float sm_scale;
+    float *part_acc;            // workspace: [units][num_splits][v_dim]
+    float *part_ml;             // workspace: [units][num_splits][2]  (running max in log2 units, denominator)
+};
+
+// true when a decode (q_len == 1) kernel exists for these head shapes
+bool decode_supported(const q4kv_spec &spec);
+hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);
+hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream);
+
+} // namespace q4kv

@@ -1,0 +1,162 @@
+"""GPU parity of q4kv_quantize / q4kv_dequantize / q4kv_append with the CPU oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_04428_amd import binding as b
+from paper_2603_04428_amd import synth
+from tests.gpu_util import DEV, bits
+
+pytestmark = pytest.mark.gpu
+F16 = np.float16
+
+
+def check_quantize(x_np):
+    x = torch.from_numpy(x_np).to(DEV)
+    codes, scale, bias = b.q4kv_quantize(x)
+    oc, os_, ob = oracle.quantize(x_np)
+    assert np.array_equal(bits(scale), os_), "scale bits"
+    assert np.array_equal(bits(bias), ob), "bias bits"
+    assert np.array_equal(bits(codes), oc), "codes"
+    # and back
+    xh = b.q4kv_dequantize(codes, scale, bias)
+    assert np.array_equal(bits(xh), oracle.dequantize(oc, os_, ob).view(np.uint16)), "dequantized"
+
+
+@pytest.mark.parametrize("dim", [64, 128, 256, 576])
+def test_quantize_random_rows_bit_exact(dim):
+    rng = np.random.default_rng(dim)
+    # several workgroups (32 groups each) and a ragged tail
+    check_quantize(rng.standard_normal((1000 + 7, dim)).astype(F16))
+    x = rng.standard_normal((333, dim))
+    x[:, ::11] *= 8
+    check_quantize(x.astype(F16))
+
+
+def test_quantize_special_groups_bit_exact():
+    rng = np.random.default_rng(0)
+    rows = []
+    ramp = np.tile(np.arange(16), 4).astype(np.float64)
+    rows.append(ramp)                                             # scale 1, codes = values
+    rows.append(np.full(64, 3.25))                                # constant group
+    z = np.zeros(64); z[3] = 7 * 2.0 ** -24; rows.append(z)       # scale rounds to zero
+    z = np.zeros(64); z[3] = 8 * 2.0 ** -24; rows.append(z)       # smallest non-zero stored scale
+    t = np.zeros(64); t[1] = 15; t[2:10] = [0.5, 1.5, 2.5, 3.5, 13.5, 14.5, 7.5, 8.5]; rows.append(t)   # ties
+    nz = np.zeros(64); nz[0] = -0.0; nz[1] = 1.0; rows.append(nz)  # -0 is the first minimum
+    pz = np.zeros(64); pz[5] = -0.0; pz[9] = 2.0; rows.append(pz)  # +0 first, -0 later
+    x = np.stack(rows).astype(F16)
+    check_quantize(x)
+    check_quantize((rng.standard_normal((200, 64)) * 3e-6).astype(F16))          # subnormal inputs
+    check_quantize((rng.standard_normal((200, 128)) * 1e-3).astype(F16))
+    check_quantize(rng.uniform(-60000, 60000, (200, 64)).astype(F16))            # near the binary16 limit
+    k = rng.integers(0, 15, (300, 64)) + 0.5                                     # values on code boundaries
+    k[:, 0], k[:, 1] = 0, 15
+    check_quantize(k.astype(F16))
+    check_quantize((k * 0.37 - 2.0).astype(F16))
+    # every binary16 magnitude pattern appears somewhere (finite only)
+    allbits = np.arange(0, 0x7C00, dtype=np.uint16)
+    allbits = np.concatenate([allbits, allbits | 0x8000])
+    rng.shuffle(allbits)
+    check_quantize(allbits[: (len(allbits) // 64) * 64].view(F16).reshape(-1, 64))
+
+
+def test_empty_input():
+    x = torch.empty((0, 128), dtype=torch.float16, device=DEV)
+    codes, scale, bias = b.q4kv_quantize(x)
+    assert codes.shape == (0, 16) and scale.shape == (0, 2)
+    assert b.q4kv_dequantize(codes, scale, bias).shape == (0, 128)
+
+
+def test_dequantize_arbitrary_codes_bit_exact():
+    rng = np.random.default_rng(5)
+    codes = rng.integers(0, 2 ** 32, (777, 32), dtype=np.uint64).astype(np.uint32)
+    scale = (rng.standard_normal((777, 4)) * 0.3).astype(F16)
+    bias = (rng.standard_normal((777, 4)) * 2).astype(F16)
+    scale[5] = 0
+    scale[6] = np.array(2.0 ** -24, F16)
+    bias[7] = 60000
+    got = b.q4kv_dequantize(torch.from_numpy(codes.view(np.int32)).to(DEV),
+                            torch.from_numpy(scale.view(np.int16)).to(DEV),
+                            torch.from_numpy(bias.view(np.int16)).to(DEV))
+    assert np.array_equal(bits(got), oracle.dequantize(codes, scale, bias).view(np.uint16))
+
+
+@pytest.mark.parametrize("alias", [False, True])
+def test_append_bit_exact_and_touches_nothing_else(alias):
+    if alias:
+        w = synth.small(21, 2, 4, 1, 576, 512, True, (250, 7, 600), 1)
+    else:
+        w = synth.small(21, 3, 4, 2, 128, 64, False, (250, 7, 600), 1)
+    A, Cn = 3, 300                                                 # chunks cross block boundaries
+    lens = np.array(w.seq_lens, np.int32)
+    need = (lens + Cn + 255) // 256
+    mb = int(need.max())
+    rng = np.random.default_rng(3)
+    nb = int(need.sum()) + 2
+    perm = rng.permutation(nb - 2)
+    table = np.zeros((A, mb), np.int32)
+    pos = 0
+    for a in range(A):
+        table[a, :need[a]] = perm[pos:pos + need[a]]
+        pos += need[a]
+    gspec = b.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, alias)
+    ospec = oracle.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, alias)
+    gk = b.Pool(gspec, w.k_dim, nb, DEV, poison=True)
+    gv = None if alias else b.Pool(gspec, w.v_dim, nb, DEV, poison=True)
+    ok = oracle.Pool(ospec, w.k_dim, nb, fill=0x7E00)
+    ov = None if alias else oracle.Pool(ospec, w.v_dim, nb, fill=0x7E00)
+    L0, L1 = (0, 2) if alias else (1, 3)
+    k_new = torch.stack([torch.stack([w.k_rows(l, a, 1000, 1000 + Cn) for a in range(A)]) for l in range(L0, L1)])
+    v_new = None if alias else torch.stack([torch.stack([w.v_rows(l, a, 1000, 1000 + Cn) for a in range(A)])
+                                            for l in range(L0, L1)])
+    oracle.append(ospec, ok, ov, k_new.numpy(), None if alias else v_new.numpy(), table, lens, L0, L1)
+    b.q4kv_append(gspec, gk, gv, k_new.to(DEV), None if alias else v_new.to(DEV), torch.from_numpy(table).to(DEV),
+                  torch.from_numpy(lens).to(DEV), L0, L1)
+    for gp, op in ((gk, ok), (gv, ov)):
+        if gp is None:
+            continue
+        assert np.array_equal(bits(gp.codes), op.codes)
+        assert np.array_equal(bits(gp.scale), op.scale)
+        assert np.array_equal(bits(gp.bias), op.bias)
+
+
+def test_append_skips_tokens_outside_the_table_or_pool():
+    w = synth.small(22, 1, 2, 2, 64, 64, False, (250,), 1)
+    spec = b.make_spec(1, 2, 2, 64)
+    k = b.Pool(spec, 64, 2, DEV, poison=True)
+    v = b.Pool(spec, 64, 2, DEV, poison=True)
+    before = bits(k.codes).copy()
+    k_new = w.k_rows(0, 0, 0, 20, DEV)[None, None].contiguous()
+    table = torch.tensor([[0, 7]], dtype=torch.int32, device=DEV)       # second block id is outside the pool
+    b.q4kv_append(spec, k, v, k_new, k_new, table, torch.tensor([250], dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+    after = bits(k.codes)
+    assert not np.array_equal(after[0, 0, :, 250:256], before[0, 0, :, 250:256])    # slots 250..255 written
+    assert np.array_equal(after[0, 1], before[0, 1])                                 # nothing else
+
+
+def test_full_size_cache_quantize_sampled_rows():
+    """One fresh 4,096-token Gemma-shaped agent cache (the size the benchmark times): K and V of 48 layers,
+    8 heads, 256 wide.  Quantized layer by layer on the GPU; seeded sample rows are regenerated on the host
+    and checked bit-exact against the oracle, then the round trip through q4kv_dequantize likewise."""
+    w = synth.Workload("gemma_one_agent_4k", 2, 48, 16, 8, 256, 256, False, [4096])
+    rng = np.random.default_rng(7)
+    for l in (0, 17, 47):
+        for tensor, rows_fn in (("k", w.k_rows), ("v", w.v_rows)):
+            x = rows_fn(l, 0, 0, 4096, DEV)                      # [4096][8][256]
+            codes, scale, bias = b.q4kv_quantize(x)
+            xh = b.q4kv_dequantize(codes, scale, bias)
+            toks = sorted(set([0, 4095] + rng.integers(0, 4096, 24).tolist()))
+            for t in toks:
+                ref = rows_fn(l, 0, t, t + 1).numpy()            # regenerated on the host
+                oc, os_, ob = oracle.quantize(ref)
+                assert np.array_equal(bits(codes[t:t + 1]), oc)
+                assert np.array_equal(bits(scale[t:t + 1]), os_)
+                assert np.array_equal(bits(bias[t:t + 1]), ob)
+                assert np.array_equal(bits(xh[t:t + 1]), oracle.dequantize(oc, os_, ob).view(np.uint16))
+            # property that holds at any size: every reconstruction within scale/2 of its input
+            s = torch.from_numpy(bits(scale).view(F16).astype(np.float32)).to(DEV).repeat_interleave(64, dim=-1)
+            err = (xh.float() - x.float()).abs()
+            ulp = torch.ldexp(torch.ones_like(err), torch.frexp(xh.float().abs().clamp_min(2.0 ** -14))[1] - 12)
+            assert bool((err <= s / 2 * 1.001 + ulp).all())
