@@ -20,12 +20,17 @@
 //  * K side: KLPT lanes share a token (each holds 16 bytes = 32 dims of its row), their partial dot
 //    products meet in LDS where the lane owning the token applies scale/bias and does the softmax
 //    bookkeeping; V side: each lane owns 8*VW output dims and walks tokens, reading p*s from LDS.
+#include <type_traits>
+
 #include "q4_device.h"
 #include "q4kv_internal.h"
 
 namespace q4kv {
 namespace {
 
+#ifndef Q4KV_DEC_WAVES_PER_EU
+#define Q4KV_DEC_WAVES_PER_EU 2 // resident waves per SIMD the register budget is sized for
+#endif
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr float kNegBig = -1.0e30f; // "minus infinity" that survives subtraction
@@ -44,26 +49,20 @@ struct DecodeParams {
 };
 
 template <int N>
-struct GroupVec { // N binary16 values = one token's scales or biases
-    uint16_t v[N];
-};
-
-template <int N>
-__device__ __forceinline__ void load_groups(const uint16_t *p, bool valid, float (&out)[N])
+__device__ __forceinline__ void load_groups(const uint16_t *p, float (&out)[N])
 {
-    // N is 1, 2 or 4: one 2-, 4- or 8-byte load
+    // N is 1, 2 or a multiple of 4: 2-, 4- or 8-byte loads
     if constexpr (N == 1) {
-        uint16_t r = valid ? *p : (uint16_t)0;
-        out[0] = half_bits_to_float(r);
+        out[0] = half_bits_to_float(*p);
     } else if constexpr (N == 2) {
-        uint32_t r = valid ? *reinterpret_cast<const uint32_t *>(p) : 0u;
+        const uint32_t r = *reinterpret_cast<const uint32_t *>(p);
         out[0] = half_bits_to_float((uint16_t)(r & 0xffffu));
         out[1] = half_bits_to_float((uint16_t)(r >> 16));
     } else {
         static_assert(N % 4 == 0, "group count");
 #pragma unroll
         for (int i = 0; i < N / 4; ++i) {
-            uint2 r = valid ? reinterpret_cast<const uint2 *>(p)[i] : make_uint2(0u, 0u);
+            const uint2 r = reinterpret_cast<const uint2 *>(p)[i];
             out[4 * i + 0] = half_bits_to_float((uint16_t)(r.x & 0xffffu));
             out[4 * i + 1] = half_bits_to_float((uint16_t)(r.x >> 16));
             out[4 * i + 2] = half_bits_to_float((uint16_t)(r.y & 0xffffu));
@@ -78,25 +77,29 @@ struct Words {
 };
 
 template <int W>
-__device__ __forceinline__ Words<W> load_words(const uint32_t *p, bool valid)
+__device__ __forceinline__ Words<W> load_words(const uint32_t *p)
 {
     Words<W> r;
     if constexpr (W == 4) {
-        uint4 t = valid ? *reinterpret_cast<const uint4 *>(p) : make_uint4(0u, 0u, 0u, 0u);
+        const uint4 t = *reinterpret_cast<const uint4 *>(p);
         r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
     } else if constexpr (W == 2) {
-        uint2 t = valid ? *reinterpret_cast<const uint2 *>(p) : make_uint2(0u, 0u);
+        const uint2 t = *reinterpret_cast<const uint2 *>(p);
         r.w[0] = t.x; r.w[1] = t.y;
     } else {
-        r.w[0] = valid ? *p : 0u;
+        r.w[0] = *p;
     }
     return r;
 }
 
 // DK, DV: head widths (multiples of 64, DK/8 and DV/8 divisible by KW and VW); NREP query heads per KV head.
 // KW / VW: 32-bit words of codes a lane takes per load on the K / V side.
+//
+// Loads are never predicated: a tile's 64 rows always exist inside its block, so rows past the agent's
+// length are read and then ignored (their score is forced to "minus infinity", their p*s to zero; codes
+// are nibbles and cannot produce a NaN, scale/bias of such rows are replaced by zero after the load).
 template <int DK, int DV, int NREP, int KW, int VW>
-__global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodeParams p)
+__global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attention_kernel(DecodeParams p)
 {
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
     constexpr int KLPT = DK / (8 * KW);      // lanes sharing one token's K row
@@ -107,17 +110,19 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodePar
     constexpr int VTPS = kWave / VLPT;
     constexpr int VSTEPS = kWave / VTPS;
     constexpr int VLPG = kGroup / (8 * VW);
-    static_assert(KLPT <= kWave && VLPT <= kWave && KLPG >= 1 && VLPG >= 1, "lane layout");
+    static_assert(KLPT <= kWave && VLPT <= kWave && KLPG >= 1 && VLPG >= 1 && VSTEPS % 2 == 0, "lane layout");
 
-    // per wave: K partial dots [NREP][64][KLPT] and p*scale [NREP][64][GV]
+    // per wave: K partial dots [NREP][64][KLPT] (binary32) and p*scale [NREP][GV][64] (binary16, tokens of
+    // consecutive V load steps interleaved so that a pair sits in one 32-bit word)
     constexpr int kPartFloats = NREP * kWave * KLPT;
-    constexpr int kPsFloats = NREP * kWave * GV;
+    constexpr int kPsFloats = NREP * GV * kWave / 2;
     constexpr int kWaveFloats = kPartFloats + kPsFloats;
     constexpr int kFinalFloats = kWaves * NREP * DV + kWaves * NREP * GV + 2 * kWaves * NREP;
     constexpr int kLdsFloats = (kWaves * kWaveFloats > kFinalFloats ? kWaves * kWaveFloats : kFinalFloats) + NREP * GK;
     __shared__ float lds[kLdsFloats];
 
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave); // wave-uniform, so tile addresses stay scalar
     const int split = blockIdx.x;
     const int kvh = blockIdx.y % p.kv_heads, agent = blockIdx.y / p.kv_heads;
     const int li = blockIdx.z, layer = p.layer_begin + li;
@@ -171,11 +176,14 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodePar
 #pragma unroll
         for (int g = 0; g < GK; ++g) qsum[r][g] = qsum_lds[r * GK + g];
 
-    float *part = lds + wave * kWaveFloats; // [NREP][64][KLPT]
-    float *ps = part + kPartFloats;         // [NREP][64][GV]
+    float *part = lds + wave * kWaveFloats;                               // [NREP][64][KLPT]
+    uint16_t *ps_h = reinterpret_cast<uint16_t *>(part + kPartFloats);     // [NREP][GV][64] binary16
+    const uint32_t *ps_w = reinterpret_cast<const uint32_t *>(ps_h);      // the same as token pairs
 
     const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / VLPG;
-    float acc[NREP][8 * VW];
+    // where the token owned by this lane (local index `lane` = step*VTPS + slot) goes in ps_h
+    const int ps_slot = 2 * VTPS * ((lane / VTPS) / 2) + 2 * (lane % VTPS) + ((lane / VTPS) & 1);
+    float acc[NREP][8 * VW]; // odd dims carry an extra factor 16 until the end (their codes sit 4 bits higher)
 #pragma unroll
     for (int r = 0; r < NREP; ++r)
 #pragma unroll
@@ -190,34 +198,48 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodePar
     }
 
     const int32_t *table = p.block_table + (int64_t)agent * p.max_blocks;
-    const int b_begin = t_begin / kBlockTokens, b_end = (t_end + kBlockTokens - 1) / kBlockTokens;
-    for (int bi = b_begin; bi < b_end; ++bi) {
-        const int t0 = bi * kBlockTokens + wave * kWave; // first token of this wave's tile
-        if (t0 >= t_end || t0 + kWave <= first) continue;
-        const int blk = table[bi];
-        if (blk < 0 || blk >= p.num_blocks) continue;
-        const int64_t row0 = (((int64_t)layer * p.num_blocks + blk) * p.kv_heads + kvh) * kBlockTokens + wave * kWave;
-
-        // ---- issue every load of the tile up front
-        Words<KW> kc[KSTEPS];
-#pragma unroll
-        for (int i = 0; i < KSTEPS; ++i) {
-            const int local = i * KTPS + ko, t = t0 + local;
-            kc[i] = load_words<KW>(p.k_codes + (row0 + local) * (DK / 8) + kj * KW, t >= first && t < t_end);
+    const int b_end = (t_end + kBlockTokens - 1) / kBlockTokens;
+    // next block index >= bi whose 64-token tile of this wave holds visible tokens of a valid block
+    auto next_tile = [&](int bi, int64_t &row0) {
+        for (; bi < b_end; ++bi) {
+            const int t0 = bi * kBlockTokens + wave * kWave;
+            if (t0 >= t_end || t0 + kWave <= first) continue;
+            const int blk = table[bi];
+            if (blk < 0 || blk >= p.num_blocks) continue;
+            row0 = (((int64_t)layer * p.num_blocks + blk) * p.kv_heads + kvh) * kBlockTokens + wave * kWave;
+            return bi;
         }
-        const bool tok_valid = (t0 + lane >= first) && (t0 + lane < t_end);
-        float ks[GK], kb[GK], vs[GV], vb[GV];
-        load_groups<GK>(p.k_scale + (row0 + lane) * GK, tok_valid, ks);
-        load_groups<GK>(p.k_bias + (row0 + lane) * GK, tok_valid, kb);
-        load_groups<GV>(p.v_scale + (row0 + lane) * p.v_row_groups, tok_valid, vs);
-        load_groups<GV>(p.v_bias + (row0 + lane) * p.v_row_groups, tok_valid, vb);
-        Words<VW> vc[VSTEPS];
-#pragma unroll
-        for (int i = 0; i < VSTEPS; ++i) {
-            const int local = i * VTPS + vo, t = t0 + local;
-            vc[i] = load_words<VW>(p.v_codes + (row0 + local) * p.v_row_words + vj * VW, t >= first && t < t_end);
-        }
+        return b_end;
+    };
 
+    Words<KW> kc[KSTEPS];
+    Words<VW> vc[VSTEPS];
+    float ks[GK], kb[GK], vs[GV], vb[GV];
+    // tile base (uniform, from row0) + a fixed per-lane offset + a compile-time step offset
+    const int k_lane_off = ko * (DK / 8) + kj * KW;
+    const int v_lane_off = vo * p.v_row_words + vj * VW;
+    auto load_k = [&](int64_t row0) {
+        const uint32_t *tile = p.k_codes + row0 * (DK / 8);
+#pragma unroll
+        for (int i = 0; i < KSTEPS; ++i) kc[i] = load_words<KW>(tile + k_lane_off + i * KTPS * (DK / 8));
+    };
+    auto load_v = [&](int64_t row0) {
+        const uint32_t *tile = p.v_codes + row0 * p.v_row_words;
+#pragma unroll
+        for (int i = 0; i < VSTEPS; ++i) vc[i] = load_words<VW>(tile + v_lane_off + i * VTPS * p.v_row_words);
+    };
+    auto load_params = [&](int64_t row0) {
+        load_groups<GK>(p.k_scale + row0 * GK + lane * GK, ks);
+        load_groups<GK>(p.k_bias + row0 * GK + lane * GK, kb);
+        load_groups<GV>(p.v_scale + row0 * p.v_row_groups + lane * p.v_row_groups, vs);
+        load_groups<GV>(p.v_bias + row0 * p.v_row_groups + lane * p.v_row_groups, vb);
+    };
+
+    // One 64-token tile.  PREFETCH is a compile-time flag: every tile but the last of a wave issues the next
+    // tile's loads unconditionally (K codes once the K side is done, the rest after the V side), so the code
+    // buffers are plain loop-carried registers and loads are always in flight while the ALUs work.
+    auto tile = [&](const int t0, const int64_t row0_next, auto prefetch) {
+        constexpr bool PREFETCH = decltype(prefetch)::value;
         // ---- K side: partial q.c over this lane's dims, for each of its tokens
 #pragma unroll
         for (int i = 0; i < KSTEPS; ++i) {
@@ -239,9 +261,11 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodePar
             for (int r = 0; r < NREP; ++r)
                 part[(r * kWave + i * KTPS + ko) * KLPT + kj] = fmaf(ra[r], kCodeScaleA, rb[r] * kCodeScaleB);
         }
+        if constexpr (PREFETCH) load_k(row0_next); // the next tile's K codes travel while this tile finishes
         wave_lds_sync();
 
         // ---- the lane that owns token `lane`: finish its scores, online softmax, publish p*s
+        const bool tok_valid = (t0 + lane >= first) && (t0 + lane < t_end);
         float alpha[NREP];
 #pragma unroll
         for (int r = 0; r < NREP; ++r) {
@@ -262,13 +286,13 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodePar
             l_run[r] = fmaf(l_run[r], alpha[r], pr);
 #pragma unroll
             for (int g = 0; g < GV; ++g) {
-                ps[(r * kWave + lane) * GV + g] = pr * vs[g] * kCodeScaleA;
-                pb[r][g] = fmaf(pb[r][g], alpha[r], pr * vb[g]);
+                ps_h[(r * GV + g) * kWave + ps_slot] = float_to_half_bits(tok_valid ? pr * vs[g] : 0.0f);
+                pb[r][g] = fmaf(pb[r][g], alpha[r], tok_valid ? pr * vb[g] : 0.0f);
             }
         }
         wave_lds_sync();
 
-        // ---- V side: acc[r][e] += (p s)[t] * c[t][e] over this lane's tokens
+        // ---- V side: acc[r][e] += (p s)[t] * c[t][e], two tokens per v_dot2_f32_f16
 #pragma unroll
         for (int r = 0; r < NREP; ++r)
             if (alpha[r] != 1.0f) { // wave-uniform
@@ -276,30 +300,46 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodePar
                 for (int e = 0; e < 8 * VW; ++e) acc[r][e] *= alpha[r];
             }
 #pragma unroll
-        for (int i = 0; i < VSTEPS; ++i) {
-            float pa[NREP], pbv[NREP];
+        for (int i = 0; i < VSTEPS; i += 2) {
+            half2_t pp[NREP];
 #pragma unroll
-            for (int r = 0; r < NREP; ++r) {
-                pa[r] = ps[(r * kWave + i * VTPS + vo) * GV + vg];
-                pbv[r] = pa[r] * (kCodeScaleB / kCodeScaleA);
-            }
+            for (int r = 0; r < NREP; ++r) pp[r] = bits_to_half2(ps_w[(r * GV + vg) * (kWave / 2) + VTPS * (i / 2) + vo]);
 #pragma unroll
             for (int w = 0; w < VW; ++w) {
-                const CodePairs c = unpack_codes(vc[i].w[w]);
 #pragma unroll
-                for (int r = 0; r < NREP; ++r) {
-                    acc[r][8 * w + 0] = fmaf((float)c.a0.x, pa[r], acc[r][8 * w + 0]);
-                    acc[r][8 * w + 4] = fmaf((float)c.a0.y, pa[r], acc[r][8 * w + 4]);
-                    acc[r][8 * w + 1] = fmaf((float)c.b0.x, pbv[r], acc[r][8 * w + 1]);
-                    acc[r][8 * w + 5] = fmaf((float)c.b0.y, pbv[r], acc[r][8 * w + 5]);
-                    acc[r][8 * w + 2] = fmaf((float)c.a1.x, pa[r], acc[r][8 * w + 2]);
-                    acc[r][8 * w + 6] = fmaf((float)c.a1.y, pa[r], acc[r][8 * w + 6]);
-                    acc[r][8 * w + 3] = fmaf((float)c.b1.x, pbv[r], acc[r][8 * w + 3]);
-                    acc[r][8 * w + 7] = fmaf((float)c.b1.y, pbv[r], acc[r][8 * w + 7]);
+                for (int by = 0; by < 4; ++by) {
+                    // byte `by` of both tokens' words: codes 2*by (low nibble) and 2*by+1 (high nibble)
+                    const uint32_t pair = __builtin_amdgcn_perm(vc[i + 1].w[w], vc[i].w[w], 0x0C040C00u + by * 0x00010001u);
+                    const half2_t lo = bits_to_half2(pair & 0x000F000Fu);
+                    const half2_t hi = bits_to_half2(pair & 0x00F000F0u);
+#pragma unroll
+                    for (int r = 0; r < NREP; ++r) {
+                        acc[r][8 * w + 2 * by] = dot2(lo, pp[r], acc[r][8 * w + 2 * by]);
+                        acc[r][8 * w + 2 * by + 1] = dot2(hi, pp[r], acc[r][8 * w + 2 * by + 1]);
+                    }
                 }
             }
         }
+        if constexpr (PREFETCH) {
+            load_params(row0_next);
+            load_v(row0_next);
+        }
         wave_lds_sync(); // the next tile overwrites part / ps
+    };
+
+    int64_t row0 = 0, row0_next = 0;
+    int bi = next_tile(t_begin / kBlockTokens, row0);
+    if (bi < b_end) {
+        load_k(row0);
+        load_params(row0);
+        load_v(row0);
+        for (;;) {
+            const int bn = next_tile(bi + 1, row0_next);
+            if (bn >= b_end) break;
+            tile(bi * kBlockTokens + wave * kWave, row0_next, std::true_type{});
+            bi = bn;
+        }
+        tile(bi * kBlockTokens + wave * kWave, 0, std::false_type{});
     }
 
     // ---- merge the lanes of each wave, then the waves, in a fixed order
@@ -316,7 +356,7 @@ __global__ __launch_bounds__(kThreads, 2) void decode_attention_kernel(DecodePar
             float v = acc[r][e];
 #pragma unroll
             for (int off = VLPT; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
-            acc[r][e] = v;
+            acc[r][e] = v * ((e & 1) ? kCodeScaleB : kCodeScaleA);
         }
         const float lsum = wave_sum(l_run[r]);
         if (lane < VLPT) {
@@ -399,8 +439,14 @@ hipError_t launch_decode_t(const AttentionArgs &a, hipStream_t stream)
     p.v_row_words = v_row_dim / 8; p.v_row_groups = v_row_dim / kGroup;
     p.score_scale = a.sm_scale * kLog2e;
     dim3 grid(a.num_splits, a.num_agents * a.spec.num_kv_heads, a.layers_in_call);
-    constexpr int KW = 4;
-    constexpr int VW = NREP >= 4 ? 2 : 4; // keeps the NREP * 8 * VW accumulators in registers
+#ifndef Q4KV_DEC_KW
+#define Q4KV_DEC_KW 4
+#endif
+#ifndef Q4KV_DEC_VW
+#define Q4KV_DEC_VW (NREP >= 4 ? 1 : 2) // keeps the NREP * 8 * VW accumulators and both code buffers in registers
+#endif
+    constexpr int KW = Q4KV_DEC_KW;
+    constexpr int VW = (DV / 16 < (Q4KV_DEC_VW)) ? DV / 16 : (Q4KV_DEC_VW);
     hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, KW, VW>), grid, dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
