@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--skip-cpu-baseline", action="store_true", help="for profiler runs: leave the oracle leg out")
+    ap.add_argument("--split-tokens", type=int, default=0, help="tokens per split-K work item (0: library default)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (agents would shard across GPUs with no exchange step); "
@@ -72,7 +73,7 @@ def main():
     q = w.q_all(dev)
     seq = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
     max_len = max(w.seq_lens)
-    split = b.q4kv_default_split_tokens(spec, w.num_agents, 1, max_len, w.num_layers)
+    split = args.split_tokens or b.q4kv_default_split_tokens(spec, w.num_agents, 1, max_len, w.num_layers)
     ws = torch.empty(b.q4kv_attention_workspace_bytes(spec, w.num_agents, 1, max_len, split, w.num_layers),
                      dtype=torch.uint8, device=dev)
     out = torch.empty((w.num_layers, w.num_agents, 1, w.num_q_heads, w.v_dim), dtype=torch.float16, device=dev)

@@ -12,14 +12,21 @@
 //  * inside a workgroup each of the 4 waves walks its own 64-token tiles (slots 64w..64w+63 of every
 //    256-token block) with private online-softmax state; waves meet only once, at the end.
 //  * codes never become integers or binary32: a nibble masked in place is a binary16 subnormal
-//    (c*2^-24 or c*2^-20), fed straight to v_dot2_f32_f16 (K side) or v_fma_mix (V side).
+//    (c*2^-24 or c*2^-20) and goes straight into the matrix core (K side) or v_dot2_f32_f16 (V side).
 //  * the affine part of the dequantization is factored out of the inner loops:
 //        q . K_hat[t]   = sum_g  s[t,g] * (q_g . c[t,g])  +  b[t,g] * sum(q_g)
 //        sum_t p_t V_hat[t,e] = sum_t (p_t s[t,g(e)]) c[t,e]  +  sum_t p_t b[t,g(e)]
 //    so scale and bias are touched once per (token, group), by the lane that owns the token.
-//  * K side: KLPT lanes share a token (each holds 16 bytes = 32 dims of its row), their partial dot
-//    products meet in LDS where the lane owning the token applies scale/bias and does the softmax
-//    bookkeeping; V side: each lane owns 8*VW output dims and walks tokens, reading p*s from LDS.
+//  * K side: q_g . c[t,g] is a contraction over head_dim with the codes laid out exactly as the matrix
+//    core wants its K-index (8 consecutive dims per 32-bit word), so it runs as v_mfma_f32_16x16x32_f16:
+//    16 tokens are the N columns, the rows are (query head, group-in-chunk) pairs, and the cross-lane
+//    sum over head_dim -- the expensive part on the vector ALUs -- comes for free.  A lane loads 16 bytes
+//    (4 words) of one token row; the four lanes that share a token cover a 64-byte chunk = two groups,
+//    and the query operand is zeroed outside a row's own group so that one instruction yields both
+//    groups' partial dot products separately.
+//  * V side: the contraction runs over tokens while a word holds 8 dims of one token, so the matrix
+//    core's operand shape does not fit; each lane owns 8*VW output dims, pairs the codes of two tokens
+//    with v_perm and multiplies them with the binary16 pair (p s)[t], (p s)[t'] in one v_dot2_f32_f16.
 #include <type_traits>
 
 #include "q4_device.h"
@@ -48,27 +55,38 @@ struct DecodeParams {
     float score_scale;             // sm_scale * log2(e): scores are kept in log2 units
 };
 
+// One token's scales or biases (N binary16 values, N = 1, 2 or a multiple of 4) as raw bits: loaded with one
+// 2-, 4- or 8-byte load per 4 values and converted only where they are used, so that issuing the load never
+// makes the wave wait for it.
 template <int N>
-__device__ __forceinline__ void load_groups(const uint16_t *p, float (&out)[N])
+struct GroupBits {
+    uint32_t w[(N + 1) / 2];
+};
+
+template <int N>
+__device__ __forceinline__ GroupBits<N> load_groups(const uint16_t *p)
 {
-    // N is 1, 2 or a multiple of 4: 2-, 4- or 8-byte loads
+    GroupBits<N> r;
     if constexpr (N == 1) {
-        out[0] = half_bits_to_float(*p);
+        r.w[0] = *p;
     } else if constexpr (N == 2) {
-        const uint32_t r = *reinterpret_cast<const uint32_t *>(p);
-        out[0] = half_bits_to_float((uint16_t)(r & 0xffffu));
-        out[1] = half_bits_to_float((uint16_t)(r >> 16));
+        r.w[0] = *reinterpret_cast<const uint32_t *>(p);
     } else {
         static_assert(N % 4 == 0, "group count");
 #pragma unroll
         for (int i = 0; i < N / 4; ++i) {
-            const uint2 r = reinterpret_cast<const uint2 *>(p)[i];
-            out[4 * i + 0] = half_bits_to_float((uint16_t)(r.x & 0xffffu));
-            out[4 * i + 1] = half_bits_to_float((uint16_t)(r.x >> 16));
-            out[4 * i + 2] = half_bits_to_float((uint16_t)(r.y & 0xffffu));
-            out[4 * i + 3] = half_bits_to_float((uint16_t)(r.y >> 16));
+            const uint2 t = reinterpret_cast<const uint2 *>(p)[i];
+            r.w[2 * i] = t.x;
+            r.w[2 * i + 1] = t.y;
         }
     }
+    return r;
+}
+
+template <int N>
+__device__ __forceinline__ float group_value(const GroupBits<N> &b, int g)
+{
+    return half_bits_to_float((uint16_t)((g & 1) ? (b.w[g / 2] >> 16) : (b.w[g / 2] & 0xffffu)));
 }
 
 template <int W>
@@ -102,22 +120,25 @@ template <int DK, int DV, int NREP, int KW, int VW>
 __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attention_kernel(DecodeParams p)
 {
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
-    constexpr int KLPT = DK / (8 * KW);      // lanes sharing one token's K row
-    constexpr int KTPS = kWave / KLPT;       // tokens per K load step
-    constexpr int KSTEPS = kWave / KTPS;     // == KLPT
-    constexpr int KLPG = kGroup / (8 * KW);  // lanes per 64-wide group (>= 1)
+    // K side (matrix core): lane = (token j = lane % 16 of a 16-token set, k-block kb = lane / 16)
+    constexpr int KWPL = DK >= 128 ? 4 : 2;        // words a lane loads per chunk (16 or 8 bytes)
+    constexpr int KCHUNKS = DK / (32 * KWPL);      // chunks per row: 4 lanes * KWPL words each
+    constexpr int KGPC = KWPL == 4 ? 2 : 1;        // quantization groups per chunk
+    constexpr int KSETS = kWave / 16;              // 16-token sets per tile
+    constexpr int KROWS = NREP * KGPC;             // distinct rows of the query operand
+    static_assert(KW == 4 && KROWS <= 16 && KCHUNKS * KGPC == GK, "K layout");
     constexpr int VLPT = DV / (8 * VW);
     constexpr int VTPS = kWave / VLPT;
     constexpr int VSTEPS = kWave / VTPS;
     constexpr int VLPG = kGroup / (8 * VW);
-    static_assert(KLPT <= kWave && VLPT <= kWave && KLPG >= 1 && VLPG >= 1 && VSTEPS % 2 == 0, "lane layout");
+    static_assert(VLPT <= kWave && VLPG >= 1 && VSTEPS % 2 == 0, "lane layout");
 
-    // per wave: K partial dots [NREP][64][KLPT] (binary32) and p*scale [NREP][GV][64] (binary16, tokens of
-    // consecutive V load steps interleaved so that a pair sits in one 32-bit word)
-    constexpr int kPartFloats = NREP * kWave * KLPT;
+    // per wave: q.c per token, group and head [64][GK][NREP] (binary32) and p*scale [NREP][GV][64] (binary16,
+    // tokens of consecutive V load steps interleaved so that a pair sits in one 32-bit word)
+    constexpr int kPartFloats = kWave * GK * NREP;
     constexpr int kPsFloats = NREP * GV * kWave / 2;
     constexpr int kWaveFloats = kPartFloats + kPsFloats;
-    constexpr int kFinalFloats = kWaves * NREP * DV + kWaves * NREP * GV + 2 * kWaves * NREP;
+    constexpr int kFinalFloats = kWaves * VTPS * NREP * DV + kWaves * NREP * GV + 2 * kWaves * NREP;
     constexpr int kLdsFloats = (kWaves * kWaveFloats > kFinalFloats ? kWaves * kWaveFloats : kFinalFloats) + NREP * GK;
     __shared__ float lds[kLdsFloats];
 
@@ -146,28 +167,39 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 
     float *qsum_lds = lds + (kLdsFloats - NREP * GK); // sum of q over each 64-wide group, [NREP][GK]
     const uint16_t *qrow = p.q + unit0 * DK;           // NREP consecutive query heads
-    if (tid < NREP * GK) {
-        const uint16_t *src = qrow + (tid / GK) * DK + (tid % GK) * kGroup;
-        float s = 0.0f;
-        for (int d = 0; d < kGroup; ++d) s += half_bits_to_float(src[d]);
-        qsum_lds[tid] = s;
+    if (tid < NREP * GK * 8) { // eight lanes per 64-wide group, 8 dims each, folded inside the octet
+        const uint4 raw = *reinterpret_cast<const uint4 *>(qrow + tid * 8);
+        const half2_t a = bits_to_half2(raw.x), b = bits_to_half2(raw.y), c = bits_to_half2(raw.z), d = bits_to_half2(raw.w);
+        float s = ((float)a.x + (float)a.y) + ((float)b.x + (float)b.y) + ((float)c.x + (float)c.y) + ((float)d.x + (float)d.y);
+        s += Q4KV_DPP(0.0f, s, 0xB1, 0xF);  // quad_perm [1,0,3,2]
+        s += Q4KV_DPP(0.0f, s, 0x4E, 0xF);  // quad_perm [2,3,0,1]
+        s += Q4KV_DPP(0.0f, s, 0x141, 0xF); // row_half_mirror
+        if ((tid & 7) == 0) qsum_lds[tid >> 3] = s;
     }
 
-    // query registers of this lane: its 8*KW dims of every head, paired the way unpack_codes pairs codes
-    const int kj = lane % KLPT, ko = lane / KLPT;
-    half2_t qa[NREP][2 * KW], qb[NREP][2 * KW];
+    // Query operand of the matrix core, one per (chunk, word): row i = lane % 16 stands for query head
+    // i % NREP and group-in-chunk (i / NREP) % KGPC; the lane holds the 8 dims of its k-block in the order
+    // unpack_codes emits codes (0,4,1,5,2,6,3,7), odd dims divided by 16 because their codes arrive 16 times
+    // larger, and zeros when its k-block belongs to the row's other group.
+    const int kj = lane % 16, kkb = lane / 16;
+    half8_t qop[KCHUNKS][KWPL];
+    {
+        const int r = kj % NREP, u = (kj / NREP) % KGPC;
+        const bool mine = (KGPC == 1) || (u == kkb / 2);
 #pragma unroll
-    for (int r = 0; r < NREP; ++r) {
-        const uint16_t *src = qrow + r * DK + kj * 8 * KW;
+        for (int c = 0; c < KCHUNKS; ++c)
 #pragma unroll
-        for (int w = 0; w < KW; ++w) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(src + 8 * w);
-            const uint32_t e01 = raw.x, e23 = raw.y, e45 = raw.z, e67 = raw.w;
-            qa[r][2 * w] = bits_to_half2((e01 & 0xffffu) | (e45 << 16));         // (q0, q4)
-            qb[r][2 * w] = bits_to_half2((e01 >> 16) | (e45 & 0xffff0000u));     // (q1, q5)
-            qa[r][2 * w + 1] = bits_to_half2((e23 & 0xffffu) | (e67 << 16));     // (q2, q6)
-            qb[r][2 * w + 1] = bits_to_half2((e23 >> 16) | (e67 & 0xffff0000u)); // (q3, q7)
-        }
+            for (int w = 0; w < KWPL; ++w) {
+                const uint16_t *src = qrow + r * DK + c * (32 * KWPL) + kkb * (8 * KWPL) + 8 * w;
+                const uint4 raw = *reinterpret_cast<const uint4 *>(src);
+                const half2_t e01 = bits_to_half2(raw.x), e23 = bits_to_half2(raw.y);
+                const half2_t e45 = bits_to_half2(raw.z), e67 = bits_to_half2(raw.w);
+                const half_t sixteenth = (half_t)0.0625f;
+                half8_t v = {e01.x, e45.x, e01.y * sixteenth, e45.y * sixteenth,
+                             e23.x, e67.x, e23.y * sixteenth, e67.y * sixteenth};
+                if (!mine) v = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                qop[c][w] = v;
+            }
     }
     __syncthreads();
     float qsum[NREP][GK];
@@ -176,7 +208,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 #pragma unroll
         for (int g = 0; g < GK; ++g) qsum[r][g] = qsum_lds[r * GK + g];
 
-    float *part = lds + wave * kWaveFloats;                               // [NREP][64][KLPT]
+    float *part = lds + wave * kWaveFloats;                               // [64][GK][NREP]
     uint16_t *ps_h = reinterpret_cast<uint16_t *>(part + kPartFloats);     // [NREP][GV][64] binary16
     const uint32_t *ps_w = reinterpret_cast<const uint32_t *>(ps_h);      // the same as token pairs
 
@@ -212,16 +244,20 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         return b_end;
     };
 
-    Words<KW> kc[KSTEPS];
+    Words<KWPL> kc[KSETS][KCHUNKS];
     Words<VW> vc[VSTEPS];
-    float ks[GK], kb[GK], vs[GV], vb[GV];
+    GroupBits<GK> ks_bits, kb_bits;
+    GroupBits<GV> vs_bits, vb_bits;
     // tile base (uniform, from row0) + a fixed per-lane offset + a compile-time step offset
-    const int k_lane_off = ko * (DK / 8) + kj * KW;
+    const int k_lane_off = kj * (DK / 8) + kkb * KWPL;
     const int v_lane_off = vo * p.v_row_words + vj * VW;
     auto load_k = [&](int64_t row0) {
         const uint32_t *tile = p.k_codes + row0 * (DK / 8);
 #pragma unroll
-        for (int i = 0; i < KSTEPS; ++i) kc[i] = load_words<KW>(tile + k_lane_off + i * KTPS * (DK / 8));
+        for (int ts = 0; ts < KSETS; ++ts)
+#pragma unroll
+            for (int c = 0; c < KCHUNKS; ++c)
+                kc[ts][c] = load_words<KWPL>(tile + k_lane_off + ts * 16 * (DK / 8) + c * 4 * KWPL);
     };
     auto load_v = [&](int64_t row0) {
         const uint32_t *tile = p.v_codes + row0 * p.v_row_words;
@@ -229,10 +265,10 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         for (int i = 0; i < VSTEPS; ++i) vc[i] = load_words<VW>(tile + v_lane_off + i * VTPS * p.v_row_words);
     };
     auto load_params = [&](int64_t row0) {
-        load_groups<GK>(p.k_scale + row0 * GK + lane * GK, ks);
-        load_groups<GK>(p.k_bias + row0 * GK + lane * GK, kb);
-        load_groups<GV>(p.v_scale + row0 * p.v_row_groups + lane * p.v_row_groups, vs);
-        load_groups<GV>(p.v_bias + row0 * p.v_row_groups + lane * p.v_row_groups, vb);
+        ks_bits = load_groups<GK>(p.k_scale + row0 * GK + lane * GK);
+        kb_bits = load_groups<GK>(p.k_bias + row0 * GK + lane * GK);
+        vs_bits = load_groups<GV>(p.v_scale + row0 * p.v_row_groups + lane * p.v_row_groups);
+        vb_bits = load_groups<GV>(p.v_bias + row0 * p.v_row_groups + lane * p.v_row_groups);
     };
 
     // One 64-token tile.  PREFETCH is a compile-time flag: every tile but the last of a wave issues the next
@@ -240,42 +276,62 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     // buffers are plain loop-carried registers and loads are always in flight while the ALUs work.
     auto tile = [&](const int t0, const int64_t row0_next, auto prefetch) {
         constexpr bool PREFETCH = decltype(prefetch)::value;
-        // ---- K side: partial q.c over this lane's dims, for each of its tokens
+        // ---- K side: q.c per (token, head, group) on the matrix core, results to LDS in token order
+        {
+            float4_t d[KSETS][KCHUNKS];
 #pragma unroll
-        for (int i = 0; i < KSTEPS; ++i) {
-            float ra[NREP], rb[NREP];
+            for (int ts = 0; ts < KSETS; ++ts)
 #pragma unroll
-            for (int r = 0; r < NREP; ++r) ra[r] = rb[r] = 0.0f;
+                for (int c = 0; c < KCHUNKS; ++c) d[ts][c] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int w = 0; w < KW; ++w) {
-                const CodePairs c = unpack_codes(kc[i].w[w]);
+            for (int w = 0; w < KWPL; ++w)
 #pragma unroll
-                for (int r = 0; r < NREP; ++r) {
-                    ra[r] = dot2(qa[r][2 * w], c.a0, ra[r]);
-                    rb[r] = dot2(qb[r][2 * w], c.b0, rb[r]);
-                    ra[r] = dot2(qa[r][2 * w + 1], c.a1, ra[r]);
-                    rb[r] = dot2(qb[r][2 * w + 1], c.b1, rb[r]);
-                }
+                for (int ts = 0; ts < KSETS; ++ts)
+#pragma unroll
+                    for (int c = 0; c < KCHUNKS; ++c) {
+                        const CodePairs cp = unpack_codes(kc[ts][c].w[w]);
+                        const uint4 packed = make_uint4(half2_to_bits(cp.a0), half2_to_bits(cp.b0),
+                                                        half2_to_bits(cp.a1), half2_to_bits(cp.b1));
+                        d[ts][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[c][w], __builtin_bit_cast(half8_t, packed),
+                                                                          d[ts][c], 0, 0, 0);
+                    }
+            // result row i = 4*(lane/16) + reg belongs to (head i % NREP, group-in-chunk i / NREP); rows past
+            // KROWS are repeats.  part[token][group][head] keeps a lane's registers contiguous.
+            constexpr int kRegs = KROWS < 4 ? KROWS : 4;
+            if (4 * kkb < KROWS) {
+#pragma unroll
+                for (int ts = 0; ts < KSETS; ++ts)
+#pragma unroll
+                    for (int c = 0; c < KCHUNKS; ++c) {
+                        float *dst = part + ((ts * 16 + kj) * GK + c * KGPC) * NREP + 4 * kkb;
+#pragma unroll
+                        for (int e = 0; e < kRegs; ++e) dst[e] = d[ts][c][e];
+                    }
             }
-#pragma unroll
-            for (int r = 0; r < NREP; ++r)
-                part[(r * kWave + i * KTPS + ko) * KLPT + kj] = fmaf(ra[r], kCodeScaleA, rb[r] * kCodeScaleB);
         }
         if constexpr (PREFETCH) load_k(row0_next); // the next tile's K codes travel while this tile finishes
         wave_lds_sync();
 
         // ---- the lane that owns token `lane`: finish its scores, online softmax, publish p*s
         const bool tok_valid = (t0 + lane >= first) && (t0 + lane < t_end);
+        float ks[GK], kb[GK], vs[GV], vb[GV];
+#pragma unroll
+        for (int g = 0; g < GK; ++g) {
+            ks[g] = group_value<GK>(ks_bits, g) * kCodeScaleA;
+            kb[g] = group_value<GK>(kb_bits, g);
+        }
+#pragma unroll
+        for (int g = 0; g < GV; ++g) {
+            vs[g] = group_value<GV>(vs_bits, g);
+            vb[g] = group_value<GV>(vb_bits, g);
+        }
         float alpha[NREP];
 #pragma unroll
         for (int r = 0; r < NREP; ++r) {
             float z = 0.0f;
 #pragma unroll
             for (int g = 0; g < GK; ++g) {
-                float d = 0.0f;
-#pragma unroll
-                for (int j = 0; j < KLPG; ++j) d += part[(r * kWave + lane) * KLPT + g * KLPG + j];
-                z = fmaf(ks[g], d, z);
+                z = fmaf(ks[g], part[(lane * GK + g) * NREP + r], z);
                 z = fmaf(kb[g], qsum[r][g], z);
             }
             z = tok_valid ? z * p.score_scale : kNegBig;
@@ -330,9 +386,13 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     int64_t row0 = 0, row0_next = 0;
     int bi = next_tile(t_begin / kBlockTokens, row0);
     if (bi < b_end) {
+        // same issue order as inside the loop (K codes first), pinned so that the wait for the K codes
+        // never covers the loads issued after them
         load_k(row0);
+        __builtin_amdgcn_sched_barrier(0);
         load_params(row0);
         load_v(row0);
+        __builtin_amdgcn_sched_barrier(0);
         for (;;) {
             const int bn = next_tile(bi + 1, row0_next);
             if (bn >= b_end) break;
@@ -342,27 +402,18 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         tile(bi * kBlockTokens + wave * kWave, 0, std::false_type{});
     }
 
-    // ---- merge the lanes of each wave, then the waves, in a fixed order
+    // ---- merge token slots, lanes and waves in a fixed order, through LDS
     __syncthreads(); // every wave is done with its part / ps region
-    float *fin_acc = lds;                              // [kWaves][NREP][DV]
-    float *fin_pb = fin_acc + kWaves * NREP * DV;      // [kWaves][NREP][GV]
-    float *fin_m = fin_pb + kWaves * NREP * GV;        // [kWaves][NREP]
-    float *fin_l = fin_m + kWaves * NREP;              // [kWaves][NREP]
+    float *fin_acc = lds;                                   // [kWaves][VTPS][NREP][DV]
+    float *fin_pb = fin_acc + kWaves * VTPS * NREP * DV;    // [kWaves][NREP][GV]
+    float *fin_m = fin_pb + kWaves * NREP * GV;             // [kWaves][NREP]
+    float *fin_l = fin_m + kWaves * NREP;                   // [kWaves][NREP]
 #pragma unroll
     for (int r = 0; r < NREP; ++r) {
-        // lanes that share dims differ in lane / VLPT: fold them with xor-shuffles over the token-slot bits
+        float *dst = fin_acc + ((wave * VTPS + vo) * NREP + r) * DV + vj * 8 * VW;
 #pragma unroll
-        for (int e = 0; e < 8 * VW; ++e) {
-            float v = acc[r][e];
-#pragma unroll
-            for (int off = VLPT; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
-            acc[r][e] = v * ((e & 1) ? kCodeScaleB : kCodeScaleA);
-        }
+        for (int e = 0; e < 8 * VW; ++e) dst[e] = acc[r][e] * ((e & 1) ? kCodeScaleB : kCodeScaleA);
         const float lsum = wave_sum(l_run[r]);
-        if (lane < VLPT) {
-#pragma unroll
-            for (int e = 0; e < 8 * VW; ++e) fin_acc[(wave * NREP + r) * DV + vj * 8 * VW + e] = acc[r][e];
-        }
 #pragma unroll
         for (int g = 0; g < GV; ++g) {
             const float s = wave_sum(pb[r][g]);
@@ -383,7 +434,10 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
             const float f = __builtin_amdgcn_exp2f(fin_m[w * NREP + r] - m);
-            o = fmaf(f, fin_acc[(w * NREP + r) * DV + e] + fin_pb[(w * NREP + r) * GV + e / kGroup], o);
+            float a = fin_pb[(w * NREP + r) * GV + e / kGroup];
+#pragma unroll
+            for (int sl = 0; sl < VTPS; ++sl) a += fin_acc[((w * VTPS + sl) * NREP + r) * DV + e];
+            o = fmaf(f, a, o);
             l = fmaf(f, fin_l[w * NREP + r], l);
         }
         const int64_t rec = (unit0 + r) * p.num_splits + split;

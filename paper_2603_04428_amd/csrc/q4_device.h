@@ -8,6 +8,8 @@ namespace q4kv {
 
 typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kGroup = 64;        // elements per quantization group (Sec. 3.2: g = 64)
 constexpr int kBlockTokens = 256; // tokens per cache block (Sec. 3.1)
@@ -58,18 +60,33 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Wave-wide reductions on the vector ALU's data-parallel-primitive lanes (no LDS round trips):
+// four steps inside each row of 16 lanes, two row broadcasts, result read from lane 63.
+#define Q4KV_DPP(old, src, ctrl, row_mask)                                                                   \
+    __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, (float)(old)),                \
+                                                          __builtin_bit_cast(int, (float)(src)), (ctrl), (row_mask), \
+                                                          0xF, false))
+
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+    v = fmaxf(v, Q4KV_DPP(v, v, 0xB1, 0xF));  // quad_perm [1,0,3,2]
+    v = fmaxf(v, Q4KV_DPP(v, v, 0x4E, 0xF));  // quad_perm [2,3,0,1]
+    v = fmaxf(v, Q4KV_DPP(v, v, 0x141, 0xF)); // row_half_mirror
+    v = fmaxf(v, Q4KV_DPP(v, v, 0x140, 0xF)); // row_mirror
+    v = fmaxf(v, Q4KV_DPP(v, v, 0x142, 0xA)); // row_bcast15 into rows 1 and 3
+    v = fmaxf(v, Q4KV_DPP(v, v, 0x143, 0xC)); // row_bcast31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    v += Q4KV_DPP(0.0f, v, 0xB1, 0xF);
+    v += Q4KV_DPP(0.0f, v, 0x4E, 0xF);
+    v += Q4KV_DPP(0.0f, v, 0x141, 0xF);
+    v += Q4KV_DPP(0.0f, v, 0x140, 0xF);
+    v += Q4KV_DPP(0.0f, v, 0x142, 0xA);
+    v += Q4KV_DPP(0.0f, v, 0x143, 0xC);
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 } // namespace q4kv
