@@ -112,8 +112,10 @@ int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, c
  *                clamped to it on the device.  max_seq_len > max_blocks*256 -> Q4KV_ERANGE.
  *   window       <= 0: global attention.  > 0: row at position p also requires t > p - window
  *                (sliding-window layers, Sec. 3.6).
- *   split_tokens tokens per split-K work item (multiple of 256), 0 = library picks; must equal the
- *                value given to q4kv_attention_workspace_bytes.
+ *   split_tokens smallest token range handed to one wavefront (multiple of 256), 0 = library picks.  The
+ *                tokens of all (layer, KV head, agent) units are dealt out evenly over a fixed set of
+ *                wavefronts; this is the floor of a wavefront's share and bounds the partial results kept
+ *                per query head.  Must equal the value given to q4kv_attention_workspace_bytes.
  *   workspace    device scratch of at least q4kv_attention_workspace_bytes(...) bytes, 16-byte aligned;
  *                contents before and after the call are unspecified.
  * Block ids outside [0, num_blocks) are skipped on the device (their tokens count as masked).

@@ -49,18 +49,41 @@ int check_pool(const q4kv_pool *p, const char *name)
 
 int round_up(int x, int m) { return (x + m - 1) / m * m; }
 
-// Split size when the caller leaves the choice to the library: enough work items to give every
-// CU several workgroups, but no smaller than one block.
+// Compute units of the current device (cached per device); the attention launch is two workgroups per unit.
+int compute_units()
+{
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+int attention_workgroups() { return 2 * compute_units(); }
+
+// Smallest token range a wave takes when the caller leaves the choice to the library: about half of an even
+// share of the largest possible job, between one block and 4,096 tokens.
 int pick_split_tokens(const q4kv_spec &s, int num_agents, int max_seq_len, int layers)
 {
-    const int64_t units = (int64_t)layers * num_agents * s.num_kv_heads;
-    const int64_t want_items = 256 * 2 * 16; // CUs * resident workgroups * rounds
-    int64_t splits_per_unit = units > 0 ? (want_items + units - 1) / units : 1;
-    if (splits_per_unit < 1) splits_per_unit = 1;
-    int64_t tokens = (max_seq_len + splits_per_unit - 1) / splits_per_unit;
-    if (tokens < 256) tokens = 256;
-    return round_up((int)tokens, 256);
+    const long long tiles = (long long)layers * s.num_kv_heads * num_agents * ((max_seq_len + 63) / 64);
+    const long long waves = (long long)attention_workgroups() * q4kv::decode_waves_per_workgroup();
+    long long blocks = tiles / waves / 2 / 4; // in 256-token blocks
+    if (blocks < 1) blocks = 1;
+    if (blocks > 16) blocks = 16;
+    return (int)blocks * 256;
 }
+
+int slots_per_unit(int max_seq_len, int split_tokens)
+{
+    const int tiles = (max_seq_len + 63) / 64, min_per_wave = split_tokens / 64;
+    return (tiles + min_per_wave - 1) / min_per_wave + 1;
+}
+
+size_t plan_bytes(int num_agents) { return (q4kv::decode_plan_ints(num_agents) * sizeof(int32_t) + 255) / 256 * 256; }
 
 } // namespace
 
@@ -157,9 +180,9 @@ size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents,
         return 0;
     }
     const int st = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
-    const int64_t splits = max_seq_len > 0 ? (max_seq_len + st - 1) / st : 1;
+    const int64_t slots = slots_per_unit(max_seq_len, st);
     const int64_t units = (int64_t)num_layers_in_call * num_agents * q_len * spec->num_q_heads;
-    return (size_t)(units * splits * (spec->v_dim + 2) * (int64_t)sizeof(float));
+    return plan_bytes(num_agents) + (size_t)(units * slots * (spec->v_dim + 2) * (int64_t)sizeof(float));
 }
 
 int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
@@ -205,7 +228,8 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     a.max_seq_len = max_seq_len;
     a.window = window;
     a.split_tokens = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, layers);
-    a.num_splits = max_seq_len > 0 ? (max_seq_len + a.split_tokens - 1) / a.split_tokens : 1;
+    a.max_slots = slots_per_unit(max_seq_len, a.split_tokens);
+    a.grid_workgroups = attention_workgroups();
     a.layer_begin = layer_begin;
     a.layers_in_call = layers;
     a.sm_scale = sm_scale;
@@ -219,8 +243,9 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     if (!workspace || workspace_bytes < need || !aligned16(workspace))
         return fail(Q4KV_EWORKSPACE, "workspace needs %zu bytes (16-byte aligned), got %zu", need, workspace_bytes);
     const int64_t units = (int64_t)layers * num_agents * q_len * spec->num_q_heads;
-    a.part_acc = static_cast<float *>(workspace);
-    a.part_ml = a.part_acc + units * a.num_splits * spec->v_dim;
+    a.plan = static_cast<int32_t *>(workspace);
+    a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents));
+    a.part_ml = a.part_acc + units * a.max_slots * spec->v_dim;
 
     hipStream_t st = (hipStream_t)hip_stream;
     hipError_t e = q4kv::launch_decode_attention(a, st);

@@ -4,16 +4,22 @@
 //
 // The step is a single pass over the cache and is HBM-bound: per cached token and KV head it reads
 // DK/2 + DV/2 bytes of codes and 4 bytes of scale/bias per 64-wide group, once, for all n_rep
-// query heads of the group.  The design follows from keeping the vector ALUs under that stream:
+// query heads of the group.  The design follows from keeping everything else under that stream:
 //
-//  * split-K: a workgroup owns (layer, agent, KV head, split of `split_tokens` tokens) and emits an
-//    un-normalised partial (acc[DV], running max m, denominator l) per query head; a small combine
-//    kernel merges the splits in a fixed order, so results are run-to-run identical.
-//  * inside a workgroup each of the 4 waves walks its own 64-token tiles (slots 64w..64w+63 of every
-//    256-token block) with private online-softmax state; waves meet only once, at the end.
-//  * codes never become integers or binary32: a nibble masked in place is a binary16 subnormal
+//  * Work decomposition ("stream-K" over tokens).  All (layer, KV head, agent) units are cut into
+//    64-token tiles and numbered consecutively; the launch is a fixed set of waves (two workgroups
+//    per compute unit) and wave g owns the contiguous tile range [g*per, (g+1)*per).  Ragged context
+//    lengths therefore balance to within one tile, a wave's range usually lies inside one or two
+//    units, and every (unit, wave) intersection emits one un-normalised partial (acc[DV], running
+//    max m, denominator l) per query head.  A small plan kernel turns seq_len[] into the tile
+//    prefix sums first; a combine kernel merges each unit's partials in a fixed order afterwards, so
+//    results are run-to-run identical.
+//  * Waves never synchronise with each other: each walks its tiles with private online-softmax state
+//    and private LDS, and the next tile's loads (also across a unit boundary) are issued while the
+//    current tile is processed, so loads are always in flight.
+//  * Codes never become integers or binary32: a nibble masked in place is a binary16 subnormal
 //    (c*2^-24 or c*2^-20) and goes straight into the matrix core (K side) or v_dot2_f32_f16 (V side).
-//  * the affine part of the dequantization is factored out of the inner loops:
+//  * The affine part of the dequantization is factored out of the inner loops:
 //        q . K_hat[t]   = sum_g  s[t,g] * (q_g . c[t,g])  +  b[t,g] * sum(q_g)
 //        sum_t p_t V_hat[t,e] = sum_t (p_t s[t,g(e)]) c[t,e]  +  sum_t p_t b[t,g(e)]
 //    so scale and bias are touched once per (token, group), by the lane that owns the token.
@@ -27,8 +33,6 @@
 //  * V side: the contraction runs over tokens while a word holds 8 dims of one token, so the matrix
 //    core's operand shape does not fit; each lane owns 8*VW output dims, pairs the codes of two tokens
 //    with v_perm and multiplies them with the binary16 pair (p s)[t], (p s)[t'] in one v_dot2_f32_f16.
-#include <type_traits>
-
 #include "q4_device.h"
 #include "q4kv_internal.h"
 
@@ -43,17 +47,77 @@ constexpr int kWaves = kThreads / kWave;
 constexpr float kNegBig = -1.0e30f; // "minus infinity" that survives subtraction
 constexpr float kLog2e = 1.4426950408889634f;
 
+// Plan written by plan_kernel into the workspace (int32):
+//   [0] TT = tiles of all agents of one (layer, KV head)   [1] per = tiles per wave   [2] N = total tiles
+//   [4 .. 4+A]        tpre[a]   tile prefix sum over agents (tpre[A] == TT)
+//   [.. +A]           tstart[a] first visible token rounded down to a tile boundary
+//   [.. +A]           nlen[a]   seq_len clamped to [0, max_seq_len]
+constexpr int kPlanHeader = 4;
+
 struct DecodeParams {
     const uint32_t *k_codes, *v_codes;
     const uint16_t *k_scale, *k_bias, *v_scale, *v_bias;
     const uint16_t *q;
-    const int32_t *block_table, *seq_len;
+    const int32_t *block_table;
+    const int32_t *plan;
     float *part_acc, *part_ml;
-    int num_blocks, kv_heads, q_heads, num_agents, max_blocks, max_seq_len, window, split_tokens, num_splits;
+    int num_blocks, kv_heads, q_heads, num_agents, max_blocks, window, max_slots;
     int layer_begin;
     int v_row_words, v_row_groups; // row pitch of the V pool in words / groups (K's pitch when V aliases K)
     float score_scale;             // sm_scale * log2(e): scores are kept in log2 units
 };
+
+// ---------------------------------------------------------------------------------------------- plan
+
+// One workgroup.  units_per_agent = layers_in_call * kv_heads; total_waves = waves of the attention launch.
+__global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restrict__ seq_len, int num_agents,
+                                                        int max_seq_len, int window, int units_per_agent,
+                                                        int total_waves, int min_tiles_per_wave,
+                                                        int32_t *__restrict__ plan)
+{
+    __shared__ int chunk_sum[kThreads];
+    const int tid = threadIdx.x;
+    int32_t *tpre = plan + kPlanHeader, *tstart = tpre + num_agents + 1, *nlen = tstart + num_agents;
+    const int per_thread = (num_agents + kThreads - 1) / kThreads;
+    const int a0 = tid * per_thread, a1 = min(num_agents, a0 + per_thread);
+    int local = 0;
+    for (int a = a0; a < a1; ++a) {
+        int n = seq_len[a];
+        n = n < 0 ? 0 : (n > max_seq_len ? max_seq_len : n);
+        const int first = (window > 0 && n > window) ? n - window : 0;
+        const int start = first & ~(kWave - 1);
+        nlen[a] = n;
+        tstart[a] = start;
+        local += n > 0 ? (n - start + kWave - 1) / kWave : 0;
+    }
+    chunk_sum[tid] = local;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int i = 0; i < kThreads; ++i) {
+            const int c = chunk_sum[i];
+            chunk_sum[i] = run;
+            run += c;
+        }
+        const long long total = (long long)run * units_per_agent;
+        long long per = (total + total_waves - 1) / total_waves;
+        if (per < min_tiles_per_wave) per = min_tiles_per_wave;
+        plan[0] = run;
+        plan[1] = (int)per;
+        plan[2] = (int)total;
+        plan[3] = 0;
+        tpre[num_agents] = run;
+    }
+    __syncthreads();
+    int run = chunk_sum[tid];
+    for (int a = a0; a < a1; ++a) {
+        tpre[a] = run;
+        const int n = nlen[a];
+        run += n > 0 ? (n - tstart[a] + kWave - 1) / kWave : 0;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------- loads
 
 // One token's scales or biases (N binary16 values, N = 1, 2 or a multiple of 4) as raw bits: loaded with one
 // 2-, 4- or 8-byte load per 4 values and converted only where they are used, so that issuing the load never
@@ -110,13 +174,26 @@ __device__ __forceinline__ Words<W> load_words(const uint32_t *p)
     return r;
 }
 
-// DK, DV: head widths (multiples of 64, DK/8 and DV/8 divisible by KW and VW); NREP query heads per KV head.
-// KW / VW: 32-bit words of codes a lane takes per load on the K / V side.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// ---------------------------------------------------------------------------------------------- attention
+
+// Position of a wave in the tile stream; every field is wave-uniform.
+struct Cursor {
+    int lu;     // (layer in call) * kv_heads + kv head
+    int agent;
+    int j;      // tile index inside the unit
+    int tiles;  // tiles of the unit
+    int start;  // token of the unit's tile 0
+    int n;      // visible tokens of the agent
+};
+
+// DK, DV: head widths (multiples of 64); NREP query heads per KV head; VW: words of V codes per lane and load.
 //
 // Loads are never predicated: a tile's 64 rows always exist inside its block, so rows past the agent's
 // length are read and then ignored (their score is forced to "minus infinity", their p*s to zero; codes
 // are nibbles and cannot produce a NaN, scale/bias of such rows are replaced by zero after the load).
-template <int DK, int DV, int NREP, int KW, int VW>
+template <int DK, int DV, int NREP, int VW>
 __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attention_kernel(DecodeParams p)
 {
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
@@ -126,129 +203,92 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     constexpr int KGPC = KWPL == 4 ? 2 : 1;        // quantization groups per chunk
     constexpr int KSETS = kWave / 16;              // 16-token sets per tile
     constexpr int KROWS = NREP * KGPC;             // distinct rows of the query operand
-    static_assert(KW == 4 && KROWS <= 16 && KCHUNKS * KGPC == GK, "K layout");
+    static_assert(KROWS <= 16 && KCHUNKS * KGPC == GK, "K layout");
+    // V side: VLPT lanes share a token, VTPS token slots per load step
     constexpr int VLPT = DV / (8 * VW);
     constexpr int VTPS = kWave / VLPT;
     constexpr int VSTEPS = kWave / VTPS;
     constexpr int VLPG = kGroup / (8 * VW);
-    static_assert(VLPT <= kWave && VLPG >= 1 && VSTEPS % 2 == 0, "lane layout");
+    static_assert(VLPT <= kWave && VLPG >= 1 && VSTEPS % 2 == 0, "V layout");
 
     // per wave: q.c per token, group and head [64][GK][NREP] (binary32) and p*scale [NREP][GV][64] (binary16,
-    // tokens of consecutive V load steps interleaved so that a pair sits in one 32-bit word)
+    // tokens of consecutive V load steps interleaved so that a pair sits in one 32-bit word); the same
+    // region serves the end-of-unit reduction [VTPS][NREP][DV] + bias sums [NREP][GV]
     constexpr int kPartFloats = kWave * GK * NREP;
     constexpr int kPsFloats = NREP * GV * kWave / 2;
-    constexpr int kWaveFloats = kPartFloats + kPsFloats;
-    constexpr int kFinalFloats = kWaves * VTPS * NREP * DV + kWaves * NREP * GV + 2 * kWaves * NREP;
-    constexpr int kLdsFloats = (kWaves * kWaveFloats > kFinalFloats ? kWaves * kWaveFloats : kFinalFloats) + NREP * GK;
-    __shared__ float lds[kLdsFloats];
+    constexpr int kFinalFloats = VTPS * NREP * DV + NREP * GV;
+    constexpr int kWaveFloats = (kPartFloats + kPsFloats > kFinalFloats ? kPartFloats + kPsFloats : kFinalFloats) + NREP * GK;
+    __shared__ float lds[kWaves * kWaveFloats];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave); // wave-uniform, so tile addresses stay scalar
-    const int split = blockIdx.x;
-    const int kvh = blockIdx.y % p.kv_heads, agent = blockIdx.y / p.kv_heads;
-    const int li = blockIdx.z, layer = p.layer_begin + li;
+    const int wave = uniform(tid / kWave);
+    const int gw = blockIdx.x * kWaves + wave; // this wave's index in the launch
 
-    int n = p.seq_len[agent];
-    n = n < p.max_seq_len ? n : p.max_seq_len;
-    const int first = (p.window > 0 && n > p.window) ? n - p.window : 0;
-    const int t_begin = split * p.split_tokens;
-    if (t_begin >= n) return; // the combine kernel never looks at splits past the agent's length
-    const int t_end = min(n, t_begin + p.split_tokens);
+    const int TT = p.plan[0], per = p.plan[1], N = p.plan[2];
+    const int32_t *tpre = p.plan + kPlanHeader, *tstart = tpre + p.num_agents + 1, *nlen = tstart + p.num_agents;
+    const long long x_begin = (long long)gw * per;
+    if (x_begin >= N) return;
+    const int x0 = (int)x_begin;
+    const int x1 = (int)min((long long)N, x_begin + per);
 
-    const int64_t unit0 = ((int64_t)li * p.num_agents + agent) * p.q_heads + (int64_t)kvh * NREP;
-    if (t_end <= first) { // split lies wholly before the window: an empty partial
-        if (tid < NREP) {
-            float *ml = p.part_ml + ((unit0 + tid) * p.num_splits + split) * 2;
-            ml[0] = kNegBig;
-            ml[1] = 0.0f;
-        }
-        return;
-    }
-
-    float *qsum_lds = lds + (kLdsFloats - NREP * GK); // sum of q over each 64-wide group, [NREP][GK]
-    const uint16_t *qrow = p.q + unit0 * DK;           // NREP consecutive query heads
-    if (tid < NREP * GK * 8) { // eight lanes per 64-wide group, 8 dims each, folded inside the octet
-        const uint4 raw = *reinterpret_cast<const uint4 *>(qrow + tid * 8);
-        const half2_t a = bits_to_half2(raw.x), b = bits_to_half2(raw.y), c = bits_to_half2(raw.z), d = bits_to_half2(raw.w);
-        float s = ((float)a.x + (float)a.y) + ((float)b.x + (float)b.y) + ((float)c.x + (float)c.y) + ((float)d.x + (float)d.y);
-        s += Q4KV_DPP(0.0f, s, 0xB1, 0xF);  // quad_perm [1,0,3,2]
-        s += Q4KV_DPP(0.0f, s, 0x4E, 0xF);  // quad_perm [2,3,0,1]
-        s += Q4KV_DPP(0.0f, s, 0x141, 0xF); // row_half_mirror
-        if ((tid & 7) == 0) qsum_lds[tid >> 3] = s;
-    }
-
-    // Query operand of the matrix core, one per (chunk, word): row i = lane % 16 stands for query head
-    // i % NREP and group-in-chunk (i / NREP) % KGPC; the lane holds the 8 dims of its k-block in the order
-    // unpack_codes emits codes (0,4,1,5,2,6,3,7), odd dims divided by 16 because their codes arrive 16 times
-    // larger, and zeros when its k-block belongs to the row's other group.
-    const int kj = lane % 16, kkb = lane / 16;
-    half8_t qop[KCHUNKS][KWPL];
-    {
-        const int r = kj % NREP, u = (kj / NREP) % KGPC;
-        const bool mine = (KGPC == 1) || (u == kkb / 2);
-#pragma unroll
-        for (int c = 0; c < KCHUNKS; ++c)
-#pragma unroll
-            for (int w = 0; w < KWPL; ++w) {
-                const uint16_t *src = qrow + r * DK + c * (32 * KWPL) + kkb * (8 * KWPL) + 8 * w;
-                const uint4 raw = *reinterpret_cast<const uint4 *>(src);
-                const half2_t e01 = bits_to_half2(raw.x), e23 = bits_to_half2(raw.y);
-                const half2_t e45 = bits_to_half2(raw.z), e67 = bits_to_half2(raw.w);
-                const half_t sixteenth = (half_t)0.0625f;
-                half8_t v = {e01.x, e45.x, e01.y * sixteenth, e45.y * sixteenth,
-                             e23.x, e67.x, e23.y * sixteenth, e67.y * sixteenth};
-                if (!mine) v = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                qop[c][w] = v;
-            }
-    }
-    __syncthreads();
-    float qsum[NREP][GK];
-#pragma unroll
-    for (int r = 0; r < NREP; ++r)
-#pragma unroll
-        for (int g = 0; g < GK; ++g) qsum[r][g] = qsum_lds[r * GK + g];
-
-    float *part = lds + wave * kWaveFloats;                               // [64][GK][NREP]
-    uint16_t *ps_h = reinterpret_cast<uint16_t *>(part + kPartFloats);     // [NREP][GV][64] binary16
+    float *region = lds + wave * kWaveFloats;
+    float *part = region;                                                  // [64][GK][NREP]
+    uint16_t *ps_h = reinterpret_cast<uint16_t *>(region + kPartFloats);   // [NREP][GV][64] binary16
     const uint32_t *ps_w = reinterpret_cast<const uint32_t *>(ps_h);      // the same as token pairs
+    float *qsum_lds = region + (kWaveFloats - NREP * GK);                  // [NREP][GK]
 
+    // ---- where tile x0 lies: unit (lu, agent) by binary search over the agents' tile prefix sums
+    Cursor cur;
+    {
+        cur.lu = x0 / TT;
+        const int r = x0 - cur.lu * TT;
+        int lo = 0, hi = p.num_agents - 1; // largest a with tpre[a] <= r and at least one tile
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (tpre[mid] <= r) lo = mid; else hi = mid - 1;
+        }
+        cur.agent = lo;
+        cur.j = r - tpre[lo];
+        cur.tiles = tpre[lo + 1] - tpre[lo];
+        cur.start = tstart[lo];
+        cur.n = nlen[lo];
+    }
+    auto advance = [&](Cursor c) { // the tile after c (meaningful while it stays below x1)
+        if (++c.j >= c.tiles) {
+            c.j = 0;
+            do {
+                if (++c.agent >= p.num_agents) {
+                    c.agent = 0;
+                    ++c.lu;
+                }
+                c.tiles = tpre[c.agent + 1] - tpre[c.agent];
+            } while (c.tiles == 0);
+            c.start = tstart[c.agent];
+            c.n = nlen[c.agent];
+        }
+        return c;
+    };
+    // first pool row of the tile; rows of an unreachable block fall back to block 0 and are fully masked
+    auto tile_row = [&](const Cursor &c, bool &reachable) {
+        const int t0 = c.start + c.j * kWave;
+        const int bi = t0 / kBlockTokens;
+        const int blk = bi < p.max_blocks ? p.block_table[(long long)c.agent * p.max_blocks + bi] : -1;
+        reachable = blk >= 0 && blk < p.num_blocks;
+        const int layer = p.layer_begin + c.lu / p.kv_heads, kvh = c.lu % p.kv_heads;
+        return (((int64_t)layer * p.num_blocks + (reachable ? blk : 0)) * p.kv_heads + kvh) * kBlockTokens +
+               (t0 % kBlockTokens);
+    };
+
+    const int kj = lane % 16, kkb = lane / 16;
     const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / VLPG;
     // where the token owned by this lane (local index `lane` = step*VTPS + slot) goes in ps_h
     const int ps_slot = 2 * VTPS * ((lane / VTPS) / 2) + 2 * (lane % VTPS) + ((lane / VTPS) & 1);
-    float acc[NREP][8 * VW]; // odd dims carry an extra factor 16 until the end (their codes sit 4 bits higher)
-#pragma unroll
-    for (int r = 0; r < NREP; ++r)
-#pragma unroll
-        for (int e = 0; e < 8 * VW; ++e) acc[r][e] = 0.0f;
-    float m_run[NREP], l_run[NREP], pb[NREP][GV]; // l_run, pb: this lane's tokens only
-#pragma unroll
-    for (int r = 0; r < NREP; ++r) {
-        m_run[r] = kNegBig;
-        l_run[r] = 0.0f;
-#pragma unroll
-        for (int g = 0; g < GV; ++g) pb[r][g] = 0.0f;
-    }
-
-    const int32_t *table = p.block_table + (int64_t)agent * p.max_blocks;
-    const int b_end = (t_end + kBlockTokens - 1) / kBlockTokens;
-    // next block index >= bi whose 64-token tile of this wave holds visible tokens of a valid block
-    auto next_tile = [&](int bi, int64_t &row0) {
-        for (; bi < b_end; ++bi) {
-            const int t0 = bi * kBlockTokens + wave * kWave;
-            if (t0 >= t_end || t0 + kWave <= first) continue;
-            const int blk = table[bi];
-            if (blk < 0 || blk >= p.num_blocks) continue;
-            row0 = (((int64_t)layer * p.num_blocks + blk) * p.kv_heads + kvh) * kBlockTokens + wave * kWave;
-            return bi;
-        }
-        return b_end;
-    };
 
     Words<KWPL> kc[KSETS][KCHUNKS];
     Words<VW> vc[VSTEPS];
     GroupBits<GK> ks_bits, kb_bits;
     GroupBits<GV> vs_bits, vb_bits;
-    // tile base (uniform, from row0) + a fixed per-lane offset + a compile-time step offset
+    // tile base (uniform, from the row) + a fixed per-lane offset + a compile-time step offset
     const int k_lane_off = kj * (DK / 8) + kkb * KWPL;
     const int v_lane_off = vo * p.v_row_words + vj * VW;
     auto load_k = [&](int64_t row0) {
@@ -271,11 +311,83 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         vb_bits = load_groups<GV>(p.v_bias + row0 * p.v_row_groups + lane * p.v_row_groups);
     };
 
-    // One 64-token tile.  PREFETCH is a compile-time flag: every tile but the last of a wave issues the next
-    // tile's loads unconditionally (K codes once the K side is done, the rest after the V side), so the code
-    // buffers are plain loop-carried registers and loads are always in flight while the ALUs work.
-    auto tile = [&](const int t0, const int64_t row0_next, auto prefetch) {
-        constexpr bool PREFETCH = decltype(prefetch)::value;
+    half8_t qop[KCHUNKS][KWPL];
+    float qsum[NREP][GK];
+    float acc[NREP][8 * VW]; // odd dims carry an extra factor 16 until the end (their codes sit 4 bits higher)
+    float m_run[NREP], l_run[NREP], pb[NREP][GV]; // l_run, pb: this lane's tokens only
+
+    bool reachable = false, reachable_next = false;
+    int64_t row0 = tile_row(cur, reachable);
+    // same issue order as inside the loop (K codes first), pinned so that the wait for the K codes never
+    // covers the loads issued after them
+    load_k(row0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_params(row0);
+    load_v(row0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    bool unit_begins = true; // the wave's first tile, or tile 0 of a unit
+    for (int x = x0; x < x1; ++x) {
+        const bool last_of_wave = x + 1 >= x1;
+        const Cursor nxt = last_of_wave ? cur : advance(cur);
+        reachable_next = reachable;
+        const int64_t row0_next = last_of_wave ? row0 : tile_row(nxt, reachable_next);
+        const bool unit_ends = last_of_wave || nxt.j == 0;
+        const int64_t unit0 = ((int64_t)(cur.lu / p.kv_heads) * p.num_agents + cur.agent) * p.q_heads +
+                              (int64_t)(cur.lu % p.kv_heads) * NREP; // first of this unit's NREP query heads
+
+        if (unit_begins) {
+            // ---- new unit: its query heads.  Query operand of the matrix core, one per (chunk, word): row
+            // i = lane % 16 stands for query head i % NREP and group-in-chunk (i / NREP) % KGPC; the lane holds
+            // the 8 dims of its k-block in the order unpack_codes emits codes (0,4,1,5,2,6,3,7), odd dims divided
+            // by 16 because their codes arrive 16 times larger, and zeros when its k-block belongs to the row's
+            // other group.
+            const uint16_t *qrow = p.q + unit0 * DK;
+            const int r = kj % NREP, u = (kj / NREP) % KGPC;
+            const bool mine = (KGPC == 1) || (u == kkb / 2);
+#pragma unroll
+            for (int c = 0; c < KCHUNKS; ++c)
+#pragma unroll
+                for (int w = 0; w < KWPL; ++w) {
+                    const uint16_t *src = qrow + r * DK + c * (32 * KWPL) + kkb * (8 * KWPL) + 8 * w;
+                    const uint4 raw = *reinterpret_cast<const uint4 *>(src);
+                    const half2_t e01 = bits_to_half2(raw.x), e23 = bits_to_half2(raw.y);
+                    const half2_t e45 = bits_to_half2(raw.z), e67 = bits_to_half2(raw.w);
+                    const half_t sixteenth = (half_t)0.0625f;
+                    half8_t v = {e01.x, e45.x, e01.y * sixteenth, e45.y * sixteenth,
+                                 e23.x, e67.x, e23.y * sixteenth, e67.y * sixteenth};
+                    if (!mine) v = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                    qop[c][w] = v;
+                }
+            // sum of q over each 64-wide group: eight lanes per group, 8 dims each, folded inside the octet
+            for (int base = 0; base < NREP * GK * 8; base += kWave) {
+                const int idx = base + lane;
+                if (idx < NREP * GK * 8) {
+                    const uint4 raw = *reinterpret_cast<const uint4 *>(qrow + idx * 8);
+                    const half2_t a = bits_to_half2(raw.x), b = bits_to_half2(raw.y), c = bits_to_half2(raw.z),
+                                  d = bits_to_half2(raw.w);
+                    float s = ((float)a.x + (float)a.y) + ((float)b.x + (float)b.y) + ((float)c.x + (float)c.y) +
+                              ((float)d.x + (float)d.y);
+                    s += Q4KV_DPP(0.0f, s, 0xB1, 0xF);  // quad_perm [1,0,3,2]
+                    s += Q4KV_DPP(0.0f, s, 0x4E, 0xF);  // quad_perm [2,3,0,1]
+                    s += Q4KV_DPP(0.0f, s, 0x141, 0xF); // row_half_mirror
+                    if ((idx & 7) == 0) qsum_lds[idx >> 3] = s;
+                }
+            }
+            wave_lds_sync();
+#pragma unroll
+            for (int rr = 0; rr < NREP; ++rr) {
+#pragma unroll
+                for (int g = 0; g < GK; ++g) qsum[rr][g] = qsum_lds[rr * GK + g];
+                m_run[rr] = kNegBig;
+                l_run[rr] = 0.0f;
+#pragma unroll
+                for (int g = 0; g < GV; ++g) pb[rr][g] = 0.0f;
+#pragma unroll
+                for (int e = 0; e < 8 * VW; ++e) acc[rr][e] = 0.0f;
+            }
+        }
+
         // ---- K side: q.c per (token, head, group) on the matrix core, results to LDS in token order
         {
             float4_t d[KSETS][KCHUNKS];
@@ -309,11 +421,13 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                     }
             }
         }
-        if constexpr (PREFETCH) load_k(row0_next); // the next tile's K codes travel while this tile finishes
+        load_k(row0_next); // the next tile's K codes travel while this tile finishes
         wave_lds_sync();
 
         // ---- the lane that owns token `lane`: finish its scores, online softmax, publish p*s
-        const bool tok_valid = (t0 + lane >= first) && (t0 + lane < t_end);
+        const int t0 = cur.start + cur.j * kWave;
+        const int first = (p.window > 0 && cur.n > p.window) ? cur.n - p.window : 0;
+        const bool tok_valid = reachable && (t0 + lane >= first) && (t0 + lane < cur.n);
         float ks[GK], kb[GK], vs[GV], vb[GV];
 #pragma unroll
         for (int g = 0; g < GK; ++g) {
@@ -376,103 +490,89 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                 }
             }
         }
-        if constexpr (PREFETCH) {
-            load_params(row0_next);
-            load_v(row0_next);
-        }
-        wave_lds_sync(); // the next tile overwrites part / ps
-    };
+        load_params(row0_next);
+        load_v(row0_next);
+        wave_lds_sync(); // the next tile (or the reduction below) overwrites part / ps
 
-    int64_t row0 = 0, row0_next = 0;
-    int bi = next_tile(t_begin / kBlockTokens, row0);
-    if (bi < b_end) {
-        // same issue order as inside the loop (K codes first), pinned so that the wait for the K codes
-        // never covers the loads issued after them
-        load_k(row0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_params(row0);
-        load_v(row0);
-        __builtin_amdgcn_sched_barrier(0);
-        for (;;) {
-            const int bn = next_tile(bi + 1, row0_next);
-            if (bn >= b_end) break;
-            tile(bi * kBlockTokens + wave * kWave, row0_next, std::true_type{});
-            bi = bn;
+        if (unit_ends) {
+            // ---- this wave's share of the unit is complete: fold token slots and lanes through LDS (fixed
+            // order) and write one partial per query head into the slot this wave has in the unit
+            float *fin_acc = region;                      // [VTPS][NREP][DV]
+            float *fin_pb = region + VTPS * NREP * DV;    // [NREP][GV]
+            float lsum[NREP];
+#pragma unroll
+            for (int r = 0; r < NREP; ++r) {
+                float *dst = fin_acc + (vo * NREP + r) * DV + vj * 8 * VW;
+#pragma unroll
+                for (int e = 0; e < 8 * VW; ++e) dst[e] = acc[r][e] * ((e & 1) ? kCodeScaleB : kCodeScaleA);
+                lsum[r] = wave_sum(l_run[r]);
+#pragma unroll
+                for (int g = 0; g < GV; ++g) {
+                    const float s = wave_sum(pb[r][g]);
+                    if (lane == 0) fin_pb[r * GV + g] = s;
+                }
+            }
+            wave_lds_sync();
+            const int unit_first_tile = cur.lu * TT + tpre[cur.agent];
+            const int slot = gw - unit_first_tile / per;
+#pragma unroll
+            for (int r = 0; r < NREP; ++r) {
+                const int64_t rec = (unit0 + r) * p.max_slots + slot;
+#pragma unroll
+                for (int e0 = 0; e0 < DV; e0 += kWave) {
+                    const int e = e0 + lane;
+                    float o = fin_pb[r * GV + e / kGroup];
+#pragma unroll
+                    for (int sl = 0; sl < VTPS; ++sl) o += fin_acc[(sl * NREP + r) * DV + e];
+                    p.part_acc[rec * DV + e] = o;
+                }
+                if (lane == 0) {
+                    p.part_ml[rec * 2] = m_run[r];
+                    p.part_ml[rec * 2 + 1] = lsum[r];
+                }
+            }
+            wave_lds_sync();
         }
-        tile(bi * kBlockTokens + wave * kWave, 0, std::false_type{});
-    }
-
-    // ---- merge token slots, lanes and waves in a fixed order, through LDS
-    __syncthreads(); // every wave is done with its part / ps region
-    float *fin_acc = lds;                                   // [kWaves][VTPS][NREP][DV]
-    float *fin_pb = fin_acc + kWaves * VTPS * NREP * DV;    // [kWaves][NREP][GV]
-    float *fin_m = fin_pb + kWaves * NREP * GV;             // [kWaves][NREP]
-    float *fin_l = fin_m + kWaves * NREP;                   // [kWaves][NREP]
-#pragma unroll
-    for (int r = 0; r < NREP; ++r) {
-        float *dst = fin_acc + ((wave * VTPS + vo) * NREP + r) * DV + vj * 8 * VW;
-#pragma unroll
-        for (int e = 0; e < 8 * VW; ++e) dst[e] = acc[r][e] * ((e & 1) ? kCodeScaleB : kCodeScaleA);
-        const float lsum = wave_sum(l_run[r]);
-#pragma unroll
-        for (int g = 0; g < GV; ++g) {
-            const float s = wave_sum(pb[r][g]);
-            if (lane == 0) fin_pb[(wave * NREP + r) * GV + g] = s;
-        }
-        if (lane == 0) {
-            fin_m[wave * NREP + r] = m_run[r];
-            fin_l[wave * NREP + r] = lsum;
-        }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < NREP * DV; idx += kThreads) {
-        const int r = idx / DV, e = idx % DV;
-        float m = kNegBig;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) m = fmaxf(m, fin_m[w * NREP + r]);
-        float o = 0.0f, l = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float f = __builtin_amdgcn_exp2f(fin_m[w * NREP + r] - m);
-            float a = fin_pb[(w * NREP + r) * GV + e / kGroup];
-#pragma unroll
-            for (int sl = 0; sl < VTPS; ++sl) a += fin_acc[((w * VTPS + sl) * NREP + r) * DV + e];
-            o = fmaf(f, a, o);
-            l = fmaf(f, fin_l[w * NREP + r], l);
-        }
-        const int64_t rec = (unit0 + r) * p.num_splits + split;
-        p.part_acc[rec * DV + e] = o;
-        if (e == 0) {
-            p.part_ml[rec * 2] = m;
-            p.part_ml[rec * 2 + 1] = l;
-        }
+        unit_begins = unit_ends;
+        cur = nxt;
+        row0 = row0_next;
+        reachable = reachable_next;
     }
 }
 
-// Merge the split partials of one (layer, agent, query head): fixed order, binary32, output binary16.
+// Merge the partials of one (layer, agent, query head) in slot order: binary32, output binary16.
 __global__ __launch_bounds__(kWave) void combine_kernel(const float *__restrict__ part_acc,
                                                         const float *__restrict__ part_ml,
-                                                        const int32_t *__restrict__ seq_len, uint16_t *__restrict__ out,
-                                                        int q_heads, int num_agents, int v_dim, int num_splits,
-                                                        int split_tokens, int max_seq_len)
+                                                        const int32_t *__restrict__ plan, uint16_t *__restrict__ out,
+                                                        int q_heads, int kv_heads, int num_agents, int v_dim,
+                                                        int max_slots)
 {
-    const int64_t unit = blockIdx.x;
+    const int64_t unit = blockIdx.x; // (layer in call, agent, query head)
+    const int qh = (int)(unit % q_heads);
     const int agent = (int)((unit / q_heads) % num_agents);
-    int n = seq_len[agent];
-    n = n < max_seq_len ? n : max_seq_len;
-    const int live = n > 0 ? (n + split_tokens - 1) / split_tokens : 0;
-    const float *ml = part_ml + unit * num_splits * 2;
+    const int li = (int)(unit / ((int64_t)q_heads * num_agents));
+    const int kvh = qh / (q_heads / kv_heads);
+    const int TT = plan[0], per = plan[1];
+    const int32_t *tpre = plan + kPlanHeader;
+    const int tiles = tpre[agent + 1] - tpre[agent];
+    int slots = 0;
+    if (tiles > 0) {
+        const long long u0 = (long long)(li * kv_heads + kvh) * TT + tpre[agent];
+        slots = (int)((u0 + tiles - 1) / per - u0 / per) + 1;
+    }
+    const float *ml = part_ml + unit * max_slots * 2;
     float m = kNegBig;
-    for (int s = 0; s < live; ++s)
+    for (int s = 0; s < slots; ++s)
         if (ml[2 * s + 1] > 0.0f) m = fmaxf(m, ml[2 * s]);
     float denom = 0.0f;
-    for (int s = 0; s < live; ++s)
+    for (int s = 0; s < slots; ++s)
         if (ml[2 * s + 1] > 0.0f) denom = fmaf(__builtin_amdgcn_exp2f(ml[2 * s] - m), ml[2 * s + 1], denom);
     const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
     for (int e = threadIdx.x; e < v_dim; e += kWave) {
         float o = 0.0f;
-        for (int s = 0; s < live; ++s)
-            if (ml[2 * s + 1] > 0.0f) o = fmaf(__builtin_amdgcn_exp2f(ml[2 * s] - m), part_acc[(unit * num_splits + s) * v_dim + e], o);
+        for (int s = 0; s < slots; ++s)
+            if (ml[2 * s + 1] > 0.0f)
+                o = fmaf(__builtin_amdgcn_exp2f(ml[2 * s] - m), part_acc[(unit * max_slots + s) * v_dim + e], o);
         out[unit * v_dim + e] = float_to_half_bits(o * inv);
     }
 }
@@ -483,25 +583,20 @@ hipError_t launch_decode_t(const AttentionArgs &a, hipStream_t stream)
     DecodeParams p;
     p.k_codes = a.k.codes; p.k_scale = a.k.scale; p.k_bias = a.k.bias;
     p.v_codes = a.v.codes; p.v_scale = a.v.scale; p.v_bias = a.v.bias;
-    p.q = a.q; p.block_table = a.block_table; p.seq_len = a.seq_len;
+    p.q = a.q; p.block_table = a.block_table; p.plan = a.plan;
     p.part_acc = a.part_acc; p.part_ml = a.part_ml;
     p.num_blocks = a.k.num_blocks; p.kv_heads = a.spec.num_kv_heads; p.q_heads = a.spec.num_q_heads;
-    p.num_agents = a.num_agents; p.max_blocks = a.max_blocks; p.max_seq_len = a.max_seq_len;
-    p.window = a.window; p.split_tokens = a.split_tokens; p.num_splits = a.num_splits;
+    p.num_agents = a.num_agents; p.max_blocks = a.max_blocks;
+    p.window = a.window; p.max_slots = a.max_slots;
     p.layer_begin = a.layer_begin;
     const int v_row_dim = a.spec.v_aliases_k ? a.spec.k_dim : a.spec.v_dim;
     p.v_row_words = v_row_dim / 8; p.v_row_groups = v_row_dim / kGroup;
     p.score_scale = a.sm_scale * kLog2e;
-    dim3 grid(a.num_splits, a.num_agents * a.spec.num_kv_heads, a.layers_in_call);
-#ifndef Q4KV_DEC_KW
-#define Q4KV_DEC_KW 4
-#endif
 #ifndef Q4KV_DEC_VW
 #define Q4KV_DEC_VW (NREP >= 4 ? 1 : 2) // keeps the NREP * 8 * VW accumulators and both code buffers in registers
 #endif
-    constexpr int KW = Q4KV_DEC_KW;
     constexpr int VW = (DV / 16 < (Q4KV_DEC_VW)) ? DV / 16 : (Q4KV_DEC_VW);
-    hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, KW, VW>), grid, dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, VW>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -512,22 +607,32 @@ hipError_t launch_decode_d(const AttentionArgs &a, int n_rep, hipStream_t stream
     case 1: return launch_decode_t<DK, DV, 1>(a, stream);
     case 2: return launch_decode_t<DK, DV, 2>(a, stream);
     case 4: return launch_decode_t<DK, DV, 4>(a, stream);
+    case 8: return launch_decode_t<DK, DV, 8>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
 } // namespace
 
+int decode_waves_per_workgroup() { return kWaves; }
+
+size_t decode_plan_ints(int num_agents) { return (size_t)kPlanHeader + 3 * (size_t)num_agents + 1; }
+
 bool decode_supported(const q4kv_spec &s)
 {
     const int n_rep = s.num_q_heads / s.num_kv_heads;
-    const bool rep_ok = n_rep == 1 || n_rep == 2 || n_rep == 4;
+    const bool rep_ok = n_rep == 1 || n_rep == 2 || n_rep == 4 || n_rep == 8;
     const bool dims_ok = (s.k_dim == 64 || s.k_dim == 128 || s.k_dim == 256) && s.v_dim == s.k_dim && !s.v_aliases_k;
     return rep_ok && dims_ok;
 }
 
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
 {
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len,
+                       a.window, a.layers_in_call * a.spec.num_kv_heads, a.grid_workgroups * kWaves,
+                       a.split_tokens / kWave, a.plan);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     const int n_rep = a.spec.num_q_heads / a.spec.num_kv_heads;
     switch (a.spec.k_dim) {
     case 64: return launch_decode_d<64, 64>(a, n_rep, stream);
@@ -541,9 +646,8 @@ hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream)
 {
     const int64_t units = (int64_t)a.layers_in_call * a.num_agents * a.q_len * a.spec.num_q_heads;
     if (units == 0) return hipSuccess;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)units), dim3(kWave), 0, stream, a.part_acc, a.part_ml, a.seq_len,
-                       a.out, a.spec.num_q_heads, a.num_agents, a.spec.v_dim, a.num_splits, a.split_tokens,
-                       a.max_seq_len);
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)units), dim3(kWave), 0, stream, a.part_acc, a.part_ml, a.plan,
+                       a.out, a.spec.num_q_heads, a.spec.num_kv_heads, a.num_agents, a.spec.v_dim, a.max_slots);
     return hipGetLastError();
 }
 

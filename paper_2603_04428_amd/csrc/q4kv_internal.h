@@ -23,15 +23,21 @@ struct AttentionArgs {
     uint16_t *out;
     const int32_t *block_table;
     const int32_t *seq_len;
-    int max_blocks, num_agents, q_len, max_seq_len, window, split_tokens, num_splits;
+    int max_blocks, num_agents, q_len, max_seq_len, window;
+    int split_tokens;           // smallest token range one wave takes (multiple of 256)
+    int max_slots;              // partial records reserved per (layer, agent, query head)
+    int grid_workgroups;        // workgroups of the attention launch (two per compute unit)
     int layer_begin, layers_in_call;
     float sm_scale;
-    float *part_acc;            // workspace: [units][num_splits][v_dim]
-    float *part_ml;             // workspace: [units][num_splits][2]  (running max in log2 units, denominator)
+    int32_t *plan;              // workspace: tile plan written by the plan kernel
+    float *part_acc;            // workspace: [units][max_slots][v_dim]
+    float *part_ml;             // workspace: [units][max_slots][2]  (running max in log2 units, denominator)
 };
 
 // true when a decode (q_len == 1) kernel exists for these head shapes
 bool decode_supported(const q4kv_spec &spec);
+int decode_waves_per_workgroup();
+size_t decode_plan_ints(int num_agents);
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream);
 

@@ -114,7 +114,11 @@ def test_batch_equals_single_agent_calls_and_block_placement():
     for a in range(3):
         one = run_gpu(w, spec, kpool, vpool, table_d[a:a + 1].contiguous(), w.seq_lens[a:a + 1], 256,
                       q=q[:, a:a + 1].contiguous())
-        assert np.array_equal(one[:, 0].view(np.uint16), full[:, a].view(np.uint16))
+        # the token ranges handed to wavefronts depend on the whole batch, so the summation order (not the
+        # result beyond rounding) differs between a batched and a single-agent call
+        assert_close(one[:, 0], full[:, a].astype(np.float64), f"agent {a} alone vs in the batch")
+        ok, _, worst = within_tol(one[:, 0], full[:, a], atol=2e-4, rtol=1e-3)
+        assert ok, worst
     # move every block to another physical slot: identical bits
     nb = kpool.num_blocks
     perm = torch.randperm(nb, generator=torch.Generator().manual_seed(0)).to(DEV)
