@@ -30,9 +30,12 @@
 //    (4 words) of one token row; the four lanes that share a token cover a 64-byte chunk = two groups,
 //    and the query operand is zeroed outside a row's own group so that one instruction yields both
 //    groups' partial dot products separately.
-//  * V side: the contraction runs over tokens while a word holds 8 dims of one token, so the matrix
-//    core's operand shape does not fit; each lane owns 8*VW output dims, pairs the codes of two tokens
-//    with v_perm and multiplies them with the binary16 pair (p s)[t], (p s)[t'] in one v_dot2_f32_f16.
+//  * V side: the contraction runs over tokens while a word holds 8 dims of one token, so the big matrix
+//    tiles do not fit (their K-index would have to be 8 tokens of one dim).  It runs on the 16-block
+//    4x4x4 form instead (v_mfma_f32_4x4x4_16B_f16): each block of 4 lanes multiplies the 4x4 matrix
+//    (query head) x (4 tokens) of binary16 p*s -- one quantization group per block, so the per-group
+//    scale can live in it -- with (4 tokens) x (4 dims) of codes.  The lane owning a word pairs the
+//    codes of two tokens with v_perm and masks nibbles in place, two tokens per register.
 #include "q4_device.h"
 #include "q4kv_internal.h"
 
@@ -63,7 +66,6 @@ struct DecodeParams {
     float *part_acc, *part_ml;
     int num_blocks, kv_heads, q_heads, num_agents, max_blocks, window, max_slots;
     int layer_begin;
-    int v_row_words, v_row_groups; // row pitch of the V pool in words / groups (K's pitch when V aliases K)
     float score_scale;             // sm_scale * log2(e): scores are kept in log2 units
 };
 
@@ -188,12 +190,12 @@ struct Cursor {
     int n;      // visible tokens of the agent
 };
 
-// DK, DV: head widths (multiples of 64); NREP query heads per KV head; VW: words of V codes per lane and load.
+// DK, DV: head widths (multiples of 64); NREP query heads per KV head.
 //
 // Loads are never predicated: a tile's 64 rows always exist inside its block, so rows past the agent's
 // length are read and then ignored (their score is forced to "minus infinity", their p*s to zero; codes
 // are nibbles and cannot produce a NaN, scale/bias of such rows are replaced by zero after the load).
-template <int DK, int DV, int NREP, int VW>
+template <int DK, int DV, int NREP>
 __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attention_kernel(DecodeParams p)
 {
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
@@ -204,15 +206,15 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     constexpr int KSETS = kWave / 16;              // 16-token sets per tile
     constexpr int KROWS = NREP * KGPC;             // distinct rows of the query operand
     static_assert(KROWS <= 16 && KCHUNKS * KGPC == GK, "K layout");
-    // V side: VLPT lanes share a token, VTPS token slots per load step
-    constexpr int VLPT = DV / (8 * VW);
+    // V side (16 blocks of 4x4x4): a lane takes one word (8 dims) per token, VLPT lanes share a token, VTPS
+    // token slots per load step; the 4 lanes of a block lie in one token slot and one quantization group
+    constexpr int VLPT = DV / 8;
     constexpr int VTPS = kWave / VLPT;
     constexpr int VSTEPS = kWave / VTPS;
-    constexpr int VLPG = kGroup / (8 * VW);
-    static_assert(VLPT <= kWave && VLPG >= 1 && VSTEPS % 2 == 0, "V layout");
-
+    constexpr int VHQ = NREP > 4 ? NREP / 4 : 1;   // passes over the query heads, 4 rows each
+    static_assert(VLPT % 8 == 0 && VLPT <= kWave && VSTEPS % 4 == 0, "V layout");
     // per wave: q.c per token, group and head [64][GK][NREP] (binary32) and p*scale [NREP][GV][64] (binary16,
-    // tokens of consecutive V load steps interleaved so that a pair sits in one 32-bit word); the same
+    // the tokens of four consecutive V load steps of a slot side by side, 8 bytes); the same
     // region serves the end-of-unit reduction [VTPS][NREP][DV] + bias sums [NREP][GV]
     constexpr int kPartFloats = kWave * GK * NREP;
     constexpr int kPsFloats = NREP * GV * kWave / 2;
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     float *region = lds + wave * kWaveFloats;
     float *part = region;                                                  // [64][GK][NREP]
     uint16_t *ps_h = reinterpret_cast<uint16_t *>(region + kPartFloats);   // [NREP][GV][64] binary16
-    const uint32_t *ps_w = reinterpret_cast<const uint32_t *>(ps_h);      // the same as token pairs
+    const uint2 *ps_q = reinterpret_cast<const uint2 *>(ps_h);            // the same as token quads
     float *qsum_lds = region + (kWaveFloats - NREP * GK);                  // [NREP][GK]
 
     // ---- where tile x0 lies: unit (lu, agent) by binary search over the agents' tile prefix sums
@@ -280,17 +282,18 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     };
 
     const int kj = lane % 16, kkb = lane / 16;
-    const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / VLPG;
+    const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / 8;
     // where the token owned by this lane (local index `lane` = step*VTPS + slot) goes in ps_h
-    const int ps_slot = 2 * VTPS * ((lane / VTPS) / 2) + 2 * (lane % VTPS) + ((lane / VTPS) & 1);
+    const int ps_slot = 4 * VTPS * ((lane / VTPS) / 4) + 4 * (lane % VTPS) + ((lane / VTPS) & 3);
+    const int v_row = NREP >= 4 ? (lane & 3) : (lane & 3) % NREP; // query head (within a pass) of this lane's operand row
 
     Words<KWPL> kc[KSETS][KCHUNKS];
-    Words<VW> vc[VSTEPS];
+    uint32_t vc[VSTEPS];
     GroupBits<GK> ks_bits, kb_bits;
     GroupBits<GV> vs_bits, vb_bits;
     // tile base (uniform, from the row) + a fixed per-lane offset + a compile-time step offset
     const int k_lane_off = kj * (DK / 8) + kkb * KWPL;
-    const int v_lane_off = vo * p.v_row_words + vj * VW;
+    const int v_lane_off = vo * (DV / 8) + vj;
     auto load_k = [&](int64_t row0) {
         const uint32_t *tile = p.k_codes + row0 * (DK / 8);
 #pragma unroll
@@ -300,20 +303,21 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                 kc[ts][c] = load_words<KWPL>(tile + k_lane_off + ts * 16 * (DK / 8) + c * 4 * KWPL);
     };
     auto load_v = [&](int64_t row0) {
-        const uint32_t *tile = p.v_codes + row0 * p.v_row_words;
+        const uint32_t *tile = p.v_codes + row0 * (DV / 8);
 #pragma unroll
-        for (int i = 0; i < VSTEPS; ++i) vc[i] = load_words<VW>(tile + v_lane_off + i * VTPS * p.v_row_words);
+        for (int i = 0; i < VSTEPS; ++i) vc[i] = tile[v_lane_off + i * VTPS * (DV / 8)];
     };
     auto load_params = [&](int64_t row0) {
         ks_bits = load_groups<GK>(p.k_scale + row0 * GK + lane * GK);
         kb_bits = load_groups<GK>(p.k_bias + row0 * GK + lane * GK);
-        vs_bits = load_groups<GV>(p.v_scale + row0 * p.v_row_groups + lane * p.v_row_groups);
-        vb_bits = load_groups<GV>(p.v_bias + row0 * p.v_row_groups + lane * p.v_row_groups);
+        vs_bits = load_groups<GV>(p.v_scale + row0 * GV + lane * GV);
+        vb_bits = load_groups<GV>(p.v_bias + row0 * GV + lane * GV);
     };
 
     half8_t qop[KCHUNKS][KWPL];
     float qsum[NREP][GK];
-    float acc[NREP][8 * VW]; // odd dims carry an extra factor 16 until the end (their codes sit 4 bits higher)
+    float4_t acc[VHQ][8]; // [pass][dim of this lane's word][head in pass]; odd dims carry an extra factor 16 until
+                          // the end (their codes sit 4 bits higher)
     float m_run[NREP], l_run[NREP], pb[NREP][GV]; // l_run, pb: this lane's tokens only
 
     bool reachable = false, reachable_next = false;
@@ -383,25 +387,29 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                 l_run[rr] = 0.0f;
 #pragma unroll
                 for (int g = 0; g < GV; ++g) pb[rr][g] = 0.0f;
-#pragma unroll
-                for (int e = 0; e < 8 * VW; ++e) acc[rr][e] = 0.0f;
             }
+#pragma unroll
+            for (int h = 0; h < VHQ; ++h)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[h][e] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
         }
 
-        // ---- K side: q.c per (token, head, group) on the matrix core, results to LDS in token order
-        {
-            float4_t d[KSETS][KCHUNKS];
+        // ---- K side: q.c per (token, head, group) on the matrix core, results to LDS in token order;
+        // two 16-token sets at a time keep the accumulators few
 #pragma unroll
-            for (int ts = 0; ts < KSETS; ++ts)
+        for (int tp = 0; tp < KSETS; tp += 2) {
+            float4_t d[2][KCHUNKS];
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
                 for (int c = 0; c < KCHUNKS; ++c) d[ts][c] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int w = 0; w < KWPL; ++w)
 #pragma unroll
-                for (int ts = 0; ts < KSETS; ++ts)
+                for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
                     for (int c = 0; c < KCHUNKS; ++c) {
-                        const CodePairs cp = unpack_codes(kc[ts][c].w[w]);
+                        const CodePairs cp = unpack_codes(kc[tp + ts][c].w[w]);
                         const uint4 packed = make_uint4(half2_to_bits(cp.a0), half2_to_bits(cp.b0),
                                                         half2_to_bits(cp.a1), half2_to_bits(cp.b1));
                         d[ts][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[c][w], __builtin_bit_cast(half8_t, packed),
@@ -412,10 +420,10 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
             constexpr int kRegs = KROWS < 4 ? KROWS : 4;
             if (4 * kkb < KROWS) {
 #pragma unroll
-                for (int ts = 0; ts < KSETS; ++ts)
+                for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
                     for (int c = 0; c < KCHUNKS; ++c) {
-                        float *dst = part + ((ts * 16 + kj) * GK + c * KGPC) * NREP + 4 * kkb;
+                        float *dst = part + (((tp + ts) * 16 + kj) * GK + c * KGPC) * NREP + 4 * kkb;
 #pragma unroll
                         for (int e = 0; e < kRegs; ++e) dst[e] = d[ts][c][e];
                     }
@@ -462,31 +470,33 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         }
         wave_lds_sync();
 
-        // ---- V side: acc[r][e] += (p s)[t] * c[t][e], two tokens per v_dot2_f32_f16
+        // ---- V side: acc[head][e] += (p s)[t] * c[t][e], four tokens per matrix instruction
 #pragma unroll
         for (int r = 0; r < NREP; ++r)
             if (alpha[r] != 1.0f) { // wave-uniform
 #pragma unroll
-                for (int e = 0; e < 8 * VW; ++e) acc[r][e] *= alpha[r];
+                for (int e = 0; e < 8; ++e) acc[r / 4][e][r % 4] *= alpha[r];
             }
 #pragma unroll
-        for (int i = 0; i < VSTEPS; i += 2) {
-            half2_t pp[NREP];
+        for (int i = 0; i < VSTEPS; i += 4) {
+            half4_t pq[VHQ];
 #pragma unroll
-            for (int r = 0; r < NREP; ++r) pp[r] = bits_to_half2(ps_w[(r * GV + vg) * (kWave / 2) + VTPS * (i / 2) + vo]);
+            for (int h = 0; h < VHQ; ++h) {
+                const uint2 raw = ps_q[((h * 4 + v_row) * GV + vg) * (kWave / 4) + VTPS * (i / 4) + vo];
+                pq[h] = __builtin_bit_cast(half4_t, raw);
+            }
 #pragma unroll
-            for (int w = 0; w < VW; ++w) {
+            for (int by = 0; by < 4; ++by) {
+                // byte `by` of the four tokens' words: codes 2*by (low nibble) and 2*by+1 (high nibble)
+                const uint32_t sel = 0x0C040C00u + by * 0x00010001u;
+                const uint32_t p01 = __builtin_amdgcn_perm(vc[i + 1], vc[i], sel);
+                const uint32_t p23 = __builtin_amdgcn_perm(vc[i + 3], vc[i + 2], sel);
+                const half4_t lo = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x000F000Fu, p23 & 0x000F000Fu));
+                const half4_t hi = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x00F000F0u, p23 & 0x00F000F0u));
 #pragma unroll
-                for (int by = 0; by < 4; ++by) {
-                    // byte `by` of both tokens' words: codes 2*by (low nibble) and 2*by+1 (high nibble)
-                    const uint32_t pair = __builtin_amdgcn_perm(vc[i + 1].w[w], vc[i].w[w], 0x0C040C00u + by * 0x00010001u);
-                    const half2_t lo = bits_to_half2(pair & 0x000F000Fu);
-                    const half2_t hi = bits_to_half2(pair & 0x00F000F0u);
-#pragma unroll
-                    for (int r = 0; r < NREP; ++r) {
-                        acc[r][8 * w + 2 * by] = dot2(lo, pp[r], acc[r][8 * w + 2 * by]);
-                        acc[r][8 * w + 2 * by + 1] = dot2(hi, pp[r], acc[r][8 * w + 2 * by + 1]);
-                    }
+                for (int h = 0; h < VHQ; ++h) {
+                    acc[h][2 * by] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[h], lo, acc[h][2 * by], 0, 0, 0);
+                    acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[h], hi, acc[h][2 * by + 1], 0, 0, 0);
                 }
             }
         }
@@ -502,9 +512,9 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
             float lsum[NREP];
 #pragma unroll
             for (int r = 0; r < NREP; ++r) {
-                float *dst = fin_acc + (vo * NREP + r) * DV + vj * 8 * VW;
+                float *dst = fin_acc + (vo * NREP + r) * DV + vj * 8;
 #pragma unroll
-                for (int e = 0; e < 8 * VW; ++e) dst[e] = acc[r][e] * ((e & 1) ? kCodeScaleB : kCodeScaleA);
+                for (int e = 0; e < 8; ++e) dst[e] = acc[r / 4][e][r % 4] * ((e & 1) ? kCodeScaleB : kCodeScaleA);
                 lsum[r] = wave_sum(l_run[r]);
 #pragma unroll
                 for (int g = 0; g < GV; ++g) {
@@ -589,14 +599,8 @@ hipError_t launch_decode_t(const AttentionArgs &a, hipStream_t stream)
     p.num_agents = a.num_agents; p.max_blocks = a.max_blocks;
     p.window = a.window; p.max_slots = a.max_slots;
     p.layer_begin = a.layer_begin;
-    const int v_row_dim = a.spec.v_aliases_k ? a.spec.k_dim : a.spec.v_dim;
-    p.v_row_words = v_row_dim / 8; p.v_row_groups = v_row_dim / kGroup;
     p.score_scale = a.sm_scale * kLog2e;
-#ifndef Q4KV_DEC_VW
-#define Q4KV_DEC_VW (NREP >= 4 ? 1 : 2) // keeps the NREP * 8 * VW accumulators and both code buffers in registers
-#endif
-    constexpr int VW = (DV / 16 < (Q4KV_DEC_VW)) ? DV / 16 : (Q4KV_DEC_VW);
-    hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, VW>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 
