@@ -18,7 +18,7 @@
 //    and private LDS, and the next tile's loads (also across a unit boundary) are issued while the
 //    current tile is processed, so loads are always in flight.
 //  * Codes never become integers or binary32: a nibble masked in place is a binary16 subnormal
-//    (c*2^-24 or c*2^-20) and goes straight into the matrix core (K side) or v_dot2_f32_f16 (V side).
+//    (c*2^-24 or c*2^-20) and goes straight into a matrix-core operand.
 //  * The affine part of the dequantization is factored out of the inner loops:
 //        q . K_hat[t]   = sum_g  s[t,g] * (q_g . c[t,g])  +  b[t,g] * sum(q_g)
 //        sum_t p_t V_hat[t,e] = sum_t (p_t s[t,g(e)]) c[t,e]  +  sum_t p_t b[t,g(e)]
@@ -57,6 +57,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 //   [.. +A]           nlen[a]   seq_len clamped to [0, max_seq_len]
 constexpr int kPlanHeader = 4;
 
+
 struct DecodeParams {
     const uint32_t *k_codes, *v_codes;
     const uint16_t *k_scale, *k_bias, *v_scale, *v_bias;
@@ -94,24 +95,24 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
     }
     chunk_sum[tid] = local;
     __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int i = 0; i < kThreads; ++i) {
-            const int c = chunk_sum[i];
-            chunk_sum[i] = run;
-            run += c;
-        }
-        const long long total = (long long)run * units_per_agent;
+    for (int off = 1; off < kThreads; off <<= 1) { // inclusive scan, log2(256) rounds
+        const int add = tid >= off ? chunk_sum[tid - off] : 0;
+        __syncthreads();
+        chunk_sum[tid] += add;
+        __syncthreads();
+    }
+    if (tid == kThreads - 1) {
+        const int all = chunk_sum[tid];
+        const long long total = (long long)all * units_per_agent;
         long long per = (total + total_waves - 1) / total_waves;
         if (per < min_tiles_per_wave) per = min_tiles_per_wave;
-        plan[0] = run;
+        plan[0] = all;
         plan[1] = (int)per;
         plan[2] = (int)total;
         plan[3] = 0;
-        tpre[num_agents] = run;
+        tpre[num_agents] = all;
     }
-    __syncthreads();
-    int run = chunk_sum[tid];
+    int run = chunk_sum[tid] - local; // exclusive prefix of this thread's chunk
     for (int a = a0; a < a1; ++a) {
         tpre[a] = run;
         const int n = nlen[a];
@@ -180,14 +181,17 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 
 // ---------------------------------------------------------------------------------------------- attention
 
-// Position of a wave in the tile stream; every field is wave-uniform.
+// Position of a wave in the tile stream; every field is wave-uniform and lives in scalar registers.
+// Everything that needs a division, a wide multiply or a memory lookup is refreshed only where it can
+// change: per unit (unit_row, unit0, first) or per 256-token block (row of the block, reachable).
 struct Cursor {
-    int lu;     // (layer in call) * kv_heads + kv head
-    int agent;
-    int j;      // tile index inside the unit
-    int tiles;  // tiles of the unit
-    int start;  // token of the unit's tile 0
-    int n;      // visible tokens of the agent
+    int li, kvh, agent;  // unit: layer in call, KV head, agent
+    int j, tiles;        // tile inside the unit, tiles of the unit
+    int t0;              // first token of the tile
+    int n, first;        // visible tokens of the agent, first visible token (sliding window)
+    int64_t unit_row;    // pool row of (layer, block 0, kv head, slot 0)
+    int64_t row;         // pool row of the tile's first token
+    bool reachable;      // the tile's block id is inside the pool
 };
 
 // DK, DV: head widths (multiples of 64); NREP query heads per KV head.
@@ -239,47 +243,58 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     const uint2 *ps_q = reinterpret_cast<const uint2 *>(ps_h);            // the same as token quads
     float *qsum_lds = region + (kWaveFloats - NREP * GK);                  // [NREP][GK]
 
-    // ---- where tile x0 lies: unit (lu, agent) by binary search over the agents' tile prefix sums
+    // ---- cursor helpers.  enter_unit / enter_block do the memory lookups; step() is a handful of scalar adds
+    auto enter_block = [&](Cursor &c) {
+        const int bi = c.t0 / kBlockTokens;
+        const int blk = bi < p.max_blocks ? p.block_table[(long long)c.agent * p.max_blocks + bi] : -1;
+        c.reachable = blk >= 0 && blk < p.num_blocks;
+        // rows of an unreachable block fall back to block 0 and are fully masked
+        c.row = c.unit_row + (int64_t)(c.reachable ? blk : 0) * (p.kv_heads * kBlockTokens) + (c.t0 % kBlockTokens);
+    };
+    auto enter_unit = [&](Cursor &c) {
+        c.tiles = tpre[c.agent + 1] - tpre[c.agent];
+        c.n = nlen[c.agent];
+        c.first = (p.window > 0 && c.n > p.window) ? c.n - p.window : 0;
+        c.unit_row = (((int64_t)(p.layer_begin + c.li) * p.num_blocks) * p.kv_heads + c.kvh) * kBlockTokens;
+    };
+    auto step = [&](Cursor &c) { // to the next tile of the stream (meaningful while it stays below x1)
+        if (++c.j < c.tiles) {
+            c.t0 += kWave;
+            if (c.t0 % kBlockTokens == 0) enter_block(c); else c.row += kWave;
+            return;
+        }
+        do {
+            if (++c.agent >= p.num_agents) {
+                c.agent = 0;
+                if (++c.kvh >= p.kv_heads) {
+                    c.kvh = 0;
+                    ++c.li;
+                }
+            }
+        } while (tpre[c.agent + 1] == tpre[c.agent]);
+        c.j = 0;
+        c.t0 = tstart[c.agent];
+        enter_unit(c);
+        enter_block(c);
+    };
+
+    // ---- where tile x0 lies: unit by binary search over the agents' tile prefix sums
     Cursor cur;
     {
-        cur.lu = x0 / TT;
-        const int r = x0 - cur.lu * TT;
+        const int lu = x0 / TT, r = x0 - lu * TT;
         int lo = 0, hi = p.num_agents - 1; // largest a with tpre[a] <= r and at least one tile
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
             if (tpre[mid] <= r) lo = mid; else hi = mid - 1;
         }
+        cur.li = lu / p.kv_heads;
+        cur.kvh = lu % p.kv_heads;
         cur.agent = lo;
         cur.j = r - tpre[lo];
-        cur.tiles = tpre[lo + 1] - tpre[lo];
-        cur.start = tstart[lo];
-        cur.n = nlen[lo];
+        cur.t0 = tstart[lo] + cur.j * kWave;
+        enter_unit(cur);
+        enter_block(cur);
     }
-    auto advance = [&](Cursor c) { // the tile after c (meaningful while it stays below x1)
-        if (++c.j >= c.tiles) {
-            c.j = 0;
-            do {
-                if (++c.agent >= p.num_agents) {
-                    c.agent = 0;
-                    ++c.lu;
-                }
-                c.tiles = tpre[c.agent + 1] - tpre[c.agent];
-            } while (c.tiles == 0);
-            c.start = tstart[c.agent];
-            c.n = nlen[c.agent];
-        }
-        return c;
-    };
-    // first pool row of the tile; rows of an unreachable block fall back to block 0 and are fully masked
-    auto tile_row = [&](const Cursor &c, bool &reachable) {
-        const int t0 = c.start + c.j * kWave;
-        const int bi = t0 / kBlockTokens;
-        const int blk = bi < p.max_blocks ? p.block_table[(long long)c.agent * p.max_blocks + bi] : -1;
-        reachable = blk >= 0 && blk < p.num_blocks;
-        const int layer = p.layer_begin + c.lu / p.kv_heads, kvh = c.lu % p.kv_heads;
-        return (((int64_t)layer * p.num_blocks + (reachable ? blk : 0)) * p.kv_heads + kvh) * kBlockTokens +
-               (t0 % kBlockTokens);
-    };
 
     const int kj = lane % 16, kkb = lane / 16;
     const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / 8;
@@ -294,18 +309,21 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     // tile base (uniform, from the row) + a fixed per-lane offset + a compile-time step offset
     const int k_lane_off = kj * (DK / 8) + kkb * KWPL;
     const int v_lane_off = vo * (DV / 8) + vj;
-    auto load_k = [&](int64_t row0) {
+    // Loads are issued in the order they are consumed (K sets, scale/bias, V steps) and every buffer register is
+    // reloaded for the next tile as soon as its last reader has been issued, so that each spends almost all of
+    // its time in flight.
+    auto load_k_pair = [&](int tp, int64_t row0) { // two 16-token sets
         const uint32_t *tile = p.k_codes + row0 * (DK / 8);
 #pragma unroll
-        for (int ts = 0; ts < KSETS; ++ts)
+        for (int ts = tp; ts < tp + 2; ++ts)
 #pragma unroll
             for (int c = 0; c < KCHUNKS; ++c)
                 kc[ts][c] = load_words<KWPL>(tile + k_lane_off + ts * 16 * (DK / 8) + c * 4 * KWPL);
     };
-    auto load_v = [&](int64_t row0) {
+    auto load_v_quad = [&](int i, int64_t row0) { // four load steps
         const uint32_t *tile = p.v_codes + row0 * (DV / 8);
 #pragma unroll
-        for (int i = 0; i < VSTEPS; ++i) vc[i] = tile[v_lane_off + i * VTPS * (DV / 8)];
+        for (int k = i; k < i + 4; ++k) vc[k] = tile[v_lane_off + k * VTPS * (DV / 8)];
     };
     auto load_params = [&](int64_t row0) {
         ks_bits = load_groups<GK>(p.k_scale + row0 * GK + lane * GK);
@@ -320,27 +338,34 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                           // the end (their codes sit 4 bits higher)
     float m_run[NREP], l_run[NREP], pb[NREP][GV]; // l_run, pb: this lane's tokens only
 
-    bool reachable = false, reachable_next = false;
-    int64_t row0 = tile_row(cur, reachable);
+    const int64_t row0 = cur.row;
     // same issue order as inside the loop (K codes first), pinned so that the wait for the K codes never
     // covers the loads issued after them
-    load_k(row0);
-    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int tp = 0; tp < KSETS; tp += 2) {
+        load_k_pair(tp, row0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     load_params(row0);
-    load_v(row0);
     __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < VSTEPS; i += 4) {
+        load_v_quad(i, row0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     bool unit_begins = true; // the wave's first tile, or tile 0 of a unit
+    int64_t unit0 = 0;
     for (int x = x0; x < x1; ++x) {
         const bool last_of_wave = x + 1 >= x1;
-        const Cursor nxt = last_of_wave ? cur : advance(cur);
-        reachable_next = reachable;
-        const int64_t row0_next = last_of_wave ? row0 : tile_row(nxt, reachable_next);
+        Cursor nxt = cur;
+        if (!last_of_wave) step(nxt); // the wave's last tile re-reads itself: a valid address, the data is ignored
+        const int64_t row0_next = nxt.row;
         const bool unit_ends = last_of_wave || nxt.j == 0;
-        const int64_t unit0 = ((int64_t)(cur.lu / p.kv_heads) * p.num_agents + cur.agent) * p.q_heads +
-                              (int64_t)(cur.lu % p.kv_heads) * NREP; // first of this unit's NREP query heads
 
         if (unit_begins) {
+            // first of this unit's NREP query heads
+            unit0 = ((int64_t)cur.li * p.num_agents + cur.agent) * p.q_heads + (int64_t)cur.kvh * NREP;
             // ---- new unit: its query heads.  Query operand of the matrix core, one per (chunk, word): row
             // i = lane % 16 stands for query head i % NREP and group-in-chunk (i / NREP) % KGPC; the lane holds
             // the 8 dims of its k-block in the order unpack_codes emits codes (0,4,1,5,2,6,3,7), odd dims divided
@@ -428,14 +453,12 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                         for (int e = 0; e < kRegs; ++e) dst[e] = d[ts][c][e];
                     }
             }
+            load_k_pair(tp, row0_next); // these registers are free again: the next tile's codes start travelling
         }
-        load_k(row0_next); // the next tile's K codes travel while this tile finishes
         wave_lds_sync();
 
         // ---- the lane that owns token `lane`: finish its scores, online softmax, publish p*s
-        const int t0 = cur.start + cur.j * kWave;
-        const int first = (p.window > 0 && cur.n > p.window) ? cur.n - p.window : 0;
-        const bool tok_valid = reachable && (t0 + lane >= first) && (t0 + lane < cur.n);
+        const bool tok_valid = cur.reachable && (cur.t0 + lane >= cur.first) && (cur.t0 + lane < cur.n);
         float ks[GK], kb[GK], vs[GV], vb[GV];
 #pragma unroll
         for (int g = 0; g < GK; ++g) {
@@ -447,6 +470,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
             vs[g] = group_value<GV>(vs_bits, g);
             vb[g] = group_value<GV>(vb_bits, g);
         }
+        load_params(row0_next);
         float alpha[NREP];
 #pragma unroll
         for (int r = 0; r < NREP; ++r) {
@@ -499,9 +523,8 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                     acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[h], hi, acc[h][2 * by + 1], 0, 0, 0);
                 }
             }
+            load_v_quad(i, row0_next);
         }
-        load_params(row0_next);
-        load_v(row0_next);
         wave_lds_sync(); // the next tile (or the reduction below) overwrites part / ps
 
         if (unit_ends) {
@@ -523,7 +546,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                 }
             }
             wave_lds_sync();
-            const int unit_first_tile = cur.lu * TT + tpre[cur.agent];
+            const int unit_first_tile = (cur.li * p.kv_heads + cur.kvh) * TT + tpre[cur.agent];
             const int slot = gw - unit_first_tile / per;
 #pragma unroll
             for (int r = 0; r < NREP; ++r) {
@@ -545,8 +568,6 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         }
         unit_begins = unit_ends;
         cur = nxt;
-        row0 = row0_next;
-        reachable = reachable_next;
     }
 }
 

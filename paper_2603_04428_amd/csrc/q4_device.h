@@ -46,12 +46,6 @@ __device__ __forceinline__ CodePairs unpack_codes(uint32_t w)
     return p;
 }
 
-// acc + a.x*b.x + a.y*b.y with a binary32 accumulator (v_dot2_f32_f16)
-__device__ __forceinline__ float dot2(half2_t a, half2_t b, float acc)
-{
-    return __builtin_amdgcn_fdot2(a, b, acc, false);
-}
-
 // Orders LDS traffic between the lanes of one wavefront: what lanes wrote before is visible to
 // every lane after.  Waves of a workgroup that do not share LDS regions need nothing stronger.
 __device__ __forceinline__ void wave_lds_sync()
