@@ -179,6 +179,7 @@ size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents,
         fail(Q4KV_EINVAL, "bad counts");
         return 0;
     }
+    if (q_len > 1) return 0; // the chunk kernel keeps everything on chip
     const int st = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
     const int64_t slots = slots_per_unit(max_seq_len, st);
     const int64_t units = (int64_t)num_layers_in_call * num_agents * q_len * spec->num_q_heads;
@@ -211,8 +212,6 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     if (!q || !out || !block_table || !seq_len) return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(q) || !aligned16(out)) return fail(Q4KV_EINVAL, "q and out must be 16-byte aligned");
     const int layers = layer_end - layer_begin;
-    if ((int64_t)num_agents * spec->num_kv_heads > 65535 || layers > 65535)
-        return fail(Q4KV_ESHAPE, "num_agents*num_kv_heads and layers per call must be <= 65535");
 
     q4kv::AttentionArgs a;
     a.spec = *spec;
@@ -234,7 +233,14 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     a.layers_in_call = layers;
     a.sm_scale = sm_scale;
 
-    if (q_len != 1) return fail(Q4KV_ESHAPE, "q_len > 1 (chunked append) is not available in this build");
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (q_len > 1) { // chunked append: causal attention of q_len new tokens per agent, no workspace needed
+        if (!q4kv::chunk_supported(*spec))
+            return fail(Q4KV_ESHAPE, "no chunk kernel for k_dim=%d v_dim=%d n_rep=%d alias=%d", spec->k_dim, spec->v_dim,
+                        spec->num_q_heads / spec->num_kv_heads, spec->v_aliases_k);
+        hipError_t e = q4kv::launch_chunk_attention(a, st);
+        return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));
+    }
     if (!q4kv::decode_supported(*spec))
         return fail(Q4KV_ESHAPE, "no decode kernel for k_dim=%d v_dim=%d n_rep=%d alias=%d", spec->k_dim, spec->v_dim,
                     spec->num_q_heads / spec->num_kv_heads, spec->v_aliases_k);
@@ -247,7 +253,6 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents));
     a.part_ml = a.part_acc + units * a.max_slots * spec->v_dim;
 
-    hipStream_t st = (hipStream_t)hip_stream;
     hipError_t e = q4kv::launch_decode_attention(a, st);
     if (e == hipSuccess) e = q4kv::launch_combine(a, st);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));

@@ -41,4 +41,8 @@ size_t decode_plan_ints(int num_agents);
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream);
 
+// true when a chunk (q_len > 1, causal) kernel exists for these head shapes
+bool chunk_supported(const q4kv_spec &spec);
+hipError_t launch_chunk_attention(const AttentionArgs &a, hipStream_t stream);
+
 } // namespace q4kv

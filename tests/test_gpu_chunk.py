@@ -1,0 +1,110 @@
+"""GPU parity of chunked-append attention (q4kv_append, then q4kv_batched_attention with q_len > 1) with the
+CPU oracle.  Tolerance: |gpu - oracle| <= 2e-3 + 2e-3*|oracle| on the binary16 outputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_04428_amd import binding as b
+from paper_2603_04428_amd import synth
+from tests.gpu_util import DEV, gpu_cache, host_cache, oracle_unit
+from tests.util import within_tol
+
+pytestmark = pytest.mark.gpu
+
+
+def assert_close(got, want, what=""):
+    ok, over, worst = within_tol(got, want)
+    assert ok, f"{what}: exceeds 2e-3 abs/rel by {over:.3e} (max abs err {worst:.3e})"
+    assert not np.isnan(got.astype(np.float32)).any()
+
+
+def append_chunk_and_attend(w, window=0):
+    """Cache of seq_lens tokens, then the library appends the chunk and attends; returns (gpu out, pools, table)."""
+    spec, kpool, vpool, table, table_d = gpu_cache(w, tokens=w.seq_lens)       # blocks for cache + chunk are reserved
+    C = w.q_len
+    before = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    for l in range(w.num_layers):
+        k_new = torch.stack([w.k_rows(l, a, n, n + C, DEV) for a, n in enumerate(w.seq_lens)])[None].contiguous()
+        v_new = torch.stack([w.v_rows(l, a, n, n + C, DEV) for a, n in enumerate(w.seq_lens)])[None].contiguous()
+        b.q4kv_append(spec, kpool, vpool, k_new, v_new, table_d, before, l, l + 1)
+    after = torch.tensor(w.final_lens(), dtype=torch.int32, device=DEV)
+    out = b.q4kv_batched_attention(spec, kpool, vpool, w.q_all(DEV), table_d, after, max(w.final_lens()), w.sm_scale,
+                                   window)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), (spec, kpool, vpool, table_d)
+
+
+SHAPES = [
+    # layers, Hq, Hkv, D, cached tokens per agent, chunk length
+    (1, 4, 2, 64, (20, 3), 6),
+    (2, 4, 2, 128, (300, 0, 70), 70),        # an agent with an empty cache; chunk spans two query tiles
+    (1, 8, 2, 128, (250,), 130),             # n_rep 4: 32 positions per query tile
+    (1, 2, 2, 256, (513, 64), 129),          # n_rep 1: 128 positions per tile, ragged last tile
+    (1, 16, 8, 256, (100,), 64),
+    (1, 8, 1, 64, (1000, 40), 33),           # n_rep 8
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_chunk_matches_oracle_small(shape):
+    L, Hq, Hkv, D, lens, C = shape
+    w = synth.small(41, L, Hq, Hkv, D, D, False, lens, q_len=C)
+    got, _ = append_chunk_and_attend(w)
+    ospec, okp, ovp, otable = host_cache(w)                  # cache + chunk, quantized by the oracle
+    want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, w.final_lens(), w.sm_scale)
+    assert_close(got, want, f"{shape}")
+
+
+def test_chunk_rows_equal_decode_steps_and_window():
+    w = synth.small(42, 1, 4, 2, 128, 128, False, (200, 31), q_len=40)
+    got, (spec, kpool, vpool, table_d) = append_chunk_and_attend(w)
+    ospec, okp, ovp, otable = host_cache(w)
+    q = w.q_all(DEV)
+    # row r of the chunk call == a decode call that sees before + r + 1 tokens (same Q4 cache, other kernel)
+    for r in (0, 17, 39):
+        lens = [n + r + 1 for n in w.seq_lens]
+        sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        one = b.q4kv_batched_attention(spec, kpool, vpool, q[:, :, r:r + 1].contiguous(), table_d, sl, max(lens),
+                                       w.sm_scale)
+        torch.cuda.synchronize()
+        assert_close(got[:, :, r], one.cpu().numpy()[:, :, 0].astype(np.float64), f"row {r} vs decode")
+    # sliding windows, also shorter than the chunk
+    for win in (1, 16, 100, 1000):
+        sl = torch.tensor(w.final_lens(), dtype=torch.int32, device=DEV)
+        g = b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, sl, max(w.final_lens()), w.sm_scale, win)
+        torch.cuda.synchronize()
+        want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, w.final_lens(), w.sm_scale, window=win)
+        assert_close(g.cpu().numpy(), want, f"window {win}")
+    # deterministic
+    sl = torch.tensor(w.final_lens(), dtype=torch.int32, device=DEV)
+    again = b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, sl, max(w.final_lens()), w.sm_scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(again.cpu().numpy().view(np.uint16), got.view(np.uint16))
+
+
+def test_poisoned_slots_past_the_chunk_are_never_used():
+    # the last block of every agent is only partly filled; everything else in the pool decodes to NaN
+    w = synth.small(43, 1, 4, 2, 64, 64, False, (130, 255), q_len=10)
+    got, _ = append_chunk_and_attend(w)
+    assert not np.isnan(got.astype(np.float32)).any()
+
+
+def test_config4_one_layer_sampled_rows():
+    """Gemma-3-12B-shaped chunked append at the benchmark's shape (10 agents, ragged 4,096..32,768 cached tokens,
+    512-token chunk), one layer in the test to bound the set-up time; the oracle recomputes chunk rows 0, 255 and
+    511 of a seeded sample of (agent, kv head) units from the generator alone."""
+    full = synth.config(4)
+    w = synth.Workload(full.name + "_layer0", full.seed, 1, full.num_q_heads, full.num_kv_heads, full.k_dim,
+                       full.v_dim, False, full.seq_lens, q_len=full.q_len)
+    got, _ = append_chunk_and_attend(w)
+    assert not np.isnan(got.astype(np.float32)).any()
+    shortest, longest = int(np.argmin(w.seq_lens)), int(np.argmax(w.seq_lens))
+    R = w.n_rep
+    for (a, h) in [(shortest, 0), (longest, 7), (3, 4)]:
+        n = w.final_lens()[a]
+        for r in (0, 255, 511):
+            vis = n - (w.q_len - 1 - r)
+            q = w.q_rows(0, a).numpy()[r:r + 1]
+            want = oracle_unit(w, 0, a, h, vis, q=q)
+            assert_close(got[0, a, r, h * R:(h + 1) * R], want[0], f"agent {a} kv head {h} chunk row {r}")
