@@ -50,6 +50,70 @@ def cpu_baseline(w, layers):
                       "agent_tokens_per_s extrapolates to all layers"}
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix throughput
+
+
+def bench_append(args, torch, b, synth, build_device_cache):
+    """Chunked append (the matrix-core path): per step, q4kv_append of a 512-token chunk for every agent and layer,
+    then causal chunk attention of the 512 new queries over cache + chunk, all 48 layers."""
+    dev = "cuda"
+    w = synth.config(4)
+    spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0, tokens=w.seq_lens)
+    C = w.q_len
+    before = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
+    after = torch.tensor(w.final_lens(), dtype=torch.int32, device=dev)
+    k_new = torch.stack([torch.stack([w.k_rows(l, a, n, n + C, dev) for a, n in enumerate(w.seq_lens)])
+                         for l in range(w.num_layers)])
+    v_new = torch.stack([torch.stack([w.v_rows(l, a, n, n + C, dev) for a, n in enumerate(w.seq_lens)])
+                         for l in range(w.num_layers)])
+    q = w.q_all(dev)
+    out = torch.empty((w.num_layers, w.num_agents, C, w.num_q_heads, w.v_dim), dtype=torch.float16, device=dev)
+    ws = torch.empty(16, dtype=torch.uint8, device=dev)
+    max_len = max(w.final_lens())
+    flops = sum(4.0 * w.num_q_heads * w.k_dim * (C * n + C * (C + 1) / 2) for n in w.seq_lens) * w.num_layers
+    q4_bytes = sum(w.final_lens()) * w.num_layers * w.q4_bytes_per_token_layer()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        b.q4kv_append(spec, kpool, vpool, k_new, v_new, table_d, before)
+        if ev:
+            ev[1].record()
+        b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, after, max_len, w.sm_scale, 0, 0, 0, None, out, ws)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    app = [e[0].elapsed_time(e[1]) for e in events]
+    att = [e[1].elapsed_time(e[2]) for e in events]
+    app_ms, att_ms = sum(app) / len(app), sum(att) / len(att)
+    tflops = flops / (att_ms * 1e-3) / 1e12
+    app_bytes = k_new.numel() * 2 * 2 * (1 + 0.28125)
+    res = {
+        "metric": "Q4 KV chunked-append attention TFLOP/s (% of dense fp16 MFMA peak) + agent-tokens/s",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "q4 codes + f16 scale/bias dequantized to f16, f32 accumulate, f16 out", "data": "synthetic",
+        "config": {"workload": w.name, "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
+                   "kv_heads": w.num_kv_heads, "head_dim": w.k_dim, "seq_lens_before": w.seq_lens, "chunk": C},
+        "agent_tokens_per_s": w.num_agents * C / ((att_ms + app_ms) * 1e-3),
+        "attention_ms": att_ms, "attention_flops": flops, "q4_bytes_if_read_once": q4_bytes,
+        "append_ms": app_ms, "append_GBps": app_bytes / (app_ms * 1e-3) / 1e9,
+        "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "chunk_attention_kernel<256,2>"},
+    }
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +121,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--skip-cpu-baseline", action="store_true", help="for profiler runs: leave the oracle leg out")
     ap.add_argument("--split-tokens", type=int, default=0, help="tokens per split-K work item (0: library default)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (a known-size reference for scaling "
+                         "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--workload", choices=["decode", "append"], default="decode",
+                    help="decode (default): the headline configuration; append: the chunked-append configuration "
+                         "(10 agents, 4,096..32,768 cached tokens, 512-token chunk), reported as TFLOP/s")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (agents would shard across GPUs with no exchange step); "
@@ -68,6 +138,8 @@ def main():
     from paper_2603_04428_amd.workload import build_device_cache
 
     dev = "cuda"
+    if args.workload == "append":
+        return bench_append(args, torch, b, synth, build_device_cache)
     w = synth.config(2)
     spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0)
     q = w.q_all(dev)
@@ -99,6 +171,12 @@ def main():
         if ev:
             ev[3].record()
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
