@@ -38,6 +38,7 @@
 //    codes of two tokens with v_perm and masks nibbles in place, two tokens per register.
 #include "q4_device.h"
 #include "q4kv_internal.h"
+#include "stream_k.h"
 
 namespace q4kv {
 namespace {
@@ -50,23 +51,13 @@ constexpr int kWaves = kThreads / kWave;
 constexpr float kNegBig = -1.0e30f; // "minus infinity" that survives subtraction
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Plan written by plan_kernel into the workspace (int32):
-//   [0] TT = tiles of all agents of one (layer, KV head)   [1] per = tiles per wave   [2] N = total tiles
-//   [4 .. 4+A]        tpre[a]   tile prefix sum over agents (tpre[A] == TT)
-//   [.. +A]           tstart[a] first visible token rounded down to a tile boundary
-//   [.. +A]           nlen[a]   seq_len clamped to [0, max_seq_len]
-constexpr int kPlanHeader = 4;
-
-
 struct DecodeParams {
     const uint32_t *k_codes, *v_codes;
     const uint16_t *k_scale, *k_bias, *v_scale, *v_bias;
     const uint16_t *q;
-    const int32_t *block_table;
-    const int32_t *plan;
+    StreamParams stream;
     float *part_acc, *part_ml;
-    int num_blocks, kv_heads, q_heads, num_agents, max_blocks, window, max_slots;
-    int layer_begin;
+    int q_heads, max_slots;
     float score_scale;             // sm_scale * log2(e): scores are kept in log2 units
 };
 
@@ -181,19 +172,6 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 
 // ---------------------------------------------------------------------------------------------- attention
 
-// Position of a wave in the tile stream; every field is wave-uniform and lives in scalar registers.
-// Everything that needs a division, a wide multiply or a memory lookup is refreshed only where it can
-// change: per unit (unit_row, unit0, first) or per 256-token block (row of the block, reachable).
-struct Cursor {
-    int li, kvh, agent;  // unit: layer in call, KV head, agent
-    int j, tiles;        // tile inside the unit, tiles of the unit
-    int t0;              // first token of the tile
-    int n, first;        // visible tokens of the agent, first visible token (sliding window)
-    int64_t unit_row;    // pool row of (layer, block 0, kv head, slot 0)
-    int64_t row;         // pool row of the tile's first token
-    bool reachable;      // the tile's block id is inside the pool
-};
-
 // DK, DV: head widths (multiples of 64); NREP query heads per KV head.
 //
 // Loads are never predicated: a tile's 64 rows always exist inside its block, so rows past the agent's
@@ -230,8 +208,8 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     const int wave = uniform(tid / kWave);
     const int gw = blockIdx.x * kWaves + wave; // this wave's index in the launch
 
-    const int TT = p.plan[0], per = p.plan[1], N = p.plan[2];
-    const int32_t *tpre = p.plan + kPlanHeader, *tstart = tpre + p.num_agents + 1, *nlen = tstart + p.num_agents;
+    const TileStream ts_(p.stream);
+    const int per = ts_.per, N = ts_.N;
     const long long x_begin = (long long)gw * per;
     if (x_begin >= N) return;
     const int x0 = (int)x_begin;
@@ -243,58 +221,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     const uint2 *ps_q = reinterpret_cast<const uint2 *>(ps_h);            // the same as token quads
     float *qsum_lds = region + (kWaveFloats - NREP * GK);                  // [NREP][GK]
 
-    // ---- cursor helpers.  enter_unit / enter_block do the memory lookups; step() is a handful of scalar adds
-    auto enter_block = [&](Cursor &c) {
-        const int bi = c.t0 / kBlockTokens;
-        const int blk = bi < p.max_blocks ? p.block_table[(long long)c.agent * p.max_blocks + bi] : -1;
-        c.reachable = blk >= 0 && blk < p.num_blocks;
-        // rows of an unreachable block fall back to block 0 and are fully masked
-        c.row = c.unit_row + (int64_t)(c.reachable ? blk : 0) * (p.kv_heads * kBlockTokens) + (c.t0 % kBlockTokens);
-    };
-    auto enter_unit = [&](Cursor &c) {
-        c.tiles = tpre[c.agent + 1] - tpre[c.agent];
-        c.n = nlen[c.agent];
-        c.first = (p.window > 0 && c.n > p.window) ? c.n - p.window : 0;
-        c.unit_row = (((int64_t)(p.layer_begin + c.li) * p.num_blocks) * p.kv_heads + c.kvh) * kBlockTokens;
-    };
-    auto step = [&](Cursor &c) { // to the next tile of the stream (meaningful while it stays below x1)
-        if (++c.j < c.tiles) {
-            c.t0 += kWave;
-            if (c.t0 % kBlockTokens == 0) enter_block(c); else c.row += kWave;
-            return;
-        }
-        do {
-            if (++c.agent >= p.num_agents) {
-                c.agent = 0;
-                if (++c.kvh >= p.kv_heads) {
-                    c.kvh = 0;
-                    ++c.li;
-                }
-            }
-        } while (tpre[c.agent + 1] == tpre[c.agent]);
-        c.j = 0;
-        c.t0 = tstart[c.agent];
-        enter_unit(c);
-        enter_block(c);
-    };
-
-    // ---- where tile x0 lies: unit by binary search over the agents' tile prefix sums
-    Cursor cur;
-    {
-        const int lu = x0 / TT, r = x0 - lu * TT;
-        int lo = 0, hi = p.num_agents - 1; // largest a with tpre[a] <= r and at least one tile
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (tpre[mid] <= r) lo = mid; else hi = mid - 1;
-        }
-        cur.li = lu / p.kv_heads;
-        cur.kvh = lu % p.kv_heads;
-        cur.agent = lo;
-        cur.j = r - tpre[lo];
-        cur.t0 = tstart[lo] + cur.j * kWave;
-        enter_unit(cur);
-        enter_block(cur);
-    }
+    Cursor cur = ts_.locate(x0);
 
     const int kj = lane % 16, kkb = lane / 16;
     const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / 8;
@@ -359,13 +286,13 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     for (int x = x0; x < x1; ++x) {
         const bool last_of_wave = x + 1 >= x1;
         Cursor nxt = cur;
-        if (!last_of_wave) step(nxt); // the wave's last tile re-reads itself: a valid address, the data is ignored
+        if (!last_of_wave) ts_.step(nxt); // the wave's last tile re-reads itself: a valid address, the data is ignored
         const int64_t row0_next = nxt.row;
         const bool unit_ends = last_of_wave || nxt.j == 0;
 
         if (unit_begins) {
             // first of this unit's NREP query heads
-            unit0 = ((int64_t)cur.li * p.num_agents + cur.agent) * p.q_heads + (int64_t)cur.kvh * NREP;
+            unit0 = ((int64_t)cur.li * p.stream.num_agents + cur.agent) * p.q_heads + (int64_t)cur.kvh * NREP;
             // ---- new unit: its query heads.  Query operand of the matrix core, one per (chunk, word): row
             // i = lane % 16 stands for query head i % NREP and group-in-chunk (i / NREP) % KGPC; the lane holds
             // the 8 dims of its k-block in the order unpack_codes emits codes (0,4,1,5,2,6,3,7), odd dims divided
@@ -546,8 +473,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                 }
             }
             wave_lds_sync();
-            const int unit_first_tile = (cur.li * p.kv_heads + cur.kvh) * TT + tpre[cur.agent];
-            const int slot = gw - unit_first_tile / per;
+            const int slot = ts_.slot_of(cur, gw);
 #pragma unroll
             for (int r = 0; r < NREP; ++r) {
                 const int64_t rec = (unit0 + r) * p.max_slots + slot;
@@ -614,12 +540,11 @@ hipError_t launch_decode_t(const AttentionArgs &a, hipStream_t stream)
     DecodeParams p;
     p.k_codes = a.k.codes; p.k_scale = a.k.scale; p.k_bias = a.k.bias;
     p.v_codes = a.v.codes; p.v_scale = a.v.scale; p.v_bias = a.v.bias;
-    p.q = a.q; p.block_table = a.block_table; p.plan = a.plan;
+    p.q = a.q;
+    p.stream = stream_params(a);
     p.part_acc = a.part_acc; p.part_ml = a.part_ml;
-    p.num_blocks = a.k.num_blocks; p.kv_heads = a.spec.num_kv_heads; p.q_heads = a.spec.num_q_heads;
-    p.num_agents = a.num_agents; p.max_blocks = a.max_blocks;
-    p.window = a.window; p.max_slots = a.max_slots;
-    p.layer_begin = a.layer_begin;
+    p.q_heads = a.spec.num_q_heads;
+    p.max_slots = a.max_slots;
     p.score_scale = a.sm_scale * kLog2e;
     hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
@@ -639,6 +564,28 @@ hipError_t launch_decode_d(const AttentionArgs &a, int n_rep, hipStream_t stream
 
 } // namespace
 
+StreamParams stream_params(const AttentionArgs &a)
+{
+    StreamParams s;
+    s.plan = a.plan;
+    s.block_table = a.block_table;
+    s.num_agents = a.num_agents;
+    s.max_blocks = a.max_blocks;
+    s.kv_heads = a.spec.num_kv_heads;
+    s.num_blocks = a.k.num_blocks;
+    s.layer_begin = a.layer_begin;
+    s.window = a.window;
+    return s;
+}
+
+hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream)
+{
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len,
+                       a.window, a.layers_in_call * a.spec.num_kv_heads, a.grid_workgroups * kWaves,
+                       a.split_tokens / kWave, a.plan);
+    return hipGetLastError();
+}
+
 int decode_waves_per_workgroup() { return kWaves; }
 
 size_t decode_plan_ints(int num_agents) { return (size_t)kPlanHeader + 3 * (size_t)num_agents + 1; }
@@ -653,10 +600,7 @@ bool decode_supported(const q4kv_spec &s)
 
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len,
-                       a.window, a.layers_in_call * a.spec.num_kv_heads, a.grid_workgroups * kWaves,
-                       a.split_tokens / kWave, a.plan);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_plan(a, stream);
     if (e != hipSuccess) return e;
     const int n_rep = a.spec.num_q_heads / a.spec.num_kv_heads;
     switch (a.spec.k_dim) {

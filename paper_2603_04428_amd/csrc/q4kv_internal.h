@@ -34,6 +34,10 @@ struct AttentionArgs {
     float *part_ml;             // workspace: [units][max_slots][2]  (running max in log2 units, denominator)
 };
 
+struct StreamParams;
+StreamParams stream_params(const AttentionArgs &a);
+hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream);   // needs grid_workgroups, split_tokens, plan
+
 // true when a decode (q_len == 1) kernel exists for these head shapes
 bool decode_supported(const q4kv_spec &spec);
 int decode_waves_per_workgroup();
