@@ -63,14 +63,16 @@ int compute_units()
     return cached[dev];
 }
 
-int attention_workgroups() { return 2 * compute_units(); }
+// Workgroups of a decode launch: the shared-latent kernel fills a compute unit's LDS with one workgroup,
+// the GQA kernel runs two per compute unit.
+int attention_workgroups(const q4kv_spec &s) { return (q4kv::mla_decode_supported(s) ? 1 : 2) * compute_units(); }
 
 // Smallest token range a wave takes when the caller leaves the choice to the library: about half of an even
 // share of the largest possible job, between one block and 4,096 tokens.
 int pick_split_tokens(const q4kv_spec &s, int num_agents, int max_seq_len, int layers)
 {
     const long long tiles = (long long)layers * s.num_kv_heads * num_agents * ((max_seq_len + 63) / 64);
-    const long long waves = (long long)attention_workgroups() * q4kv::decode_waves_per_workgroup();
+    const long long waves = (long long)attention_workgroups(s) * q4kv::decode_waves_per_workgroup();
     long long blocks = tiles / waves / 2 / 4; // in 256-token blocks
     if (blocks < 1) blocks = 1;
     if (blocks > 16) blocks = 16;
@@ -228,7 +230,7 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     a.window = window;
     a.split_tokens = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, layers);
     a.max_slots = slots_per_unit(max_seq_len, a.split_tokens);
-    a.grid_workgroups = attention_workgroups();
+    a.grid_workgroups = attention_workgroups(*spec);
     a.layer_begin = layer_begin;
     a.layers_in_call = layers;
     a.sm_scale = sm_scale;
@@ -241,7 +243,8 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
         hipError_t e = q4kv::launch_chunk_attention(a, st);
         return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));
     }
-    if (!q4kv::decode_supported(*spec))
+    const bool mla = q4kv::mla_decode_supported(*spec);
+    if (!mla && !q4kv::decode_supported(*spec))
         return fail(Q4KV_ESHAPE, "no decode kernel for k_dim=%d v_dim=%d n_rep=%d alias=%d", spec->k_dim, spec->v_dim,
                     spec->num_q_heads / spec->num_kv_heads, spec->v_aliases_k);
 
@@ -253,7 +256,7 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents));
     a.part_ml = a.part_acc + units * a.max_slots * spec->v_dim;
 
-    hipError_t e = q4kv::launch_decode_attention(a, st);
+    hipError_t e = mla ? q4kv::launch_mla_decode_attention(a, st) : q4kv::launch_decode_attention(a, st);
     if (e == hipSuccess) e = q4kv::launch_combine(a, st);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));
 }

@@ -45,6 +45,11 @@ size_t decode_plan_ints(int num_agents);
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream);
 
+// shared-latent decode (V is a prefix of K, 16 query heads per latent head): plan + attention; the partials are
+// merged by launch_combine like the GQA ones
+bool mla_decode_supported(const q4kv_spec &spec);
+hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t stream);
+
 // true when a chunk (q_len > 1, causal) kernel exists for these head shapes
 bool chunk_supported(const q4kv_spec &spec);
 hipError_t launch_chunk_attention(const AttentionArgs &a, hipStream_t stream);

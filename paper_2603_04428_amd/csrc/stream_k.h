@@ -26,15 +26,18 @@ struct StreamParams {
 // Position of a wave in the tile stream; every field is wave-uniform and lives in scalar registers.
 // Everything that needs a division, a wide multiply or a memory lookup is refreshed only where it can
 // change: per unit (unit_row, first) or per 256-token block (row of the block, reachable).
-struct Cursor {
+// Flag is the type of `reachable`: a kernel picks the one its register allocation fares better with.
+template <typename Flag>
+struct CursorT {
     int li, kvh, agent;  // unit: layer in call, KV head, agent
     int j, tiles;        // tile inside the unit, tiles of the unit
     int t0;              // first token of the tile
     int n, first;        // visible tokens of the agent, first visible token (sliding window)
     int64_t unit_row;    // pool row of (layer, block 0, kv head, slot 0)
     int64_t row;         // pool row of the tile's first token
-    bool reachable;      // the tile's block id is inside the pool
+    Flag reachable;      // the tile's block id is inside the pool
 };
+typedef CursorT<bool> Cursor;
 
 struct TileStream {
     StreamParams sp;
@@ -51,7 +54,8 @@ struct TileStream {
         nlen = tstart + s.num_agents;
     }
 
-    __device__ __forceinline__ void enter_block(Cursor &c) const
+    template <typename C>
+    __device__ __forceinline__ void enter_block(C &c) const
     {
         const int bi = c.t0 / kBlockTokens;
         const int blk = bi < sp.max_blocks ? sp.block_table[(long long)c.agent * sp.max_blocks + bi] : -1;
@@ -60,7 +64,8 @@ struct TileStream {
         c.row = c.unit_row + (int64_t)(c.reachable ? blk : 0) * (sp.kv_heads * kBlockTokens) + (c.t0 % kBlockTokens);
     }
 
-    __device__ __forceinline__ void enter_unit(Cursor &c) const
+    template <typename C>
+    __device__ __forceinline__ void enter_unit(C &c) const
     {
         c.tiles = tpre[c.agent + 1] - tpre[c.agent];
         c.n = nlen[c.agent];
@@ -69,7 +74,8 @@ struct TileStream {
     }
 
     // to the next tile of the stream (meaningful while it stays below the wave's last tile)
-    __device__ __forceinline__ void step(Cursor &c) const
+    template <typename C>
+    __device__ __forceinline__ void step(C &c) const
     {
         if (++c.j < c.tiles) {
             c.t0 += kWave;
@@ -92,9 +98,10 @@ struct TileStream {
     }
 
     // where tile x lies: unit by binary search over the agents' tile prefix sums
-    __device__ __forceinline__ Cursor locate(int x) const
+    template <typename C = Cursor>
+    __device__ __forceinline__ C locate(int x) const
     {
-        Cursor c;
+        C c;
         const int lu = x / TT, r = x - lu * TT;
         int lo = 0, hi = sp.num_agents - 1; // largest a with tpre[a] <= r and at least one tile
         while (lo < hi) {
@@ -112,7 +119,8 @@ struct TileStream {
     }
 
     // index of the partial record that wave `gw` writes for the unit the cursor is in
-    __device__ __forceinline__ int slot_of(const Cursor &c, int gw) const
+    template <typename C>
+    __device__ __forceinline__ int slot_of(const C &c, int gw) const
     {
         const int unit_first_tile = (c.li * sp.kv_heads + c.kvh) * TT + tpre[c.agent];
         return gw - unit_first_tile / per;
