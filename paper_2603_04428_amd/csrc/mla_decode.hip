@@ -115,10 +115,7 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
     constexpr int kLoads = kTileWords / (kWave * 4); // 1 KiB transfers per tile
     constexpr int BTP = GK > 8 ? 12 : 8;    // binary16 slots per token in the token-major bias copy
 
-    // Two tile buffers as two separate objects: the compiler then knows that reads of one never touch the
-    // buffer an in-flight transfer is filling, and does not make them wait for it.
-    __shared__ __attribute__((aligned(16))) uint32_t codes_a[kWaves][kTileWords];
-    __shared__ __attribute__((aligned(16))) uint32_t codes_b[kWaves][kTileWords];
+    __shared__ __attribute__((aligned(16))) uint32_t codes_all[kWaves][2][kTileWords]; // two tile buffers per wave
     // scale and bias of the tile, [32-token half][group][q][e] <-> token 32*half + 4*e + q: one 16-byte read gives
     // a lane the 8 tokens of its contraction slots
     __shared__ __attribute__((aligned(16))) uint16_t sc_all[kWaves][2][GK][4][8];
@@ -137,8 +134,7 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
     const int x0 = (int)x_begin;
     const int x1 = (int)min((long long)N, x_begin + per);
 
-    uint32_t *const buf_a = codes_a[wave];
-    uint32_t *const buf_b = codes_b[wave];
+    uint32_t *const bufs = &codes_all[wave][0][0];
     uint16_t *const sc = &sc_all[wave][0][0][0][0];
     uint16_t *const bg = &bg_all[wave][0][0][0][0];
     uint16_t *const bt = bt_all[wave];
@@ -150,17 +146,31 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
     const int tok_q = lane % 4, tok_e = (lane % 32) / 4, tok_h2 = lane / 32; // where token `lane` sits in sc / bg
     const uint32_t nibble_mask = col < 8 ? 0x0F0F0F0Fu : 0xF0F0F0F0u;
 
-    typedef CursorT<int> Cursor; // an all-int cursor is kept in registers across the two tile bodies
+    typedef CursorT<int> Cursor;
     Cursor cur = ts.locate<Cursor>(x0);
 
     uint32_t sraw[GK], braw[GK]; // scale / bias bits of token `lane` of the tile in flight
 
-    auto issue_tile = [&](const Cursor &c, uint32_t *dst) __attribute__((always_inline)) {
-        const uint32_t *src = p.codes + c.row * W + lane * 4;
+    // Start the transfer of a tile: kLoads instructions move 1 KiB each straight from global memory into LDS
+    // (lane i's 16 bytes land at M0 + offset + 16 i), then the lane's scale and bias loads.  The transfers are
+    // written as asm statements so that the compiler neither tracks them nor makes later LDS reads of the
+    // other buffer wait for them; the tile loop waits for them itself (vmcnt) before it touches the buffer.
+    auto issue_tile = [&](const Cursor &c, int buf) __attribute__((always_inline)) {
+        const uint32_t *src = p.codes + c.row * W; // wave-uniform
+        const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(bufs + buf * kTileWords);
+        const uint32_t lane_off = lane * 16;
 #pragma unroll
-        for (int i = 0; i < kLoads; ++i)
-            __builtin_amdgcn_global_load_lds((global_ptr_t)(src + i * (kWave * 4)), (lds_ptr_t)(dst + i * (kWave * 4)), 16,
-                                             0, 0);
+        for (int i = 0; i < kLoads; i += 4) {
+            const uint32_t *s4k = src + i * (kWave * 4);
+            const uint32_t d4k = dst + i * 1024;
+            asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(s4k), "s"(d4k) : "memory", "m0");
+            if (i + 1 < kLoads)
+                asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" ::"v"(lane_off), "s"(s4k) : "memory");
+            if (i + 2 < kLoads)
+                asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" ::"v"(lane_off), "s"(s4k) : "memory");
+            if (i + 3 < kLoads)
+                asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" ::"v"(lane_off), "s"(s4k) : "memory");
+        }
         const uint16_t *sp = p.scale + (c.row + lane) * GK;
         const uint16_t *bp = p.bias + (c.row + lane) * GK;
 #pragma unroll
@@ -172,53 +182,19 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
 
     half8_t qop[GK][2]; // query operand per (group, word pair member): element order of code_operand, odd elements / 16
     half8_t qsop;       // group sums of q: slots of qk 0 = high parts of groups 0..7, qk 1 = low parts, qk 2 / 3 = groups 8..
-    float4_t acc[GV][4]; // [group][byte M]: rows = (word column, low / high nibble), columns = heads
-    float4_t pbacc;      // rows = groups: sum_t b[t,g] p[h,t]
-    float m_run = kNegBig, l_run = 0.0f; // of head `col`; l_run covers this lane's tokens only
-    int64_t unit0 = 0;
-    bool unit_begins = true;
     int x = x0;
+    int buf = 0;        // tile buffer the current tile arrives in
 
-    auto tile = [&](const uint32_t *cb, uint32_t *cb_next) __attribute__((always_inline)) {
-        const bool last_of_wave = x + 1 >= x1;
-        Cursor nxt = cur;
-        if (!last_of_wave) ts.step(nxt); // the wave's last tile re-reads itself: a valid address, the data is ignored
-        const bool unit_ends = last_of_wave || nxt.j == 0;
-
-        // ---- everything of this tile has landed: codes in `cb`, scale / bias in registers
-        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
-        const int tok = cur.t0 + lane;
-        const bool tok_valid = cur.reachable && tok >= cur.first && tok < cur.n;
+    issue_tile(cur, 0);
+    while (x < x1) {
+        // ---- a unit (or the part of it inside this wave's range) begins: its 16 query heads as operand B of the
+        // score contraction.  Lane (head col, slot qk) holds, for group g and word r, the 8 elements of word
+        // 8g + 2qk + r in the order code_operand emits codes (0,4,1,5,2,6,3,7), odd elements divided by 16
+        // because their codes arrive 16 times larger.
+        const int64_t unit0 =
+            ((int64_t)cur.li * p.stream.num_agents + cur.agent) * p.q_heads + (int64_t)cur.kvh * kHeads;
+        const int slot = ts.slot_of(cur, gw);
         {
-            // rows outside the agent's range may hold anything: their scale and bias become zero so that no NaN
-            // or infinity reaches a matrix operand (codes are nibbles and always finite)
-            uint32_t s[GK], b[BTP];
-#pragma unroll
-            for (int g = 0; g < GK; ++g) {
-                s[g] = tok_valid ? sraw[g] : 0u;
-                b[g] = tok_valid ? braw[g] : 0u;
-            }
-#pragma unroll
-            for (int g = GK; g < BTP; ++g) b[g] = 0u;
-#pragma unroll
-            for (int g = 0; g < GK; ++g) sc[((tok_h2 * GK + g) * 4 + tok_q) * 8 + tok_e] = (uint16_t)s[g];
-#pragma unroll
-            for (int g = 0; g < GV; ++g) bg[((tok_h2 * GV + g) * 4 + tok_q) * 8 + tok_e] = (uint16_t)b[g];
-            uint2 *btw = reinterpret_cast<uint2 *>(bt + lane * BTP);
-#pragma unroll
-            for (int i = 0; i < BTP / 4; ++i)
-                btw[i] = make_uint2(b[4 * i] | (b[4 * i + 1] << 16), b[4 * i + 2] | (b[4 * i + 3] << 16));
-        }
-        // the next tile starts travelling (into the buffer the previous tile was read from)
-        issue_tile(nxt, cb_next);
-        __builtin_amdgcn_sched_barrier(0);
-        wave_lds_sync();
-
-        if (unit_begins) {
-            unit0 = ((int64_t)cur.li * p.stream.num_agents + cur.agent) * p.q_heads + (int64_t)cur.kvh * kHeads;
-            // ---- new unit: the 16 query heads as operand B of the score contraction.  Lane (head col, slot qk)
-            // holds, for group g and word r, the 8 elements of word 8g + 2qk + r in the order code_operand emits
-            // codes (0,4,1,5,2,6,3,7), odd elements divided by 16 because their codes arrive 16 times larger.
             const uint16_t *qrow = p.q + (unit0 + col) * DK + 16 * qk;
             float qs[GK];
 #pragma unroll
@@ -249,53 +225,118 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                 part[e] = (qk & 1) ? (half_t)(v - (float)hi) : hi;
             }
             qsop = half8_t{part[0], part[1], part[2], part[3], part[4], part[5], part[6], part[7]};
-            m_run = kNegBig;
-            l_run = 0.0f;
-            pbacc = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int g = 0; g < GV; ++g)
-#pragma unroll
-                for (int m = 0; m < 4; ++m) acc[g][m] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
         }
-
-        // The accumulators stay in the accumulator registers around the loop: without this tie the compiler
-        // carries them in ordinary registers between tiles and copies all of them forth and back in every tile.
-        asm volatile("" : "+a"(pbacc));
+        float4_t acc[GV][4]; // [group][byte M]: rows = (word column, low / high nibble), columns = heads
+        float4_t pbacc = float4_t{0.0f, 0.0f, 0.0f, 0.0f}; // rows = groups: sum_t b[t,g] p[h,t]
 #pragma unroll
         for (int g = 0; g < GV; ++g)
 #pragma unroll
-            for (int m = 0; m < 4; ++m) asm volatile("" : "+a"(acc[g][m]));
+            for (int m = 0; m < 4; ++m) acc[g][m] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        float m_run = kNegBig, l_run = 0.0f; // of head `col`; l_run covers this lane's tokens only
+        bool first_tile = true, unit_ends;
 
-        // ---- scores of the 64 tokens, four 16-token sets: z[h2][sub][r] is token 32 h2 + 16 sub + 4 r + qk, head col
-        float z[2][2][4];
-        const float c_code = p.score_scale * kCodeScaleA;
+        do { // ---- the tiles of the unit
+            const uint32_t *cb = bufs + buf * kTileWords;
+            const bool last_of_wave = x + 1 >= x1;
+            Cursor nxt = cur;
+            if (!last_of_wave) ts.step(nxt); // the wave's last tile re-reads itself: a valid address, the data is ignored
+            unit_ends = last_of_wave || nxt.j == 0;
+
+            // everything of this tile has landed: codes in `cb`, scale / bias in registers
+            __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+            const int tok = cur.t0 + lane;
+            const bool tok_valid = cur.reachable && tok >= cur.first && tok < cur.n;
+            {
+                // rows outside the agent's range may hold anything: their scale and bias become zero so that no NaN
+                // or infinity reaches a matrix operand (codes are nibbles and always finite)
+                uint32_t s[GK], b[BTP];
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
+                for (int g = 0; g < GK; ++g) {
+                    s[g] = tok_valid ? sraw[g] : 0u;
+                    b[g] = tok_valid ? braw[g] : 0u;
+                }
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
+                for (int g = GK; g < BTP; ++g) b[g] = 0u;
+#pragma unroll
+                for (int g = 0; g < GK; ++g) sc[((tok_h2 * GK + g) * 4 + tok_q) * 8 + tok_e] = (uint16_t)s[g];
+#pragma unroll
+                for (int g = 0; g < GV; ++g) bg[((tok_h2 * GV + g) * 4 + tok_q) * 8 + tok_e] = (uint16_t)b[g];
+                uint2 *btw = reinterpret_cast<uint2 *>(bt + lane * BTP);
+#pragma unroll
+                for (int i = 0; i < BTP / 4; ++i)
+                    btw[i] = make_uint2(b[4 * i] | (b[4 * i + 1] << 16), b[4 * i + 2] | (b[4 * i + 3] << 16));
+            }
+            // the next tile starts travelling (into the buffer the previous tile was read from)
+            issue_tile(nxt, buf ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+            wave_lds_sync();
+
+            // LDS reads are issued one step ahead of their use (the next 16-token set, the next value group) and
+            // fenced so that they stay there: with one wave per SIMD nothing else would hide their latency.
+            struct SetIn {   // code words 8g + 2qk, 8g + 2qk + 1 of this lane's row of a 16-token set
+                uint2 w[GK];
+            };
+            auto load_set = [&](int h2, int sub) __attribute__((always_inline)) {
+                SetIn in;
                 const int t_row = 32 * h2 + 16 * sub + trow; // this lane's A row
-                // bias term: A = b[t][.] (slots as in qsop), B = group sums of q
-                const uint16_t *btp = bt + t_row * BTP + ((GK > 8 && qk >= 2) ? 8 : 0);
+#pragma unroll
+                for (int g = 0; g < GK; ++g) in.w[g] = *reinterpret_cast<const uint2 *>(cb + t_row * W + 8 * g + 2 * qk);
+                return in;
+            };
+            struct GroupIn {    // operands of one (32-token half, value group) step
+                uint32_t w[8];  // word column 8g + col % 8 of tokens 32 h2 + 4 e + qk
+                uint4 s8;       // their scales
+            };
+            auto load_group = [&](int h2, int g) __attribute__((always_inline)) {
+                GroupIn in;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) in.w[e] = cb[(32 * h2 + 4 * e + qk) * W + 8 * g + (col % 8)];
+                in.s8 = *reinterpret_cast<const uint4 *>(sc + ((h2 * GK + g) * 4 + qk) * 8);
+                return in;
+            };
+
+            // ---- scores of the 64 tokens, four 16-token sets: z[h2][sub][r] is token 32 h2 + 16 sub + 4 r + qk, head col
+            float z[2][2][4];
+            const float c_code = p.score_scale * kCodeScaleA;
+            const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+            SetIn set_in = load_set(0, 0);
+            GroupIn grp_in;
+#pragma unroll
+            for (int set = 0; set < 4; ++set) {
+                const int h2 = set / 2, sub = set % 2;
+                SetIn set_next;
+                if (set < 3) set_next = load_set((set + 1) / 2, (set + 1) % 2);
+                else grp_in = load_group(0, 0);
+                // scale of the four tokens this lane gets results for and the bias row (slots as in qsop): needed
+                // only behind the matrix instructions, which hide these reads
+                uint2 s4[GK];
+#pragma unroll
+                for (int g = 0; g < GK; ++g)
+                    s4[g] = *reinterpret_cast<const uint2 *>(sc + ((h2 * GK + g) * 4 + qk) * 8 + 4 * sub);
+                const uint16_t *btp = bt + (32 * h2 + 16 * sub + trow) * BTP + ((GK > 8 && qk >= 2) ? 8 : 0);
                 uint2 b0 = *reinterpret_cast<const uint2 *>(btp);
                 uint2 b1 = *reinterpret_cast<const uint2 *>(btp + 4);
+                __builtin_amdgcn_sched_barrier(0);
                 if (qk >= 2) {
                     b1 = make_uint2(0u, 0u);
                     if (GK <= 8) b0 = make_uint2(0u, 0u);
                 }
-                const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+                float4_t d[GK];
+#pragma unroll
+                for (int g = 0; g < GK; ++g) {
+                    d[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(set_in.w[g].x), qop[g][0], zero, 0, 0, 0);
+                    d[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(set_in.w[g].y), qop[g][1], d[g], 0, 0, 0);
+                }
+                // bias term: A = b[t][.], B = group sums of q
                 const float4_t bterm =
                     __builtin_amdgcn_mfma_f32_16x16x32_f16(words_to_half8(b0.x, b0.y, b1.x, b1.y), qsop, zero, 0, 0, 0);
                 float4_t s_acc = zero;
 #pragma unroll
                 for (int g = 0; g < GK; ++g) {
-                    const uint2 w = *reinterpret_cast<const uint2 *>(cb + t_row * W + 8 * g + 2 * qk);
-                    float4_t d = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(w.x), qop[g][0], zero, 0, 0, 0);
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(w.y), qop[g][1], d, 0, 0, 0);
-                    const uint2 s4 = *reinterpret_cast<const uint2 *>(sc + ((h2 * GK + g) * 4 + qk) * 8 + 4 * sub);
-                    s_acc[0] = fmaf(half_of(s4.x, 0), d[0], s_acc[0]);
-                    s_acc[1] = fmaf(half_of(s4.x, 1), d[1], s_acc[1]);
-                    s_acc[2] = fmaf(half_of(s4.y, 0), d[2], s_acc[2]);
-                    s_acc[3] = fmaf(half_of(s4.y, 1), d[3], s_acc[3]);
+                    s_acc[0] = fmaf(half_of(s4[g].x, 0), d[g][0], s_acc[0]);
+                    s_acc[1] = fmaf(half_of(s4[g].x, 1), d[g][1], s_acc[1]);
+                    s_acc[2] = fmaf(half_of(s4[g].y, 0), d[g][2], s_acc[2]);
+                    s_acc[3] = fmaf(half_of(s4[g].y, 1), d[g][3], s_acc[3]);
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) z[h2][sub][r] = fmaf(s_acc[r], c_code, bterm[r] * p.score_scale);
@@ -303,139 +344,139 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                 // below the branch that follows and keeps every matrix result of the tile alive until then
                 asm volatile("" : "+v"(z[h2][sub][0]), "+v"(z[h2][sub][1]), "+v"(z[h2][sub][2]), "+v"(z[h2][sub][3]));
                 __builtin_amdgcn_sched_barrier(0);
+                if (set < 3) set_in = set_next;
             }
 
-        // ---- online softmax of head col over the tile
-        const bool edge = !(cur.reachable && cur.t0 >= cur.first && cur.t0 + kWave <= cur.n); // wave-uniform
-        if (edge) {
+            // ---- online softmax of head col over the tile.  m_run is the reference the exponentials are taken
+            // against, not the exact running maximum: it moves only when a tile's maximum exceeds it by more than
+            // kSlack (in log2 units), so p <= 2^kSlack and p * s stays far inside binary16 for any binary16 scale,
+            // and the accumulators are rescaled a handful of times per unit instead of in every other tile.
+            constexpr float kSlack = 3.0f;
+            const bool edge = !(cur.reachable && cur.t0 >= cur.first && cur.t0 + kWave <= cur.n); // wave-uniform
+            if (edge) {
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+                    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int t = cur.t0 + 32 * h2 + 16 * sub + 4 * r + qk;
+                            if (!(cur.reachable && t >= cur.first && t < cur.n)) z[h2][sub][r] = kNegBig;
+                        }
+            }
+            float mt = kNegBig;
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) mt = fmaxf(mt, z[h2][sub][r]);
+            mt = xor32_max(xor16_max(mt));
+            const bool moved = mt > m_run + kSlack; // the same in the four lanes of a head
+            const float m_new = moved ? mt : m_run;
+            const float alpha = moved ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;
+            m_run = m_new;
+            float psum = 0.0f;
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int t = cur.t0 + 32 * h2 + 16 * sub + 4 * r + qk;
-                        if (!(cur.reachable && t >= cur.first && t < cur.n)) z[h2][sub][r] = kNegBig;
+                        float pr = __builtin_amdgcn_exp2f(z[h2][sub][r] - m_new);
+                        if (edge && z[h2][sub][r] == kNegBig) pr = 0.0f; // also when the whole tile is masked
+                        z[h2][sub][r] = pr;
+                        psum += pr;
                     }
-        }
-        float mt = kNegBig;
+            l_run = fmaf(l_run, alpha, psum);
+            if (!first_tile && __builtin_amdgcn_ballot_w64(moved) != 0ull) { // accumulators are zero in a unit's first tile
+                // Rare.  The empty asm statements tie the accumulators to the accumulator registers on entry, and
+                // the products are handed back through a matrix instruction with zero operands (0*0 + C = C) whose
+                // result lives there again: on the path that skips this block the accumulators then never move.
+                const half8_t none = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                asm volatile("" : "+a"(pbacc));
+                pbacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(none, none, pbacc * alpha, 0, 0, 0);
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
+                for (int g = 0; g < GV; ++g)
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) mt = fmaxf(mt, z[h2][sub][r]);
-        mt = xor32_max(xor16_max(mt));
-        const float m_new = fmaxf(m_run, mt);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        float psum = 0.0f;
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float pr = __builtin_amdgcn_exp2f(z[h2][sub][r] - m_new);
-                    if (edge && z[h2][sub][r] == kNegBig) pr = 0.0f; // also when the whole tile is masked
-                    z[h2][sub][r] = pr;
-                    psum += pr;
-                }
-        l_run = fmaf(l_run, alpha, psum);
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ull) { // some head's maximum moved
-            // Rare after the first tiles of a unit.  The empty asm statements tie the accumulators to the
-            // accumulator registers on entry, and the products are handed back through a matrix instruction with
-            // zero operands (0*0 + C = C) whose result lives there again: on the path that skips this block the
-            // accumulators then never move.
-            const half8_t none = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-            asm volatile("" : "+a"(pbacc));
-            pbacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(none, none, pbacc * alpha, 0, 0, 0);
-#pragma unroll
-            for (int g = 0; g < GV; ++g)
-#pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    asm volatile("" : "+a"(acc[g][m]));
-                    acc[g][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(none, none, acc[g][m] * alpha, 0, 0, 0);
-                }
-        }
+                    for (int m = 0; m < 4; ++m) {
+                        asm volatile("" : "+a"(acc[g][m]));
+                        acc[g][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(none, none, acc[g][m] * alpha, 0, 0, 0);
+                    }
+            }
 
-        // ---- values: per 32-token half, B = p * s (binary16) of tokens 32 h2 + 4 e + qk, e = 0..7
+            // ---- values: per 32-token half, B = p * s (binary16) of tokens 32 h2 + 4 e + qk, e = 0..7
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-            half2_t p16[4];
-            p16[0] = half2_t{(half_t)z[h2][0][0], (half_t)z[h2][0][1]};
-            p16[1] = half2_t{(half_t)z[h2][0][2], (half_t)z[h2][0][3]};
-            p16[2] = half2_t{(half_t)z[h2][1][0], (half_t)z[h2][1][1]};
-            p16[3] = half2_t{(half_t)z[h2][1][2], (half_t)z[h2][1][3]};
-            const half8_t pop = words_to_half8(half2_to_bits(p16[0]), half2_to_bits(p16[1]), half2_to_bits(p16[2]),
-                                               half2_to_bits(p16[3]));
-            {
+            for (int h2 = 0; h2 < 2; ++h2) {
+                half2_t p16[4];
+                p16[0] = half2_t{(half_t)z[h2][0][0], (half_t)z[h2][0][1]};
+                p16[1] = half2_t{(half_t)z[h2][0][2], (half_t)z[h2][0][3]};
+                p16[2] = half2_t{(half_t)z[h2][1][0], (half_t)z[h2][1][1]};
+                p16[3] = half2_t{(half_t)z[h2][1][2], (half_t)z[h2][1][3]};
+                const half8_t pop = words_to_half8(half2_to_bits(p16[0]), half2_to_bits(p16[1]), half2_to_bits(p16[2]),
+                                                   half2_to_bits(p16[3]));
                 const int g_row = (col % 8) < GV ? (col % 8) : GV - 1; // rows past GV repeat a valid row, unused
                 const uint4 braw4 = *reinterpret_cast<const uint4 *>(bg + ((h2 * GV + g_row) * 4 + qk) * 8);
-                pbacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(words_to_half8(braw4.x, braw4.y, braw4.z, braw4.w), pop,
-                                                               pbacc, 0, 0, 0);
-            }
 #pragma unroll
-            for (int g = 0; g < GV; ++g) {
-                const uint4 s8 = *reinterpret_cast<const uint4 *>(sc + ((h2 * GK + g) * 4 + qk) * 8);
-                const half8_t ps = words_to_half8(half2_to_bits(p16[0] * bits_to_half2(s8.x)),
-                                                  half2_to_bits(p16[1] * bits_to_half2(s8.y)),
-                                                  half2_to_bits(p16[2] * bits_to_half2(s8.z)),
-                                                  half2_to_bits(p16[3] * bits_to_half2(s8.w)));
-                uint32_t wm[8];
+                for (int g = 0; g < GV; ++g) {
+                    GroupIn grp_next;
+                    if (g + 1 < GV) grp_next = load_group(h2, g + 1);
+                    else if (h2 == 0) grp_next = load_group(1, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const half8_t ps = words_to_half8(half2_to_bits(p16[0] * bits_to_half2(grp_in.s8.x)),
+                                                      half2_to_bits(p16[1] * bits_to_half2(grp_in.s8.y)),
+                                                      half2_to_bits(p16[2] * bits_to_half2(grp_in.s8.z)),
+                                                      half2_to_bits(p16[3] * bits_to_half2(grp_in.s8.w)));
+                    uint32_t wm[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) wm[e] = cb[(32 * h2 + 4 * e + qk) * W + 8 * g + (col % 8)] & nibble_mask;
+                    for (int e = 0; e < 8; ++e) wm[e] = grp_in.w[e] & nibble_mask;
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    const uint32_t sel = 0x0C040C00u + m * 0x00010001u; // byte m of two tokens into the low bytes of two halves
-                    const half8_t cop =
-                        words_to_half8(__builtin_amdgcn_perm(wm[1], wm[0], sel), __builtin_amdgcn_perm(wm[3], wm[2], sel),
-                                       __builtin_amdgcn_perm(wm[5], wm[4], sel), __builtin_amdgcn_perm(wm[7], wm[6], sel));
-                    acc[g][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cop, ps, acc[g][m], 0, 0, 0);
+                    for (int m = 0; m < 4; ++m) {
+                        const uint32_t sel = 0x0C040C00u + m * 0x00010001u; // byte m of two tokens into the low bytes of two halves
+                        const half8_t cop =
+                            words_to_half8(__builtin_amdgcn_perm(wm[1], wm[0], sel), __builtin_amdgcn_perm(wm[3], wm[2], sel),
+                                           __builtin_amdgcn_perm(wm[5], wm[4], sel), __builtin_amdgcn_perm(wm[7], wm[6], sel));
+                        acc[g][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cop, ps, acc[g][m], 0, 0, 0);
+                    }
+                    if (g == GV - 1) // bias sums of this half: rows = groups
+                        pbacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(words_to_half8(braw4.x, braw4.y, braw4.z, braw4.w), pop,
+                                                                       pbacc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (g + 1 < GV || h2 == 0) grp_in = grp_next;
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
-        }
-        wave_lds_sync(); // the next tile rewrites sc / bg / bt
+            wave_lds_sync(); // the next tile rewrites sc / bg / bt
+            first_tile = false;
+            cur = nxt;
+            buf ^= 1;
+            ++x;
+        } while (!unit_ends);
 
-        if (unit_ends) {
-            // ---- this wave's share of the unit is complete: one partial per query head, written straight from
-            // the accumulators.  Lane (head col, quad qk) holds rows 4 qk + r of every tile: word column
-            // 8 g + 4 (qk % 2) + r, nibble 2 m + qk / 2; of the bias sums it holds groups 4 (qk % 2) + r.
-            const float l_tot = xor32_sum(xor16_sum(l_run));
-            const bool odd = (qk & 1) != 0;
-            float pb[8];
+        // ---- this wave's share of the unit is complete: one partial per query head, written straight from the
+        // accumulators.  Lane (head col, quad qk) holds rows 4 qk + r of every tile: word column
+        // 8 g + 4 (qk % 2) + r, nibble 2 m + qk / 2; of the bias sums it holds groups 4 (qk % 2) + r.
+        const float l_tot = xor32_sum(xor16_sum(l_run));
+        const bool odd = (qk & 1) != 0;
+        float pb[8];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float other = xor16_other(pbacc[r], odd);
-                pb[r] = odd ? other : pbacc[r];
-                pb[4 + r] = odd ? pbacc[r] : other;
-            }
-            const int slot = ts.slot_of(cur, gw);
-            const int64_t rec = (unit0 + col) * p.max_slots + slot;
-            float *dst = p.part_acc + rec * DV + 8 * (4 * (qk % 2)) + qk / 2;
-            const float unscale = qk >= 2 ? kCodeScaleB : kCodeScaleA;
-#pragma unroll
-            for (int g = 0; g < GV; ++g)
-#pragma unroll
-                for (int m = 0; m < 4; ++m)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) dst[kGroup * g + 8 * r + 2 * m] = fmaf(acc[g][m][r], unscale, pb[g]);
-            if (qk == 0) {
-                p.part_ml[rec * 2] = m_run;
-                p.part_ml[rec * 2 + 1] = l_tot;
-            }
+        for (int r = 0; r < 4; ++r) {
+            const float other = xor16_other(pbacc[r], odd);
+            pb[r] = odd ? other : pbacc[r];
+            pb[4 + r] = odd ? pbacc[r] : other;
         }
-        unit_begins = unit_ends;
-        cur = nxt;
-    };
-
-    issue_tile(cur, buf_a);
-    for (;;) {
-        tile(buf_a, buf_b);
-        if (++x >= x1) break;
-        tile(buf_b, buf_a);
-        if (++x >= x1) break;
+        const int64_t rec = (unit0 + col) * p.max_slots + slot;
+        float *dst = p.part_acc + rec * DV + 8 * (4 * (qk % 2)) + qk / 2;
+        const float unscale = qk >= 2 ? kCodeScaleB : kCodeScaleA;
+#pragma unroll
+        for (int g = 0; g < GV; ++g)
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[kGroup * g + 8 * r + 2 * m] = fmaf(acc[g][m][r], unscale, pb[g]);
+        if (qk == 0) {
+            p.part_ml[rec * 2] = m_run;
+            p.part_ml[rec * 2 + 1] = l_tot;
+        }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70); // the last tile's look-ahead transfer must land before the LDS is released
 }
