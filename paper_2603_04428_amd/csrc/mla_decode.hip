@@ -271,24 +271,34 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
             __builtin_amdgcn_sched_barrier(0);
             wave_lds_sync();
 
-            // LDS reads are issued one step ahead of their use (the next 16-token set, the next value group) and
-            // fenced so that they stay there: with one wave per SIMD nothing else would hide their latency.
-            struct SetIn {   // code words 8g + 2qk, 8g + 2qk + 1 of this lane's row of a 16-token set
-                uint2 w[GK];
+            // LDS reads are issued ahead of their use (one 16-token set, two value groups) and fenced so that
+            // they stay there: with one wave per SIMD nothing else hides their latency.  LDS returns data in
+            // issue order, so a step waits only for its own operands while the later ones are still on their way.
+            struct SetIn {    // operands of one 16-token set of scores
+                uint2 w[GK];  // code words 8g + 2qk, 8g + 2qk + 1 of this lane's row
+                uint2 s4[GK]; // scale of the four tokens this lane gets results for
+                uint2 b0, b1; // bias row (slots as in qsop)
             };
             auto load_set = [&](int h2, int sub) __attribute__((always_inline)) {
                 SetIn in;
                 const int t_row = 32 * h2 + 16 * sub + trow; // this lane's A row
 #pragma unroll
                 for (int g = 0; g < GK; ++g) in.w[g] = *reinterpret_cast<const uint2 *>(cb + t_row * W + 8 * g + 2 * qk);
+#pragma unroll
+                for (int g = 0; g < GK; ++g)
+                    in.s4[g] = *reinterpret_cast<const uint2 *>(sc + ((h2 * GK + g) * 4 + qk) * 8 + 4 * sub);
+                const uint16_t *btp = bt + t_row * BTP + ((GK > 8 && qk >= 2) ? 8 : 0);
+                in.b0 = *reinterpret_cast<const uint2 *>(btp);
+                in.b1 = *reinterpret_cast<const uint2 *>(btp + 4);
                 return in;
             };
             struct GroupIn {    // operands of one (32-token half, value group) step
                 uint32_t w[8];  // word column 8g + col % 8 of tokens 32 h2 + 4 e + qk
                 uint4 s8;       // their scales
             };
-            auto load_group = [&](int h2, int g) __attribute__((always_inline)) {
+            auto load_group = [&](int step) __attribute__((always_inline)) { // step = h2 * GV + g
                 GroupIn in;
+                const int h2 = step / GV, g = step % GV;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) in.w[e] = cb[(32 * h2 + 4 * e + qk) * W + 8 * g + (col % 8)];
                 in.s8 = *reinterpret_cast<const uint4 *>(sc + ((h2 * GK + g) * 4 + qk) * 8);
@@ -300,27 +310,18 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
             const float c_code = p.score_scale * kCodeScaleA;
             const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
             SetIn set_in = load_set(0, 0);
-            GroupIn grp_in;
+            GroupIn grp_in[2]; // a ring of the next two value steps
 #pragma unroll
             for (int set = 0; set < 4; ++set) {
                 const int h2 = set / 2, sub = set % 2;
                 SetIn set_next;
-                if (set < 3) set_next = load_set((set + 1) / 2, (set + 1) % 2);
-                else grp_in = load_group(0, 0);
-                // scale of the four tokens this lane gets results for and the bias row (slots as in qsop): needed
-                // only behind the matrix instructions, which hide these reads
-                uint2 s4[GK];
-#pragma unroll
-                for (int g = 0; g < GK; ++g)
-                    s4[g] = *reinterpret_cast<const uint2 *>(sc + ((h2 * GK + g) * 4 + qk) * 8 + 4 * sub);
-                const uint16_t *btp = bt + (32 * h2 + 16 * sub + trow) * BTP + ((GK > 8 && qk >= 2) ? 8 : 0);
-                uint2 b0 = *reinterpret_cast<const uint2 *>(btp);
-                uint2 b1 = *reinterpret_cast<const uint2 *>(btp + 4);
-                __builtin_amdgcn_sched_barrier(0);
-                if (qk >= 2) {
-                    b1 = make_uint2(0u, 0u);
-                    if (GK <= 8) b0 = make_uint2(0u, 0u);
+                if (set < 3) {
+                    set_next = load_set((set + 1) / 2, (set + 1) % 2);
+                } else {
+                    grp_in[0] = load_group(0);
+                    grp_in[1] = load_group(1);
                 }
+                __builtin_amdgcn_sched_barrier(0);
                 float4_t d[GK];
 #pragma unroll
                 for (int g = 0; g < GK; ++g) {
@@ -328,15 +329,20 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                     d[g] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(set_in.w[g].y), qop[g][1], d[g], 0, 0, 0);
                 }
                 // bias term: A = b[t][.], B = group sums of q
+                uint2 b0 = set_in.b0, b1 = set_in.b1;
+                if (qk >= 2) {
+                    b1 = make_uint2(0u, 0u);
+                    if (GK <= 8) b0 = make_uint2(0u, 0u);
+                }
                 const float4_t bterm =
                     __builtin_amdgcn_mfma_f32_16x16x32_f16(words_to_half8(b0.x, b0.y, b1.x, b1.y), qsop, zero, 0, 0, 0);
                 float4_t s_acc = zero;
 #pragma unroll
                 for (int g = 0; g < GK; ++g) {
-                    s_acc[0] = fmaf(half_of(s4[g].x, 0), d[g][0], s_acc[0]);
-                    s_acc[1] = fmaf(half_of(s4[g].x, 1), d[g][1], s_acc[1]);
-                    s_acc[2] = fmaf(half_of(s4[g].y, 0), d[g][2], s_acc[2]);
-                    s_acc[3] = fmaf(half_of(s4[g].y, 1), d[g][3], s_acc[3]);
+                    s_acc[0] = fmaf(half_of(set_in.s4[g].x, 0), d[g][0], s_acc[0]);
+                    s_acc[1] = fmaf(half_of(set_in.s4[g].x, 1), d[g][1], s_acc[1]);
+                    s_acc[2] = fmaf(half_of(set_in.s4[g].y, 0), d[g][2], s_acc[2]);
+                    s_acc[3] = fmaf(half_of(set_in.s4[g].y, 1), d[g][3], s_acc[3]);
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) z[h2][sub][r] = fmaf(s_acc[r], c_code, bterm[r] * p.score_scale);
@@ -419,17 +425,17 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                 const uint4 braw4 = *reinterpret_cast<const uint4 *>(bg + ((h2 * GV + g_row) * 4 + qk) * 8);
 #pragma unroll
                 for (int g = 0; g < GV; ++g) {
-                    GroupIn grp_next;
-                    if (g + 1 < GV) grp_next = load_group(h2, g + 1);
-                    else if (h2 == 0) grp_next = load_group(1, 0);
+                    const int step = h2 * GV + g;
+                    const GroupIn in = grp_in[step % 2];
+                    if (step + 2 < 2 * GV) grp_in[step % 2] = load_group(step + 2);
                     __builtin_amdgcn_sched_barrier(0);
-                    const half8_t ps = words_to_half8(half2_to_bits(p16[0] * bits_to_half2(grp_in.s8.x)),
-                                                      half2_to_bits(p16[1] * bits_to_half2(grp_in.s8.y)),
-                                                      half2_to_bits(p16[2] * bits_to_half2(grp_in.s8.z)),
-                                                      half2_to_bits(p16[3] * bits_to_half2(grp_in.s8.w)));
+                    const half8_t ps = words_to_half8(half2_to_bits(p16[0] * bits_to_half2(in.s8.x)),
+                                                      half2_to_bits(p16[1] * bits_to_half2(in.s8.y)),
+                                                      half2_to_bits(p16[2] * bits_to_half2(in.s8.z)),
+                                                      half2_to_bits(p16[3] * bits_to_half2(in.s8.w)));
                     uint32_t wm[8];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) wm[e] = grp_in.w[e] & nibble_mask;
+                    for (int e = 0; e < 8; ++e) wm[e] = in.w[e] & nibble_mask;
 #pragma unroll
                     for (int m = 0; m < 4; ++m) {
                         const uint32_t sel = 0x0C040C00u + m * 0x00010001u; // byte m of two tokens into the low bytes of two halves
@@ -442,7 +448,6 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                         pbacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(words_to_half8(braw4.x, braw4.y, braw4.z, braw4.w), pop,
                                                                        pbacc, 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (g + 1 < GV || h2 == 0) grp_in = grp_next;
                 }
             }
             wave_lds_sync(); // the next tile rewrites sc / bg / bt
