@@ -114,6 +114,15 @@ def bench_append(args, torch, b, synth, build_device_cache):
     print(json.dumps(res))
 
 
+def calibration_copy(torch, dev):
+    """One plain device-to-device copy kernel of known size: 1 GiB read + 1 GiB written."""
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_latent(args, torch, b, synth, build_device_cache):
     """Decode over the shared-latent cache (DeepSeek-V2-Lite-shaped: 5 agents x 32,768 tokens x 27 layers, one
     576-wide Q4 row per token read by 16 heads), all layers in one call; reported as HBM GB/s."""
@@ -133,6 +142,8 @@ def bench_latent(args, torch, b, synth, build_device_cache):
     def step():
         b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, seq, max_len, w.sm_scale, 0, split, 0, None, out, ws)
 
+    if args.calibrate_copy:
+        calibration_copy(torch, dev)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -227,11 +238,7 @@ def main():
             ev[3].record()
 
     if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB written
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibration_copy(torch, dev)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
