@@ -497,17 +497,21 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     }
 }
 
-// Merge the partials of one (layer, agent, query head) in slot order: binary32, output binary16.
-__global__ __launch_bounds__(kWave) void combine_kernel(const float *__restrict__ part_acc,
-                                                        const float *__restrict__ part_ml,
-                                                        const int32_t *__restrict__ plan, uint16_t *__restrict__ out,
-                                                        int q_heads, int kv_heads, int num_agents, int v_dim,
-                                                        int max_slots)
+// Merge the partials of every (layer, agent, query head) in slot order: binary32, output binary16.  A thread owns
+// four consecutive output elements of one head (16-byte loads); v_dim / 4 threads share a head.
+__global__ __launch_bounds__(kThreads) void combine_kernel(const float *__restrict__ part_acc,
+                                                           const float *__restrict__ part_ml,
+                                                           const int32_t *__restrict__ plan, uint16_t *__restrict__ out,
+                                                           int q_heads, int kv_heads, int num_agents, int v_dim,
+                                                           int max_slots, long long units)
 {
-    const int64_t unit = blockIdx.x; // (layer in call, agent, query head)
+    const int threads_per_unit = v_dim / 4;
+    const long long unit = (long long)blockIdx.x * (kThreads / threads_per_unit) + threadIdx.x / threads_per_unit;
+    if (unit >= units) return; // (layer in call, agent, query head)
+    const int e = (threadIdx.x % threads_per_unit) * 4;
     const int qh = (int)(unit % q_heads);
     const int agent = (int)((unit / q_heads) % num_agents);
-    const int li = (int)(unit / ((int64_t)q_heads * num_agents));
+    const int li = (int)(unit / ((long long)q_heads * num_agents));
     const int kvh = qh / (q_heads / kv_heads);
     const int TT = plan[0], per = plan[1];
     const int32_t *tpre = plan + kPlanHeader;
@@ -522,16 +526,22 @@ __global__ __launch_bounds__(kWave) void combine_kernel(const float *__restrict_
     for (int s = 0; s < slots; ++s)
         if (ml[2 * s + 1] > 0.0f) m = fmaxf(m, ml[2 * s]);
     float denom = 0.0f;
-    for (int s = 0; s < slots; ++s)
-        if (ml[2 * s + 1] > 0.0f) denom = fmaf(__builtin_amdgcn_exp2f(ml[2 * s] - m), ml[2 * s + 1], denom);
-    const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
-    for (int e = threadIdx.x; e < v_dim; e += kWave) {
-        float o = 0.0f;
-        for (int s = 0; s < slots; ++s)
-            if (ml[2 * s + 1] > 0.0f)
-                o = fmaf(__builtin_amdgcn_exp2f(ml[2 * s] - m), part_acc[(unit * max_slots + s) * v_dim + e], o);
-        out[unit * v_dim + e] = float_to_half_bits(o * inv);
+    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    const float *acc = part_acc + unit * max_slots * v_dim + e;
+    for (int s = 0; s < slots; ++s) {
+        if (!(ml[2 * s + 1] > 0.0f)) continue;
+        const float wgt = __builtin_amdgcn_exp2f(ml[2 * s] - m);
+        denom = fmaf(wgt, ml[2 * s + 1], denom);
+        const float4 a = *reinterpret_cast<const float4 *>(acc + (long long)s * v_dim);
+        o.x = fmaf(wgt, a.x, o.x);
+        o.y = fmaf(wgt, a.y, o.y);
+        o.z = fmaf(wgt, a.z, o.z);
+        o.w = fmaf(wgt, a.w, o.w);
     }
+    const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
+    const uint32_t lo = (uint32_t)float_to_half_bits(o.x * inv) | ((uint32_t)float_to_half_bits(o.y * inv) << 16);
+    const uint32_t hi = (uint32_t)float_to_half_bits(o.z * inv) | ((uint32_t)float_to_half_bits(o.w * inv) << 16);
+    *reinterpret_cast<uint2 *>(out + unit * v_dim + e) = make_uint2(lo, hi);
 }
 
 template <int DK, int DV, int NREP>
@@ -615,8 +625,11 @@ hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream)
 {
     const int64_t units = (int64_t)a.layers_in_call * a.num_agents * a.q_len * a.spec.num_q_heads;
     if (units == 0) return hipSuccess;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)units), dim3(kWave), 0, stream, a.part_acc, a.part_ml, a.plan,
-                       a.out, a.spec.num_q_heads, a.spec.num_kv_heads, a.num_agents, a.spec.v_dim, a.max_slots);
+    const int units_per_block = kThreads / (a.spec.v_dim / 4); // v_dim is a multiple of 64 and at most 1,024 here
+    const int64_t blocks = (units + units_per_block - 1) / units_per_block;
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, a.part_acc, a.part_ml, a.plan,
+                       a.out, a.spec.num_q_heads, a.spec.num_kv_heads, a.num_agents, a.spec.v_dim, a.max_slots,
+                       (long long)units);
     return hipGetLastError();
 }
 
