@@ -10,12 +10,15 @@
 //    positions times the n_rep query heads of the group.  Each wave owns 32 rows.
 //  * KV tiles of 64 tokens are fetched as Q4 (codes + scale/bias, coalesced 16-byte loads, prefetched one
 //    tile ahead into registers), dequantized ONCE per workgroup into LDS as binary16 and reused by all 128
-//    rows: K_hat row-major (dims inside a word stay in the order the nibble masks deliver them; the query
-//    operand uses the same order), V_hat transposed so that the PV contraction finds 4 consecutive tokens in
-//    8 bytes.
+//    rows, both row-major with the dims inside a word in the order the nibble masks deliver them
+//    (0,4,1,5,2,6,3,7): the query operand uses the same order for K_hat, the output store undoes it for V_hat.
 //  * The wave computes S^T = K_hat Q^T (tokens are the M rows), so that the probabilities come out of the
 //    matrix core already in the register layout the second GEMM wants for its B operand (P^T); no shuffle
-//    or LDS round trip between the GEMMs.  O^T = V_hat^T P^T accumulates in binary32.
+//    or LDS round trip between the GEMMs.  O^T = V_hat^T P^T accumulates in binary32; its A operand wants 8
+//    tokens of one dim per lane, which the transposing LDS read (ds_read_b64_tr_b16) delivers straight from the
+//    row-major tile: in a group of 16 lanes, lane 4e + c points at 4 consecutive dims (chunk c) of token e, and
+//    element e of what lane j receives is half j % 4 of the chunk that lane 4e + j / 4 addressed, i.e. dim j of
+//    token e.
 //  * Softmax is online, per query row (= per lane column): scores in binary32, log2 domain.
 //  * The workgroups of one KV head are adjacent in the launch order of ONE XCD, so the 8 query tiles of a
 //    unit stream the same KV tiles through the same L2 at the same time.
@@ -58,24 +61,55 @@ __device__ __forceinline__ half2_t nibbles_hi16(uint32_t w) // 16 * code
     return bits_to_half2((w & 0x00F000F0u) | 0x64006400u) - half2_t{(half_t)1024.0f, (half_t)1024.0f};
 }
 
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4_t *lds_short4_ptr;
+
+// x[i] (op) x[i ^ 16], x[i] (op) x[i ^ 32] without touching LDS
+__device__ __forceinline__ float xor16_max(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+__device__ __forceinline__ float xor32_max(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+}
+__device__ __forceinline__ float xor16_sum(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+__device__ __forceinline__ float xor32_sum(float x)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+
 // D = 256 keeps 128 accumulator registers per lane besides the query operand, so it runs one wave per SIMD
 // (512 registers); narrower heads fit two.
 template <int D, int NREP>
 __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_kernel(ChunkParams p)
 {
     constexpr int G = D / kGroup;
-    constexpr int KPITCH = D + 8;      // halves per K_hat row in LDS (pad: conflict-free 16-byte operand reads)
-    constexpr int VPITCH = kTile + 8;  // halves per V_hat^T row
+    // halves per row of the dequantized tiles in LDS.  K_hat rows are read 16 bytes per lane by 16 rows at a time
+    // (pitch = 16 bytes mod 256), V_hat rows 8 bytes per lane by 4 rows x 32 bytes at a time (pitch = 32 mod 256)
+    constexpr int KPITCH = D + 8;
+    constexpr int VPITCH = D + 16;
     constexpr int QPOS = kRowsWG / NREP; // chunk positions per workgroup
     constexpr int KSTEPS = D / 32;     // k-steps of the QK contraction
     constexpr int ETILES = D / 16;     // 16-row tiles of O^T
     constexpr int WORDS = D / 8;       // code words per row
-    constexpr int KW_PER_THREAD = kTile * WORDS / kThreads;         // K code words a thread dequantizes per tile
-    constexpr int VPAIRS_PER_THREAD = (kTile / 2) * WORDS / kThreads; // (token pair, word column) items per thread
-    static_assert(KW_PER_THREAD % 4 == 0 || KW_PER_THREAD == 2, "K tile split");
+    constexpr int WPT = kTile * WORDS / kThreads; // code words of K (and of V) a thread dequantizes per tile
+    static_assert(WPT == 8 || WPT == 4 || WPT == 2, "tile split");
+    constexpr int THREADS_PER_ROW = WORDS / WPT;  // 4: a thread's words lie inside one quantization group
 
     __shared__ __attribute__((aligned(16))) half_t k_lds[kTile * KPITCH];
-    __shared__ __attribute__((aligned(16))) half_t v_lds[D * VPITCH];
+    __shared__ __attribute__((aligned(16))) half_t v_lds[kTile * VPITCH];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -123,101 +157,86 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
             qop[qi][ks] = half8_t{e01.x, e45.x, e01.y, e45.y, e23.x, e67.x, e23.y, e67.y};
         }
     }
+    // what every row of this wave sees / hides (rows differ along lane % 16): tiles inside [all_first, all_vis)
+    // need no masks
+    int all_vis = min(row_vis[0], row_vis[1]), all_first = max(row_first[0], row_first[1]);
+#pragma unroll
+    for (int s = 1; s < 16; s <<= 1) {
+        all_vis = min(all_vis, __shfl_xor(all_vis, s, kWave));
+        all_first = max(all_first, __shfl_xor(all_first, s, kWave));
+    }
 
-    float4_t o_acc[2][ETILES]; // O^T: [q tile][16-dim tile], lane column = query row, regs = dims 4*kb .. 4*kb+3
+    float4_t o_acc[2][ETILES]; // O^T: [q tile][16-dim tile], lane column = query row, regs = row positions 4*kb .. 4*kb+3
 #pragma unroll
     for (int qi = 0; qi < 2; ++qi)
 #pragma unroll
         for (int et = 0; et < ETILES; ++et) o_acc[qi][et] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    // m_run: the reference the exponentials are taken against.  It moves only when a tile's maximum exceeds it by
+    // more than kSlack (log2 units), so the accumulators are rescaled a few times per row, not once per tile.
+    constexpr float kSlack = 3.0f;
     float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.0f, 0.0f};
 
-    // ---- KV tile staging: raw Q4 in registers one tile ahead
+    // ---- KV tile staging: raw Q4 in registers one tile ahead.  Thread -> token tid / 4 of the tile, WPT consecutive
+    // words (tid % 4) * WPT .. of its K row and of its V row
     const int32_t *table = p.block_table + (int64_t)agent * p.max_blocks;
-    uint32_t kraw[KW_PER_THREAD], vraw[2 * VPAIRS_PER_THREAD];
-    uint32_t ksb[2], vsb[2 * VPAIRS_PER_THREAD][2]; // scale / bias bits of the rows this thread dequantizes
-    // K: thread handles KW_PER_THREAD consecutive words of one token row: token = tid / (WORDS / KW_PER_THREAD)
-    constexpr int K_THREADS_PER_ROW = WORDS / KW_PER_THREAD;
-    const int k_tok = tid / K_THREADS_PER_ROW, k_w0 = (tid % K_THREADS_PER_ROW) * KW_PER_THREAD;
-    const int k_grp = (k_w0 * 8) / kGroup; // the thread's words lie in one group when KW_PER_THREAD <= 8
-    static_assert(KW_PER_THREAD <= 8, "a thread's K words must stay inside one quantization group");
-    // V: item i of this thread: token pair tp = item / WORDS, word column wc = item % WORDS
+    uint32_t kraw[WPT], vraw[WPT];
+    uint32_t ksb[2], vsb[2]; // scale / bias bits of the group this thread dequantizes
+    const int k_tok = tid / THREADS_PER_ROW, k_w0 = (tid % THREADS_PER_ROW) * WPT;
+    const int k_grp = (k_w0 * 8) / kGroup;
     auto tile_row0 = [&](int t0, bool &ok) {
         const int bi = t0 / kBlockTokens;
         const int blk = bi < p.max_blocks ? table[bi] : -1;
         ok = blk >= 0 && blk < p.num_blocks;
         return (((int64_t)layer * p.num_blocks + (ok ? blk : 0)) * p.kv_heads + kvh) * kBlockTokens + (t0 % kBlockTokens);
     };
-    auto load_tile = [&](int t0, bool &ok) {
-        const int64_t row0 = tile_row0(t0, ok);
-        const int64_t krow = row0 + k_tok;
-        if constexpr (KW_PER_THREAD % 4 == 0) {
+    auto load_words = [&](const uint32_t *src, uint32_t (&dst)[WPT]) {
+        if constexpr (WPT % 4 == 0) {
 #pragma unroll
-            for (int i = 0; i < KW_PER_THREAD / 4; ++i) {
-                const uint4 t = *reinterpret_cast<const uint4 *>(p.k_codes + krow * WORDS + k_w0 + 4 * i);
-                kraw[4 * i] = t.x; kraw[4 * i + 1] = t.y; kraw[4 * i + 2] = t.z; kraw[4 * i + 3] = t.w;
+            for (int i = 0; i < WPT / 4; ++i) {
+                const uint4 t = *reinterpret_cast<const uint4 *>(src + 4 * i);
+                dst[4 * i] = t.x; dst[4 * i + 1] = t.y; dst[4 * i + 2] = t.z; dst[4 * i + 3] = t.w;
             }
         } else {
-            const uint2 t = *reinterpret_cast<const uint2 *>(p.k_codes + krow * WORDS + k_w0);
-            kraw[0] = t.x; kraw[1] = t.y;
-        }
-        ksb[0] = p.k_scale[krow * G + k_grp];
-        ksb[1] = p.k_bias[krow * G + k_grp];
-#pragma unroll
-        for (int i = 0; i < VPAIRS_PER_THREAD; ++i) {
-            const int item = tid + i * kThreads, tp = item / WORDS, wc = item % WORDS;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int64_t vrow = row0 + 2 * tp + h;
-                vraw[2 * i + h] = p.v_codes[vrow * WORDS + wc];
-                vsb[2 * i + h][0] = p.v_scale[vrow * G + wc / 8];
-                vsb[2 * i + h][1] = p.v_bias[vrow * G + wc / 8];
-            }
+            const uint2 t = *reinterpret_cast<const uint2 *>(src);
+            dst[0] = t.x; dst[1] = t.y;
         }
     };
-    // dequantize the staged tile into LDS.  Rows of an unreachable block and rows at or past t_end (never
-    // visible, possibly never written) become zeros, so that no stale bit pattern can reach an accumulator.
+    auto load_tile = [&](int t0, bool &ok) {
+        const int64_t row = tile_row0(t0, ok) + k_tok;
+        load_words(p.k_codes + row * WORDS + k_w0, kraw);
+        load_words(p.v_codes + row * WORDS + k_w0, vraw);
+        ksb[0] = p.k_scale[row * G + k_grp];
+        ksb[1] = p.k_bias[row * G + k_grp];
+        vsb[0] = p.v_scale[row * G + k_grp];
+        vsb[1] = p.v_bias[row * G + k_grp];
+    };
+    // dequantize the staged words of one row into LDS.  Rows of an unreachable block and rows at or past t_end
+    // (never visible, possibly never written) become zeros, so that no stale bit pattern can reach an accumulator.
+    auto store_row = [&](half_t *dst, const uint32_t (&raw)[WPT], const uint32_t (&sb)[2], bool ok) {
+        const half_t s = ok ? __builtin_bit_cast(half_t, (uint16_t)sb[0]) : (half_t)0.0f;
+        const half_t b = ok ? __builtin_bit_cast(half_t, (uint16_t)sb[1]) : (half_t)0.0f;
+        const half2_t s2 = {s, s}, b2 = {b, b};
+        const half2_t s16 = s2 * half2_t{(half_t)0.0625f, (half_t)0.0625f};
+#pragma unroll
+        for (int w = 0; w < WPT; ++w) {
+            const uint32_t word = ok ? raw[w] : 0u, w8 = word >> 8;
+            const half2_t v0 = pk_fma(nibbles_lo(word), s2, b2);    // dims 0, 4
+            const half2_t v1 = pk_fma(nibbles_hi16(word), s16, b2); // dims 1, 5
+            const half2_t v2 = pk_fma(nibbles_lo(w8), s2, b2);      // dims 2, 6
+            const half2_t v3 = pk_fma(nibbles_hi16(w8), s16, b2);   // dims 3, 7
+            *reinterpret_cast<uint4 *>(dst + 8 * w) =
+                make_uint4(half2_to_bits(v0), half2_to_bits(v1), half2_to_bits(v2), half2_to_bits(v3));
+        }
+    };
     auto store_tile = [&](int t0, bool ok_tile) {
-        {
-            const bool ok = ok_tile && (t0 + k_tok < t_end);
-            const half_t s = ok ? __builtin_bit_cast(half_t, (uint16_t)ksb[0]) : (half_t)0.0f;
-            const half_t b = ok ? __builtin_bit_cast(half_t, (uint16_t)ksb[1]) : (half_t)0.0f;
-            const half2_t s2 = {s, s}, b2 = {b, b};
-            const half2_t s16 = s2 * half2_t{(half_t)0.0625f, (half_t)0.0625f};
-            half_t *dst = k_lds + k_tok * KPITCH + k_w0 * 8;
-#pragma unroll
-            for (int w = 0; w < KW_PER_THREAD; ++w) {
-                const uint32_t word = ok ? kraw[w] : 0u, w8 = word >> 8;
-                const half2_t v0 = pk_fma(nibbles_lo(word), s2, b2);    // dims 0, 4
-                const half2_t v1 = pk_fma(nibbles_hi16(word), s16, b2); // dims 1, 5
-                const half2_t v2 = pk_fma(nibbles_lo(w8), s2, b2);      // dims 2, 6
-                const half2_t v3 = pk_fma(nibbles_hi16(w8), s16, b2);   // dims 3, 7
-                *reinterpret_cast<uint4 *>(dst + 8 * w) =
-                    make_uint4(half2_to_bits(v0), half2_to_bits(v1), half2_to_bits(v2), half2_to_bits(v3));
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < VPAIRS_PER_THREAD; ++i) {
-            const int item = tid + i * kThreads, tp = item / WORDS, wc = item % WORDS;
-            const bool oka = ok_tile && (t0 + 2 * tp < t_end), okb = ok_tile && (t0 + 2 * tp + 1 < t_end);
-            const half_t sa = oka ? __builtin_bit_cast(half_t, (uint16_t)vsb[2 * i][0]) : (half_t)0.0f;
-            const half_t sb = okb ? __builtin_bit_cast(half_t, (uint16_t)vsb[2 * i + 1][0]) : (half_t)0.0f;
-            const half_t ba = oka ? __builtin_bit_cast(half_t, (uint16_t)vsb[2 * i][1]) : (half_t)0.0f;
-            const half_t bb = okb ? __builtin_bit_cast(half_t, (uint16_t)vsb[2 * i + 1][1]) : (half_t)0.0f;
-            const half2_t s2 = {sa, sb}, b2 = {ba, bb};
-            const half2_t s16 = s2 * half2_t{(half_t)0.0625f, (half_t)0.0625f};
-            const uint32_t wa = vraw[2 * i], wb = vraw[2 * i + 1]; // codes are nibbles: with scale = bias = 0 they vanish
-#pragma unroll
-            for (int by = 0; by < 4; ++by) {
-                // byte `by` of both tokens: dims 2*by (low nibble) and 2*by + 1 (high nibble)
-                const uint32_t pair = __builtin_amdgcn_perm(wb, wa, 0x0C040C00u + by * 0x00010001u);
-                const half2_t lo = pk_fma(nibbles_lo(pair), s2, b2);
-                const half2_t hi = pk_fma(nibbles_hi16(pair), s16, b2);
-                const int e = wc * 8 + 2 * by;
-                *reinterpret_cast<uint32_t *>(v_lds + e * VPITCH + 2 * tp) = half2_to_bits(lo);
-                *reinterpret_cast<uint32_t *>(v_lds + (e + 1) * VPITCH + 2 * tp) = half2_to_bits(hi);
-            }
-        }
+        const bool ok = ok_tile && (t0 + k_tok < t_end);
+        store_row(k_lds + k_tok * KPITCH + k_w0 * 8, kraw, ksb, ok);
+        store_row(v_lds + k_tok * VPITCH + k_w0 * 8, vraw, vsb, ok);
     };
+
+    // transposing read of V_hat: this lane's address inside a tile for (16-dim tile 0, 32-token block 0, first
+    // half): token 4 kb + (lane % 16) / 4, dims 4 (lane % 4) ..
+    const half_t *v_lane = v_lds + (4 * kb + qn / 4) * VPITCH + 4 * (qn % 4);
 
     bool ok_next = false;
     if (t_begin < t_end) load_tile(t_begin, ok_next);
@@ -245,7 +264,10 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
             }
 
         // ---- online softmax per query row (lane column), then P^T in binary16 as the next B operand
+        const bool masked = !(ok_cur && t0 >= all_first && t0 + kTile <= all_vis); // wave-uniform
         half8_t pt[2][kTile / 32]; // [q tile][32-token block]: tokens 4*kb..+3 of both 16-token tiles of the block
+        bool any_moved = false;
+        float alpha[2];
 #pragma unroll
         for (int qi = 0; qi < 2; ++qi) {
             float mx = kNegBig;
@@ -253,69 +275,85 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
             for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int t = t0 + tt * 16 + 4 * kb + e;
-                    const bool vis = ok_cur && t < row_vis[qi] && t >= row_first[qi];
-                    const float z = vis ? st[qi][tt][e] * p.score_scale : kNegBig;
+                    float z = st[qi][tt][e] * p.score_scale;
+                    if (masked) {
+                        const int t = t0 + tt * 16 + 4 * kb + e;
+                        if (!(ok_cur && t < row_vis[qi] && t >= row_first[qi])) z = kNegBig;
+                    }
                     st[qi][tt][e] = z;
                     mx = fmaxf(mx, z);
                 }
             // the row's tokens live in the 4 lanes qn, qn+16, qn+32, qn+48
-            mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-            const float m_new = fmaxf(m_run[qi], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m_run[qi] - m_new);
+            mx = xor32_max(xor16_max(mx));
+            const bool moved = mx > m_run[qi] + kSlack;
+            const float m_new = moved ? mx : m_run[qi];
+            alpha[qi] = moved ? __builtin_amdgcn_exp2f(m_run[qi] - m_new) : 1.0f;
+            any_moved |= moved;
             m_run[qi] = m_new;
             float sum = 0.0f;
 #pragma unroll
             for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float pr = st[qi][tt][e] > 0.5f * kNegBig ? __builtin_amdgcn_exp2f(st[qi][tt][e] - m_new) : 0.0f;
+                    float pr = __builtin_amdgcn_exp2f(st[qi][tt][e] - m_new);
+                    if (masked && !(st[qi][tt][e] > 0.5f * kNegBig)) pr = 0.0f; // also a row with nothing visible yet
                     st[qi][tt][e] = pr;
                     sum += pr;
                 }
-            sum += __shfl_xor(sum, 16, kWave);
-            sum += __shfl_xor(sum, 32, kWave);
-            l_run[qi] = fmaf(l_run[qi], alpha, sum);
-#pragma unroll
-            for (int et = 0; et < ETILES; ++et) o_acc[qi][et] *= alpha;
+            l_run[qi] = fmaf(l_run[qi], alpha[qi], sum); // this lane's tokens only; lanes are added up at the end
 #pragma unroll
             for (int tb = 0; tb < kTile / 32; ++tb)
                 pt[qi][tb] = half8_t{(half_t)st[qi][2 * tb][0], (half_t)st[qi][2 * tb][1], (half_t)st[qi][2 * tb][2],
                                      (half_t)st[qi][2 * tb][3], (half_t)st[qi][2 * tb + 1][0], (half_t)st[qi][2 * tb + 1][1],
                                      (half_t)st[qi][2 * tb + 1][2], (half_t)st[qi][2 * tb + 1][3]};
         }
+        if (__builtin_amdgcn_ballot_w64(any_moved) != 0ull) {
+            // Rare after a row's first tiles.  The empty asm statements tie the accumulators to the accumulator
+            // registers on entry and the products return through a matrix instruction with zero operands
+            // (0*0 + C = C), so that on the path that skips this block they never leave those registers.
+            const half8_t none = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int qi = 0; qi < 2; ++qi)
+#pragma unroll
+                for (int et = 0; et < ETILES; ++et) {
+                    asm volatile("" : "+a"(o_acc[qi][et]));
+                    o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(none, none, o_acc[qi][et] * alpha[qi], 0, 0, 0);
+                }
+        }
 
-        // ---- O^T += V_hat^T P^T : A operand = 8 tokens of one dim in P^T's token order
+        // ---- O^T += V_hat^T P^T : A operand = 8 tokens of one dim in P^T's token order (tokens 4 kb .. + 3 of
+        // both 16-token tiles of a 32-token block), fetched with two transposing reads
 #pragma unroll
         for (int et = 0; et < ETILES; ++et)
 #pragma unroll
             for (int tb = 0; tb < kTile / 32; ++tb) {
-                const half_t *vrow = v_lds + (et * 16 + qn) * VPITCH + tb * 32 + 4 * kb;
-                const uint2 lo = *reinterpret_cast<const uint2 *>(vrow);
-                const uint2 hi = *reinterpret_cast<const uint2 *>(vrow + 16);
-                const half8_t va = __builtin_bit_cast(half8_t, make_uint4(lo.x, lo.y, hi.x, hi.y));
+                const half_t *src = v_lane + tb * 32 * VPITCH + et * 16;
+                const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)src);
+                const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(src + 16 * VPITCH));
+                const half8_t va = __builtin_bit_cast(half8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
                 for (int qi = 0; qi < 2; ++qi)
                     o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pt[qi][tb], o_acc[qi][et], 0, 0, 0);
             }
     }
 
-    // ---- normalise and store: lane column = query row, regs = 4 consecutive dims
+    // ---- normalise and store: lane column = query row, regs = 4 consecutive row positions of V_hat, which hold
+    // dims (0,4,1,5) or (2,6,3,7) of an 8-dim word
 #pragma unroll
     for (int qi = 0; qi < 2; ++qi) {
+        const float l_tot = xor32_sum(xor16_sum(l_run[qi]));
         if (row_pos[qi] >= p.q_len) continue;
         const int r_w = wave * kRowsWave + qi * 16 + qn;
         const int head = kvh * NREP + r_w % NREP;
-        const float inv = l_run[qi] > 0.0f ? 1.0f / l_run[qi] : 0.0f;
+        const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
         uint16_t *dst = p.out + ((q_agent + row_pos[qi]) * p.q_heads + head) * D;
 #pragma unroll
         for (int et = 0; et < ETILES; ++et) {
-            const uint32_t a = (uint32_t)float_to_half_bits(o_acc[qi][et][0] * inv) |
-                               ((uint32_t)float_to_half_bits(o_acc[qi][et][1] * inv) << 16);
-            const uint32_t b = (uint32_t)float_to_half_bits(o_acc[qi][et][2] * inv) |
-                               ((uint32_t)float_to_half_bits(o_acc[qi][et][3] * inv) << 16);
-            *reinterpret_cast<uint2 *>(dst + et * 16 + 4 * kb) = make_uint2(a, b);
+            uint16_t *d8 = dst + et * 16 + 8 * (kb / 2) + 2 * (kb % 2); // the word of 8 dims, dims 0.. or 2..
+            d8[0] = float_to_half_bits(o_acc[qi][et][0] * inv);
+            d8[4] = float_to_half_bits(o_acc[qi][et][1] * inv);
+            d8[1] = float_to_half_bits(o_acc[qi][et][2] * inv);
+            d8[5] = float_to_half_bits(o_acc[qi][et][3] * inv);
         }
     }
 }
