@@ -28,10 +28,7 @@
 namespace q4kv {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
 constexpr int kRowsWG = 128;  // query rows per workgroup
-constexpr int kRowsWave = kRowsWG / kWaves;
 constexpr int kTile = 64;     // KV tokens per tile
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -90,11 +87,15 @@ __device__ __forceinline__ float xor32_sum(float x)
     return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
 }
 
-// D = 256 keeps 128 accumulator registers per lane besides the query operand, so it runs one wave per SIMD
-// (512 registers); narrower heads fit two.
-template <int D, int NREP>
-__global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_kernel(ChunkParams p)
+// QT: 16-row query tiles per wave.  Two tiles halve the LDS operand traffic per matrix instruction; one tile keeps
+// a wave within 256 registers also at D = 256, so that two waves share a SIMD and one wave's dequantization and
+// softmax run under the other's matrix instructions.  The workgroup always owns 128 rows: 128 / (16 QT) waves.
+template <int D, int NREP, int QT>
+__global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attention_kernel(ChunkParams p)
 {
+    constexpr int kRowsWave = 16 * QT;
+    constexpr int kWaves = kRowsWG / kRowsWave;
+    constexpr int kThreads = kWaves * kWave;
     constexpr int G = D / kGroup;
     // halves per row of the dequantized tiles in LDS.  K_hat rows are read 16 bytes per lane by 16 rows at a time
     // (pitch = 16 bytes mod 256), V_hat rows 8 bytes per lane by 4 rows x 32 bytes at a time (pitch = 32 mod 256)
@@ -108,8 +109,9 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
     static_assert(WPT == 8 || WPT == 4 || WPT == 2, "tile split");
     constexpr int THREADS_PER_ROW = WORDS / WPT;  // 4: a thread's words lie inside one quantization group
 
-    __shared__ __attribute__((aligned(16))) half_t k_lds[kTile * KPITCH];
-    __shared__ __attribute__((aligned(16))) half_t v_lds[kTile * VPITCH];
+    // two tiles each: while the waves multiply against one, they dequantize the next into the other
+    __shared__ __attribute__((aligned(16))) half_t k_lds[2][kTile * KPITCH];
+    __shared__ __attribute__((aligned(16))) half_t v_lds[2][kTile * VPITCH];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -136,11 +138,11 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
 
     // ---- this lane's query rows: column n = lane % 16 of the two 16-row tiles of its wave
     const int qn = lane % 16, kb = lane / 16;
-    int row_pos[2], row_vis[2], row_first[2];
-    half8_t qop[2][KSTEPS];
+    int row_pos[QT], row_vis[QT], row_first[QT];
+    half8_t qop[QT][KSTEPS];
     const int64_t q_agent = ((int64_t)li * p.num_agents + agent) * p.q_len;
 #pragma unroll
-    for (int qi = 0; qi < 2; ++qi) {
+    for (int qi = 0; qi < QT; ++qi) {
         const int r_w = wave * kRowsWave + qi * 16 + qn;   // row inside the workgroup
         const int c = pos0 + r_w / NREP, head = kvh * NREP + r_w % NREP;
         row_pos[qi] = c;
@@ -159,29 +161,41 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
     }
     // what every row of this wave sees / hides (rows differ along lane % 16): tiles inside [all_first, all_vis)
     // need no masks
-    int all_vis = min(row_vis[0], row_vis[1]), all_first = max(row_first[0], row_first[1]);
+    int all_vis = row_vis[0], all_first = row_first[0];
+#pragma unroll
+    for (int qi = 1; qi < QT; ++qi) {
+        all_vis = min(all_vis, row_vis[qi]);
+        all_first = max(all_first, row_first[qi]);
+    }
 #pragma unroll
     for (int s = 1; s < 16; s <<= 1) {
         all_vis = min(all_vis, __shfl_xor(all_vis, s, kWave));
         all_first = max(all_first, __shfl_xor(all_first, s, kWave));
     }
 
-    float4_t o_acc[2][ETILES]; // O^T: [q tile][16-dim tile], lane column = query row, regs = row positions 4*kb .. 4*kb+3
+    float4_t o_acc[QT][ETILES]; // O^T: [q tile][16-dim tile], lane column = query row, regs = row positions 4*kb .. 4*kb+3
 #pragma unroll
-    for (int qi = 0; qi < 2; ++qi)
+    for (int qi = 0; qi < QT; ++qi)
 #pragma unroll
         for (int et = 0; et < ETILES; ++et) o_acc[qi][et] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
     // m_run: the reference the exponentials are taken against.  It moves only when a tile's maximum exceeds it by
     // more than kSlack (log2 units), so the accumulators are rescaled a few times per row, not once per tile.
     constexpr float kSlack = 3.0f;
-    float m_run[2] = {kNegBig, kNegBig}, l_run[2] = {0.0f, 0.0f};
+    float m_run[QT], l_run[QT];
+#pragma unroll
+    for (int qi = 0; qi < QT; ++qi) {
+        m_run[qi] = kNegBig;
+        l_run[qi] = 0.0f;
+    }
 
-    // ---- KV tile staging: raw Q4 in registers one tile ahead.  Thread -> token tid / 4 of the tile, WPT consecutive
-    // words (tid % 4) * WPT .. of its K row and of its V row
+    // ---- KV tile staging: raw Q4 in registers one tile ahead.  A thread takes WPT consecutive words of one token's
+    // K row and the same words of its V row
     const int32_t *table = p.block_table + (int64_t)agent * p.max_blocks;
     uint32_t kraw[WPT], vraw[WPT];
     uint32_t ksb[2], vsb[2]; // scale / bias bits of the group this thread dequantizes
-    const int k_tok = tid / THREADS_PER_ROW, k_w0 = (tid % THREADS_PER_ROW) * WPT;
+    // 16 consecutive lanes take 16 consecutive tokens (and the same part of the row): their 16-byte LDS stores then
+    // fall into 16 different bank groups, like the operand reads
+    const int k_tok = (tid % 16) + 16 * (tid / (16 * THREADS_PER_ROW)), k_w0 = ((tid / 16) % THREADS_PER_ROW) * WPT;
     const int k_grp = (k_w0 * 8) / kGroup;
     auto tile_row0 = [&](int t0, bool &ok) {
         const int bi = t0 / kBlockTokens;
@@ -212,64 +226,102 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
     };
     // dequantize the staged words of one row into LDS.  Rows of an unreachable block and rows at or past t_end
     // (never visible, possibly never written) become zeros, so that no stale bit pattern can reach an accumulator.
-    auto store_row = [&](half_t *dst, const uint32_t (&raw)[WPT], const uint32_t (&sb)[2], bool ok) {
+    // Dequantization of the staged rows happens one code word (8 dims, one 16-byte store) at a time, so that the
+    // matrix loops below can take a word between their steps: a wave cannot overlap its own vector and matrix
+    // instructions, but the other wave of its SIMD fills in whenever both streams are mixed rather than phased.
+    struct RowDequant {
+        half2_t s2, s16, b2;
+        bool ok;
+    };
+    auto row_params = [&](const uint32_t (&sb)[2], bool ok) {
+        RowDequant r;
         const half_t s = ok ? __builtin_bit_cast(half_t, (uint16_t)sb[0]) : (half_t)0.0f;
         const half_t b = ok ? __builtin_bit_cast(half_t, (uint16_t)sb[1]) : (half_t)0.0f;
-        const half2_t s2 = {s, s}, b2 = {b, b};
-        const half2_t s16 = s2 * half2_t{(half_t)0.0625f, (half_t)0.0625f};
-#pragma unroll
-        for (int w = 0; w < WPT; ++w) {
-            const uint32_t word = ok ? raw[w] : 0u, w8 = word >> 8;
-            const half2_t v0 = pk_fma(nibbles_lo(word), s2, b2);    // dims 0, 4
-            const half2_t v1 = pk_fma(nibbles_hi16(word), s16, b2); // dims 1, 5
-            const half2_t v2 = pk_fma(nibbles_lo(w8), s2, b2);      // dims 2, 6
-            const half2_t v3 = pk_fma(nibbles_hi16(w8), s16, b2);   // dims 3, 7
-            *reinterpret_cast<uint4 *>(dst + 8 * w) =
-                make_uint4(half2_to_bits(v0), half2_to_bits(v1), half2_to_bits(v2), half2_to_bits(v3));
-        }
+        r.s2 = half2_t{s, s};
+        r.b2 = half2_t{b, b};
+        r.s16 = r.s2 * half2_t{(half_t)0.0625f, (half_t)0.0625f};
+        r.ok = ok;
+        return r;
     };
-    auto store_tile = [&](int t0, bool ok_tile) {
-        const bool ok = ok_tile && (t0 + k_tok < t_end);
-        store_row(k_lds + k_tok * KPITCH + k_w0 * 8, kraw, ksb, ok);
-        store_row(v_lds + k_tok * VPITCH + k_w0 * 8, vraw, vsb, ok);
+    auto store_word = [&](half_t *dst, uint32_t raw, const RowDequant &r) {
+        const uint32_t word = r.ok ? raw : 0u, w8 = word >> 8;
+        const half2_t v0 = pk_fma(nibbles_lo(word), r.s2, r.b2);    // dims 0, 4
+        const half2_t v1 = pk_fma(nibbles_hi16(word), r.s16, r.b2); // dims 1, 5
+        const half2_t v2 = pk_fma(nibbles_lo(w8), r.s2, r.b2);      // dims 2, 6
+        const half2_t v3 = pk_fma(nibbles_hi16(w8), r.s16, r.b2);   // dims 3, 7
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(half2_to_bits(v0), half2_to_bits(v1), half2_to_bits(v2), half2_to_bits(v3));
     };
+    // rows of an unreachable block and rows at or past t_end (never visible, possibly never written) become zeros,
+    // so that no stale bit pattern can reach an accumulator
+    auto row_ok = [&](int t0, bool ok_tile) { return ok_tile && (t0 + k_tok < t_end); };
+    const int k_dst = k_tok * KPITCH + k_w0 * 8, v_dst = k_tok * VPITCH + k_w0 * 8;
 
     // transposing read of V_hat: this lane's address inside a tile for (16-dim tile 0, 32-token block 0, first
     // half): token 4 kb + (lane % 16) / 4, dims 4 (lane % 4) ..
-    const half_t *v_lane = v_lds + (4 * kb + qn / 4) * VPITCH + 4 * (qn % 4);
+    const int v_lane = (4 * kb + qn / 4) * VPITCH + 4 * (qn % 4);
 
-    bool ok_next = false;
-    if (t_begin < t_end) load_tile(t_begin, ok_next);
-    for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
-        __syncthreads(); // every wave is done reading the previous tile
-        store_tile(t0, ok_next);
-        const bool ok_cur = ok_next;
-        if (t0 + kTile < t_end) load_tile(t0 + kTile, ok_next);
-        __syncthreads();
-
-        // ---- S^T = K_hat Q^T : [64 tokens][32 query rows] per wave, binary32
-        float4_t st[2][kTile / 16]; // [q tile][token tile]: lane column = query row, regs = tokens 4*kb .. 4*kb+3
+    // One barrier per tile: tile i is multiplied out of buffer i % 2 while tile i + 1 (already in registers) is
+    // dequantized into the other buffer and tile i + 2 is fetched.
+    bool ok_next = false, ok_cur = false;
+    int buf = 0;
+    const int t_last = t_begin < t_end ? t_begin + (t_end - 1 - t_begin) / kTile * kTile : 0; // start of the last tile
+    if (t_begin < t_end) {
+        load_tile(t_begin, ok_next);
+        const RowDequant kr = row_params(ksb, row_ok(t_begin, ok_next)), vr = row_params(vsb, row_ok(t_begin, ok_next));
 #pragma unroll
-        for (int qi = 0; qi < 2; ++qi)
+        for (int w = 0; w < WPT; ++w) {
+            store_word(k_lds[0] + k_dst + 8 * w, kraw[w], kr);
+            store_word(v_lds[0] + v_dst + 8 * w, vraw[w], vr);
+        }
+        ok_cur = ok_next;
+        if (t_begin + kTile < t_end) load_tile(t_begin + kTile, ok_next);
+    }
+    __syncthreads();
+    for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
+        const half_t *k_cur = k_lds[buf], *v_cur = v_lds[buf];
+
+        // ---- S^T = K_hat Q^T : [64 tokens][16 QT query rows] per wave, binary32.  Step ks multiplies the four
+        // 16-token tiles against dims 32 ks .. 32 ks + 31 (operands fetched one step ahead), then takes its share of
+        // the next tile's K rows: registers -> LDS (other buffer).  Past the last tile that stores zeros into the
+        // idle buffer: straight-line code keeps the mix.
+        const bool ok_this = ok_cur;
+        const bool more = t0 + kTile < t_end;
+        const RowDequant kr = row_params(ksb, row_ok(t0 + kTile, ok_next && more));
+        const RowDequant vr = row_params(vsb, row_ok(t0 + kTile, ok_next && more));
+        float4_t st[QT][kTile / 16]; // [q tile][token tile]: lane column = query row, regs = tokens 4*kb .. 4*kb+3
+#pragma unroll
+        for (int qi = 0; qi < QT; ++qi)
 #pragma unroll
             for (int tt = 0; tt < kTile / 16; ++tt) st[qi][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        half8_t ka[2][kTile / 16];
+        auto load_ka = [&](int ks) {
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks)
+            for (int tt = 0; tt < kTile / 16; ++tt)
+                ka[ks % 2][tt] = *reinterpret_cast<const half8_t *>(k_cur + (tt * 16 + qn) * KPITCH + 32 * ks + 8 * kb);
+        };
+        load_ka(0);
 #pragma unroll
-            for (int tt = 0; tt < kTile / 16; ++tt) {
-                const half8_t ka = *reinterpret_cast<const half8_t *>(k_lds + (tt * 16 + qn) * KPITCH + 32 * ks + 8 * kb);
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            if (ks + 1 < KSTEPS) load_ka(ks + 1);
 #pragma unroll
-                for (int qi = 0; qi < 2; ++qi)
-                    st[qi][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qop[qi][ks], st[qi][tt], 0, 0, 0);
-            }
+            for (int tt = 0; tt < kTile / 16; ++tt)
+#pragma unroll
+                for (int qi = 0; qi < QT; ++qi)
+                    st[qi][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[ks % 2][tt], qop[qi][ks], st[qi][tt], 0, 0, 0);
+            // words of the K row spread evenly over the steps
+#pragma unroll
+            for (int w = 0; w < WPT; ++w)
+                if (w * KSTEPS / WPT == ks) store_word(k_lds[buf ^ 1] + k_dst + 8 * w, kraw[w], kr);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 
         // ---- online softmax per query row (lane column), then P^T in binary16 as the next B operand
-        const bool masked = !(ok_cur && t0 >= all_first && t0 + kTile <= all_vis); // wave-uniform
-        half8_t pt[2][kTile / 32]; // [q tile][32-token block]: tokens 4*kb..+3 of both 16-token tiles of the block
+        const bool masked = !(ok_this && t0 >= all_first && t0 + kTile <= all_vis); // wave-uniform
+        half8_t pt[QT][kTile / 32]; // [q tile][32-token block]: tokens 4*kb..+3 of both 16-token tiles of the block
         bool any_moved = false;
-        float alpha[2];
+        float alpha[QT];
 #pragma unroll
-        for (int qi = 0; qi < 2; ++qi) {
+        for (int qi = 0; qi < QT; ++qi) {
             float mx = kNegBig;
 #pragma unroll
             for (int tt = 0; tt < kTile / 16; ++tt)
@@ -278,7 +330,7 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
                     float z = st[qi][tt][e] * p.score_scale;
                     if (masked) {
                         const int t = t0 + tt * 16 + 4 * kb + e;
-                        if (!(ok_cur && t < row_vis[qi] && t >= row_first[qi])) z = kNegBig;
+                        if (!(ok_this && t < row_vis[qi] && t >= row_first[qi])) z = kNegBig;
                     }
                     st[qi][tt][e] = z;
                     mx = fmaxf(mx, z);
@@ -313,7 +365,7 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
             // (0*0 + C = C), so that on the path that skips this block they never leave those registers.
             const half8_t none = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int qi = 0; qi < 2; ++qi)
+            for (int qi = 0; qi < QT; ++qi)
 #pragma unroll
                 for (int et = 0; et < ETILES; ++et) {
                     asm volatile("" : "+a"(o_acc[qi][et]));
@@ -322,25 +374,42 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
         }
 
         // ---- O^T += V_hat^T P^T : A operand = 8 tokens of one dim in P^T's token order (tokens 4 kb .. + 3 of
-        // both 16-token tiles of a 32-token block), fetched with two transposing reads
-#pragma unroll
-        for (int et = 0; et < ETILES; ++et)
+        // both 16-token tiles of a 32-token block), fetched with two transposing reads one step ahead; the next
+        // tile's V rows are dequantized between the steps
+        half8_t va[2][2]; // [step parity][32-token block]
+        auto load_va = [&](int et) {
 #pragma unroll
             for (int tb = 0; tb < kTile / 32; ++tb) {
-                const half_t *src = v_lane + tb * 32 * VPITCH + et * 16;
+                const half_t *src = v_cur + v_lane + tb * 32 * VPITCH + et * 16;
                 const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)src);
                 const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(src + 16 * VPITCH));
-                const half8_t va = __builtin_bit_cast(half8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-                for (int qi = 0; qi < 2; ++qi)
-                    o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pt[qi][tb], o_acc[qi][et], 0, 0, 0);
+                va[et % 2][tb] = __builtin_bit_cast(half8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
+        };
+        load_va(0);
+#pragma unroll
+        for (int et = 0; et < ETILES; ++et) {
+            if (et + 1 < ETILES) load_va(et + 1);
+#pragma unroll
+            for (int tb = 0; tb < kTile / 32; ++tb)
+#pragma unroll
+                for (int qi = 0; qi < QT; ++qi)
+                    o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[et % 2][tb], pt[qi][tb], o_acc[qi][et], 0, 0, 0);
+#pragma unroll
+            for (int w = 0; w < WPT; ++w)
+                if (w * ETILES / WPT == et) store_word(v_lds[buf ^ 1] + v_dst + 8 * w, vraw[w], vr);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        ok_cur = ok_next;
+        load_tile(min(t0 + 2 * kTile, t_last), ok_next); // past the end: the last tile again, never used
+        __syncthreads(); // every wave is done with this buffer and has filled its part of the other
+        buf ^= 1;
     }
 
     // ---- normalise and store: lane column = query row, regs = 4 consecutive row positions of V_hat, which hold
     // dims (0,4,1,5) or (2,6,3,7) of an 8-dim word
 #pragma unroll
-    for (int qi = 0; qi < 2; ++qi) {
+    for (int qi = 0; qi < QT; ++qi) {
         const float l_tot = xor32_sum(xor16_sum(l_run[qi]));
         if (row_pos[qi] >= p.q_len) continue;
         const int r_w = wave * kRowsWave + qi * 16 + qn;
@@ -361,6 +430,8 @@ __global__ __launch_bounds__(kThreads, (D >= 256 ? 1 : 2)) void chunk_attention_
 template <int D, int NREP>
 hipError_t launch_chunk_t(const AttentionArgs &a, hipStream_t stream)
 {
+    constexpr int QT = D >= 256 ? 1 : 2;
+    constexpr int kThreads = kRowsWG / (16 * QT) * kWave;
     ChunkParams p;
     p.k_codes = a.k.codes; p.k_scale = a.k.scale; p.k_bias = a.k.bias;
     p.v_codes = a.v.codes; p.v_scale = a.v.scale; p.v_bias = a.v.bias;
@@ -377,7 +448,7 @@ hipError_t launch_chunk_t(const AttentionArgs &a, hipStream_t stream)
     const int64_t grid = units_padded * p.q_tiles;
     if (grid <= 0) return hipSuccess;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((chunk_attention_kernel<D, NREP>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((chunk_attention_kernel<D, NREP, QT>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 
