@@ -293,21 +293,25 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         for (int qi = 0; qi < QT; ++qi)
 #pragma unroll
             for (int tt = 0; tt < kTile / 16; ++tt) st[qi][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-        half8_t ka[2][kTile / 16];
+        constexpr int KA_AHEAD = KSTEPS > 2 ? 2 : 1; // steps the operand reads run ahead
+        half8_t ka[KA_AHEAD + 1][kTile / 16];
         auto load_ka = [&](int ks) {
 #pragma unroll
             for (int tt = 0; tt < kTile / 16; ++tt)
-                ka[ks % 2][tt] = *reinterpret_cast<const half8_t *>(k_cur + (tt * 16 + qn) * KPITCH + 32 * ks + 8 * kb);
+                ka[ks % (KA_AHEAD + 1)][tt] =
+                    *reinterpret_cast<const half8_t *>(k_cur + (tt * 16 + qn) * KPITCH + 32 * ks + 8 * kb);
         };
-        load_ka(0);
+#pragma unroll
+        for (int ks = 0; ks < KA_AHEAD; ++ks) load_ka(ks);
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            if (ks + 1 < KSTEPS) load_ka(ks + 1);
+            if (ks + KA_AHEAD < KSTEPS) load_ka(ks + KA_AHEAD);
 #pragma unroll
             for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
                 for (int qi = 0; qi < QT; ++qi)
-                    st[qi][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[ks % 2][tt], qop[qi][ks], st[qi][tt], 0, 0, 0);
+                    st[qi][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[ks % (KA_AHEAD + 1)][tt], qop[qi][ks],
+                                                                        st[qi][tt], 0, 0, 0);
             // words of the K row spread evenly over the steps
 #pragma unroll
             for (int w = 0; w < WPT; ++w)
@@ -348,7 +352,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float pr = __builtin_amdgcn_exp2f(st[qi][tt][e] - m_new);
-                    if (masked && !(st[qi][tt][e] > 0.5f * kNegBig)) pr = 0.0f; // also a row with nothing visible yet
+                    if (masked) pr = st[qi][tt][e] > 0.5f * kNegBig ? pr : 0.0f; // also a row with nothing visible yet
                     st[qi][tt][e] = pr;
                     sum += pr;
                 }
@@ -376,25 +380,27 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         // ---- O^T += V_hat^T P^T : A operand = 8 tokens of one dim in P^T's token order (tokens 4 kb .. + 3 of
         // both 16-token tiles of a 32-token block), fetched with two transposing reads one step ahead; the next
         // tile's V rows are dequantized between the steps
-        half8_t va[2][2]; // [step parity][32-token block]
+        constexpr int VA_AHEAD = 3; // steps the operand reads run ahead
+        half8_t va[VA_AHEAD + 1][2]; // [step in the ring][32-token block]
         auto load_va = [&](int et) {
 #pragma unroll
             for (int tb = 0; tb < kTile / 32; ++tb) {
                 const half_t *src = v_cur + v_lane + tb * 32 * VPITCH + et * 16;
                 const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)src);
                 const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(src + 16 * VPITCH));
-                va[et % 2][tb] = __builtin_bit_cast(half8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                va[et % (VA_AHEAD + 1)][tb] = __builtin_bit_cast(half8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
         };
-        load_va(0);
+#pragma unroll
+        for (int et = 0; et < VA_AHEAD; ++et) load_va(et);
 #pragma unroll
         for (int et = 0; et < ETILES; ++et) {
-            if (et + 1 < ETILES) load_va(et + 1);
+            if (et + VA_AHEAD < ETILES) load_va(et + VA_AHEAD);
 #pragma unroll
             for (int tb = 0; tb < kTile / 32; ++tb)
 #pragma unroll
                 for (int qi = 0; qi < QT; ++qi)
-                    o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[et % 2][tb], pt[qi][tb], o_acc[qi][et], 0, 0, 0);
+                    o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[et % (VA_AHEAD + 1)][tb], pt[qi][tb], o_acc[qi][et], 0, 0, 0);
 #pragma unroll
             for (int w = 0; w < WPT; ++w)
                 if (w * ETILES / WPT == et) store_word(v_lds[buf ^ 1] + v_dst + 8 * w, vraw[w], vr);
