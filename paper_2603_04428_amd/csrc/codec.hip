@@ -13,8 +13,24 @@ namespace q4kv {
 namespace {
 
 constexpr int kThreads = 256;
+#ifndef Q4KV_CODEC_WG_PER_CU
+#define Q4KV_CODEC_WG_PER_CU 8 // measured best for the read+write mix (4, 8, 16, 32 tried)
+#endif
 
 #pragma clang fp contract(off)
+
+// min over the 8 lanes of an octet of both halves of a packed binary16 pair: two quad permutes and a mirror
+// inside each half row, on the vector ALU's data-parallel-primitive lanes
+__device__ __forceinline__ half2_t octet_pk_min(half2_t v)
+{
+    int u = (int)half2_to_bits(v);
+    v = __builtin_elementwise_min(v, bits_to_half2((uint32_t)__builtin_amdgcn_update_dpp(u, u, 0xB1, 0xF, 0xF, false)));  // quad_perm [1,0,3,2]
+    u = (int)half2_to_bits(v);
+    v = __builtin_elementwise_min(v, bits_to_half2((uint32_t)__builtin_amdgcn_update_dpp(u, u, 0x4E, 0xF, 0xF, false)));  // quad_perm [2,3,0,1]
+    u = (int)half2_to_bits(v);
+    v = __builtin_elementwise_min(v, bits_to_half2((uint32_t)__builtin_amdgcn_update_dpp(u, u, 0x141, 0xF, 0xF, false))); // row_half_mirror
+    return v;
+}
 
 // Quantize the 8 elements held by this lane; the 8 lanes of an octet form one group.
 // Returns the packed word; *scale_bits / *bias_bits are the group's stored parameters.
@@ -31,18 +47,14 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
         x[2 * i] = half_bits_to_float(xb[2 * i]);
         x[2 * i + 1] = half_bits_to_float(xb[2 * i + 1]);
     }
-    float mn = x[0], mx = x[0];
-#pragma unroll
-    for (int i = 1; i < 8; ++i) {
-        mn = fminf(mn, x[i]);
-        mx = fmaxf(mx, x[i]);
-    }
-    // octet-wide min / max: partner lanes 7-j, j^2, j^1 (three DPP-able exchanges)
-#pragma unroll
-    for (int off = 4; off >= 1; off >>= 1) {
-        mn = fminf(mn, __shfl_xor(mn, off, 8));
-        mx = fmaxf(mx, __shfl_xor(mx, off, 8));
-    }
+    // min and max of the group in packed binary16 (exact: the inputs are binary16), carried together as
+    // (min, -max) so that one packed minimum per exchange serves both
+    const half2_t p0 = bits_to_half2(wds[0]), p1 = bits_to_half2(wds[1]), p2 = bits_to_half2(wds[2]), p3 = bits_to_half2(wds[3]);
+    const half2_t lo2 = __builtin_elementwise_min(__builtin_elementwise_min(p0, p1), __builtin_elementwise_min(p2, p3));
+    const half2_t hi2 = __builtin_elementwise_max(__builtin_elementwise_max(p0, p1), __builtin_elementwise_max(p2, p3));
+    half2_t mm = {lo2.x < lo2.y ? lo2.x : lo2.y, -(hi2.x > hi2.y ? hi2.x : hi2.y)};
+    mm = octet_pk_min(mm);
+    const float mn = (float)mm.x, mx = -(float)mm.y;
     // The stored bias is the bit pattern of the first minimal element.  Only a zero minimum has two
     // encodings; then the sign of the first zero in the group decides.
     uint16_t bb = float_to_half_bits(mn);
@@ -60,12 +72,35 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
     const float s = half_bits_to_float(sb);
     uint32_t word = 0;
     if (s != 0.0f) {
+        // code = clamp(rint(fl(d / s)), 0, 15) with a correctly rounded binary32 division.  The division is the
+        // expensive part, so the quotient is first approximated as t = d * rcp(s): rcp is within 1 ulp and d / s < 32
+        // here (d <= max - min, and s is (max - min) / 15 rounded to binary16, at worst halved when it is a binary16
+        // subnormal), so |t - fl(d / s)| <= 32 * (2^-23 + 2^-24 + 2^-24) = 2^-17.  rint(t) can differ from
+        // rint(fl(d / s)) only if a half-integer lies within that distance of t; such octets (about one element in
+        // 2^15) redo all eight codes with the true division.  v_cvt_pk_u8_f32 rounds to nearest even and saturates
+        // at 0 (checked on the device); quotients reach 15.5 only in the careful path, which clamps them first.
+        const float inv = __builtin_amdgcn_rcpf(s);
+        float d[8], t[8];
+        // the upper clamp only matters when the stored scale was rounded down a lot (a binary16 subnormal); then too
+        // the lane takes the careful path
+        bool careful = (mx - mn) * inv >= 15.4f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            float r = __builtin_rintf((x[i] - mn) / s); // ties to even
-            r = fminf(fmaxf(r, 0.0f), 15.0f);
-            word |= (uint32_t)r << (4 * i);
+            d[i] = x[i] - mn;
+            t[i] = d[i] * inv;
+            careful |= fabsf(__builtin_amdgcn_fractf(t[i]) - 0.5f) <= 0x1p-16f;
         }
+        if (careful) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t[i] = fminf(d[i] / s, 15.0f);
+        }
+        uint32_t even = 0, odd = 0; // codes 0,2,4,6 and 1,3,5,7 as bytes
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            even = __builtin_amdgcn_cvt_pk_u8_f32(t[2 * i], i, even);
+            odd = __builtin_amdgcn_cvt_pk_u8_f32(t[2 * i + 1], i, odd);
+        }
+        word = even | (odd << 4);
     }
     *scale_bits = sb;
     *bias_bits = bb;
@@ -75,10 +110,12 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
 // rows are addressed through `map`, which turns a source row index into a destination row index
 // (or -1 to skip the row).
 struct FlatRows {
+    static constexpr bool kIdentity = true; // destination group = source group: no row arithmetic at all
     __device__ __forceinline__ int64_t operator()(int64_t row) const { return row; }
 };
 
 struct PagedRows { // source rows [layers_in_call][A][C][H] -> pool rows [layer][block][H][slot]
+    static constexpr bool kIdentity = false;
     const int32_t *block_table;
     const int32_t *seq_len_before;
     int max_blocks, num_agents, chunk_len, heads, layer_begin, num_blocks;
@@ -111,11 +148,14 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
         const uint4 raw = *reinterpret_cast<const uint4 *>(x + grp * kGroup + sub * 8);
         uint16_t sb, bb;
         const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
-        const int64_t row = grp / groups_per_row;
-        const int g = (int)(grp % groups_per_row);
-        const int64_t drow = map(row);
-        if (drow < 0) continue;
-        const int64_t dgrp = drow * groups_per_row + g;
+        int64_t dgrp = grp;
+        if constexpr (!RowMap::kIdentity) {
+            const int64_t row = grp / groups_per_row;
+            const int g = (int)(grp % groups_per_row);
+            const int64_t drow = map(row);
+            if (drow < 0) continue;
+            dgrp = drow * groups_per_row + g;
+        }
         codes[dgrp * 8 + sub] = word;
         if (sub == 0) {
             scale[dgrp] = sb;
@@ -149,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
 int grid_for(int64_t items, int per_block)
 {
     int64_t blocks = (items + per_block - 1) / per_block;
-    const int64_t cap = 256 * 32; // 256 CUs, plenty of resident workgroups each; the kernels grid-stride
+    const int64_t cap = 256 * Q4KV_CODEC_WG_PER_CU; // the kernels grid-stride
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     return (int)blocks;

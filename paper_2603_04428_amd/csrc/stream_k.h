@@ -36,6 +36,8 @@ struct CursorT {
     int64_t unit_row;    // pool row of (layer, block 0, kv head, slot 0)
     int64_t row;         // pool row of the tile's first token
     Flag reachable;      // the tile's block id is inside the pool
+    int blk_ahead;       // table entry of the block after the tile's (-1 past the table): fetched one block early so
+                         // that the lookup is never on the path of the next tile's loads
 };
 typedef CursorT<bool> Cursor;
 
@@ -55,13 +57,31 @@ struct TileStream {
     }
 
     template <typename C>
-    __device__ __forceinline__ void enter_block(C &c) const
+    __device__ __forceinline__ void place_block(C &c, int blk) const
     {
-        const int bi = c.t0 / kBlockTokens;
-        const int blk = bi < sp.max_blocks ? sp.block_table[(long long)c.agent * sp.max_blocks + bi] : -1;
         c.reachable = blk >= 0 && blk < sp.num_blocks;
         // rows of an unreachable block fall back to block 0 and are fully masked
         c.row = c.unit_row + (int64_t)(c.reachable ? blk : 0) * (sp.kv_heads * kBlockTokens) + (c.t0 % kBlockTokens);
+    }
+
+    template <typename C>
+    __device__ __forceinline__ void enter_block(C &c) const
+    {
+        const int bi = c.t0 / kBlockTokens;
+        const int32_t *row = sp.block_table + (long long)c.agent * sp.max_blocks;
+        const int blk = bi < sp.max_blocks ? row[bi] : -1;
+        c.blk_ahead = bi + 1 < sp.max_blocks ? row[bi + 1] : -1;
+        place_block(c, blk);
+    }
+
+    // the same when the tile stream walks from one block of an agent into the next
+    template <typename C>
+    __device__ __forceinline__ void next_block(C &c) const
+    {
+        const int bi = c.t0 / kBlockTokens;
+        const int blk = c.blk_ahead;
+        c.blk_ahead = bi + 1 < sp.max_blocks ? sp.block_table[(long long)c.agent * sp.max_blocks + bi + 1] : -1;
+        place_block(c, blk);
     }
 
     template <typename C>
@@ -79,7 +99,7 @@ struct TileStream {
     {
         if (++c.j < c.tiles) {
             c.t0 += kWave;
-            if (c.t0 % kBlockTokens == 0) enter_block(c); else c.row += kWave;
+            if (c.t0 % kBlockTokens == 0) next_block(c); else c.row += kWave;
             return;
         }
         do {
