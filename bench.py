@@ -274,7 +274,7 @@ def main():
                      "kernel": "decode_attention_kernel<256,256,2> (+ combine_kernel in the same call)"},
     }
     if not args.skip_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, [0, w.num_layers - 1])
+        res["cpu_baseline"] = cpu_baseline(w, [0, w.num_layers // 3, 2 * w.num_layers // 3, w.num_layers - 1])
     print(json.dumps(res))
 
 
