@@ -126,6 +126,19 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
                            int32_t split_tokens, int32_t layer_begin, int32_t layer_end, void *workspace,
                            size_t workspace_bytes, void *hip_stream);
 
+/* Sec. 3.6 (models that interleave global and sliding-window layers): q4kv_batched_attention with one window per
+ * layer of the call instead of a single one.
+ *   window_per_layer  HOST int32 [layer_end - layer_begin], read before the call returns; entry i belongs to layer
+ *                     layer_begin + i; <= 0: global attention on that layer.
+ * At most 128 layers per call (more -> Q4KV_EINVAL; split the layer range).  Everything else, the workspace size
+ * included, is as for q4kv_batched_attention.  On decode the tokens a window hides are never read. */
+int q4kv_batched_attention_windows(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                                   uint16_t *out, const int32_t *block_table, int32_t max_blocks,
+                                   const int32_t *seq_len, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                   float sm_scale, const int32_t *window_per_layer, int32_t split_tokens,
+                                   int32_t layer_begin, int32_t layer_end, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
 /* Bytes of workspace q4kv_batched_attention needs for these arguments (0 on bad arguments). */
 size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
                                       int32_t split_tokens, int32_t num_layers_in_call);

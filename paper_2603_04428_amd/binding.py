@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libq4kv.so")
 
 EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_append", "q4kv_batched_attention",
-           "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_last_error",
+           "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_last_error",
            "q4kv_version"]
 
 
@@ -53,6 +53,9 @@ def lib():
                                   i32, i32, vp]
         l.q4kv_batched_attention.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32, vp,
                                              i32, i32, i32, C.c_float, i32, i32, i32, i32, vp, C.c_size_t, vp]
+        l.q4kv_batched_attention_windows.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp,
+                                                     i32, vp, i32, i32, i32, C.c_float, C.POINTER(i32), i32, i32, i32,
+                                                     vp, C.c_size_t, vp]
         l.q4kv_attention_workspace_bytes.restype = C.c_size_t
         l.q4kv_attention_workspace_bytes.argtypes = [C.POINTER(Spec), i32, i32, i32, i32, i32]
         l.q4kv_default_split_tokens.restype = i32
@@ -166,7 +169,8 @@ def q4kv_attention_workspace_bytes(spec, num_agents, q_len, max_seq_len, split_t
 
 def q4kv_batched_attention(spec, kpool, vpool, q, block_table, seq_len, max_seq_len, sm_scale, window=0,
                            split_tokens=0, layer_begin=0, layer_end=None, out=None, workspace=None):
-    """q: fp16 [layers_in_call][A][q_len][q_heads][k_dim] -> fp16 out of the same leading shape, v_dim wide."""
+    """q: fp16 [layers_in_call][A][q_len][q_heads][k_dim] -> fp16 out of the same leading shape, v_dim wide.
+    window: one int for all layers, or a sequence with one window per layer of the call (q4kv_batched_attention_windows)."""
     layer_end = spec.num_layers if layer_end is None else layer_end
     Lr, A, q_len = q.shape[0], q.shape[1], q.shape[2]
     if out is None:
@@ -176,10 +180,16 @@ def q4kv_batched_attention(spec, kpool, vpool, q, block_table, seq_len, max_seq_
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     kp = kpool.c()
     vp = None if spec.v_aliases_k else vpool.c()
-    _check(lib().q4kv_batched_attention(C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp),
-                                        _dev(q, torch.float16, "q"), _dev(out, torch.float16, "out"),
-                                        _dev(block_table, torch.int32, "block_table"), block_table.shape[1],
-                                        _dev(seq_len, torch.int32, "seq_len"), A, q_len, max_seq_len, float(sm_scale),
-                                        int(window), int(split_tokens), layer_begin, layer_end,
-                                        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()))
+    common = (C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp),
+              _dev(q, torch.float16, "q"), _dev(out, torch.float16, "out"),
+              _dev(block_table, torch.int32, "block_table"), block_table.shape[1],
+              _dev(seq_len, torch.int32, "seq_len"), A, q_len, max_seq_len, float(sm_scale))
+    tail = (int(split_tokens), layer_begin, layer_end, C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream())
+    if isinstance(window, (list, tuple)) or hasattr(window, "__len__"):      # one window per layer of the call (host)
+        if len(window) != layer_end - layer_begin:
+            raise ValueError(f"{len(window)} windows for {layer_end - layer_begin} layers")
+        windows = (C.c_int32 * len(window))(*[int(x) for x in window])
+        _check(lib().q4kv_batched_attention_windows(*common, windows, *tail))
+    else:
+        _check(lib().q4kv_batched_attention(*common, int(window), *tail))
     return out

@@ -85,7 +85,10 @@ int slots_per_unit(int max_seq_len, int split_tokens)
     return (tiles + min_per_wave - 1) / min_per_wave + 1;
 }
 
-size_t plan_bytes(int num_agents) { return (q4kv::decode_plan_ints(num_agents) * sizeof(int32_t) + 255) / 256 * 256; }
+size_t plan_bytes(int num_agents, int layers)
+{
+    return (q4kv::decode_plan_ints(num_agents, layers) * sizeof(int32_t) + 255) / 256 * 256;
+}
 
 } // namespace
 
@@ -185,14 +188,14 @@ size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents,
     const int st = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
     const int64_t slots = slots_per_unit(max_seq_len, st);
     const int64_t units = (int64_t)num_layers_in_call * num_agents * q_len * spec->num_q_heads;
-    return plan_bytes(num_agents) + (size_t)(units * slots * (spec->v_dim + 2) * (int64_t)sizeof(float));
+    return plan_bytes(num_agents, num_layers_in_call) + (size_t)(units * slots * (spec->v_dim + 2) * (int64_t)sizeof(float));
 }
 
-int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
-                           uint16_t *out, const int32_t *block_table, int32_t max_blocks, const int32_t *seq_len,
-                           int32_t num_agents, int32_t q_len, int32_t max_seq_len, float sm_scale, int32_t window,
-                           int32_t split_tokens, int32_t layer_begin, int32_t layer_end, void *workspace,
-                           size_t workspace_bytes, void *hip_stream)
+static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                            uint16_t *out, const int32_t *block_table, int32_t max_blocks, const int32_t *seq_len,
+                            int32_t num_agents, int32_t q_len, int32_t max_seq_len, float sm_scale, int32_t window,
+                            const int32_t *layer_window, int32_t split_tokens, int32_t layer_begin, int32_t layer_end,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     int rc = check_spec(spec);
     if (rc) return rc;
@@ -228,6 +231,7 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
     a.q_len = q_len;
     a.max_seq_len = max_seq_len;
     a.window = window;
+    a.layer_window = layer_window;
     a.split_tokens = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, layers);
     a.max_slots = slots_per_unit(max_seq_len, a.split_tokens);
     a.grid_workgroups = attention_workgroups(*spec);
@@ -253,12 +257,37 @@ int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv
         return fail(Q4KV_EWORKSPACE, "workspace needs %zu bytes (16-byte aligned), got %zu", need, workspace_bytes);
     const int64_t units = (int64_t)layers * num_agents * q_len * spec->num_q_heads;
     a.plan = static_cast<int32_t *>(workspace);
-    a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents));
+    a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents, layers));
     a.part_ml = a.part_acc + units * a.max_slots * spec->v_dim;
 
     hipError_t e = mla ? q4kv::launch_mla_decode_attention(a, st) : q4kv::launch_decode_attention(a, st);
     if (e == hipSuccess) e = q4kv::launch_combine(a, st);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));
+}
+
+int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                           uint16_t *out, const int32_t *block_table, int32_t max_blocks, const int32_t *seq_len,
+                           int32_t num_agents, int32_t q_len, int32_t max_seq_len, float sm_scale, int32_t window,
+                           int32_t split_tokens, int32_t layer_begin, int32_t layer_end, void *workspace,
+                           size_t workspace_bytes, void *hip_stream)
+{
+    return attention_common(spec, k, v, q, out, block_table, max_blocks, seq_len, num_agents, q_len, max_seq_len, sm_scale,
+                            window, nullptr, split_tokens, layer_begin, layer_end, workspace, workspace_bytes, hip_stream);
+}
+
+int q4kv_batched_attention_windows(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                                   uint16_t *out, const int32_t *block_table, int32_t max_blocks,
+                                   const int32_t *seq_len, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                   float sm_scale, const int32_t *window_per_layer, int32_t split_tokens,
+                                   int32_t layer_begin, int32_t layer_end, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream)
+{
+    if (!window_per_layer) return fail(Q4KV_EINVAL, "NULL window_per_layer");
+    if (layer_end - layer_begin > q4kv::max_window_layers())
+        return fail(Q4KV_EINVAL, "at most %d layers per call with per-layer windows", q4kv::max_window_layers());
+    return attention_common(spec, k, v, q, out, block_table, max_blocks, seq_len, num_agents, q_len, max_seq_len, sm_scale,
+                            0, window_per_layer, split_tokens, layer_begin, layer_end, workspace, workspace_bytes,
+                            hip_stream);
 }
 
 } // extern "C"

@@ -33,6 +33,7 @@ constexpr int kTile = 64;     // KV tokens per tile
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kXcds = 8;
+constexpr int kMaxChunkWindowLayers = 128; // layers per call when every layer brings its own window
 
 struct ChunkParams {
     const uint32_t *k_codes, *v_codes;
@@ -43,6 +44,8 @@ struct ChunkParams {
     int num_blocks, kv_heads, q_heads, num_agents, max_blocks, max_seq_len, window, q_len;
     int layer_begin, layers_in_call, q_tiles;
     float score_scale;
+    int per_layer_windows;          // 1: layer_window[] holds the window of every layer of the call
+    int layer_window[kMaxChunkWindowLayers];
 };
 
 __device__ __forceinline__ half2_t pk_fma(half2_t a, half2_t b, half2_t c) { return a * b + c; }
@@ -127,13 +130,14 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
 
     int n = p.seq_len[agent];
     n = n < 0 ? 0 : (n > p.max_seq_len ? p.max_seq_len : n);
+    const int window = p.per_layer_windows ? p.layer_window[li] : p.window;
     const int pos0 = qt * QPOS;                   // first chunk position of this workgroup
     if (pos0 >= p.q_len) return;
     // chunk position c sees tokens [first(c), vis(c)),  vis(c) = n - (q_len - 1 - c)
     const int vis_last = n - (p.q_len - 1 - min(p.q_len - 1, pos0 + QPOS - 1)); // keys visible to the last row here
     const int vis_first = n - (p.q_len - 1 - pos0);
     int t_begin = 0;
-    if (p.window > 0 && vis_first - p.window > 0) t_begin = (vis_first - p.window) & ~(kTile - 1);
+    if (window > 0 && vis_first - window > 0) t_begin = (vis_first - window) & ~(kTile - 1);
     const int t_end = vis_last; // exclusive; may be <= 0 when nothing is visible
 
     // ---- this lane's query rows: column n = lane % 16 of the two 16-row tiles of its wave
@@ -148,7 +152,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         row_pos[qi] = c;
         const bool live = c < p.q_len;
         row_vis[qi] = live ? n - (p.q_len - 1 - c) : 0;
-        row_first[qi] = (p.window > 0 && row_vis[qi] > p.window) ? row_vis[qi] - p.window : 0;
+        row_first[qi] = (window > 0 && row_vis[qi] > window) ? row_vis[qi] - window : 0;
         const uint16_t *src = p.q + ((q_agent + (live ? c : 0)) * p.q_heads + head) * D;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
@@ -445,6 +449,9 @@ hipError_t launch_chunk_t(const AttentionArgs &a, hipStream_t stream)
     p.num_blocks = a.k.num_blocks; p.kv_heads = a.spec.num_kv_heads; p.q_heads = a.spec.num_q_heads;
     p.num_agents = a.num_agents; p.max_blocks = a.max_blocks; p.max_seq_len = a.max_seq_len;
     p.window = a.window; p.q_len = a.q_len;
+    p.per_layer_windows = a.layer_window != nullptr;
+    for (int i = 0; i < kMaxChunkWindowLayers; ++i)
+        p.layer_window[i] = (a.layer_window && i < a.layers_in_call) ? a.layer_window[i] : 0;
     p.layer_begin = a.layer_begin; p.layers_in_call = a.layers_in_call;
     constexpr int QPOS = kRowsWG / NREP;
     p.q_tiles = (a.q_len + QPOS - 1) / QPOS;

@@ -63,51 +63,102 @@ struct DecodeParams {
 
 // ---------------------------------------------------------------------------------------------- plan
 
-// One workgroup.  units_per_agent = layers_in_call * kv_heads; total_waves = waves of the attention launch.
+// Sliding windows of the layers of a call, passed to plan_kernel by value: one window for all layers, or one each.
+struct LayerWindows {
+    int uniform;                 // 1: `window` holds for every layer
+    int window;
+    int w[kMaxWindowLayers];
+};
+
+// One workgroup.  total_waves = waves of the attention launch.  Writes the plan described in stream_k.h.
 __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restrict__ seq_len, int num_agents,
-                                                        int max_seq_len, int window, int units_per_agent,
-                                                        int total_waves, int min_tiles_per_wave,
+                                                        int max_seq_len, const LayerWindows lw, int layers,
+                                                        int kv_heads, int total_waves, int min_tiles_per_wave,
                                                         int32_t *__restrict__ plan)
 {
     __shared__ int chunk_sum[kThreads];
+    __shared__ int s_cls[kMaxWindowLayers], s_win[kMaxWindowLayers], s_tt[kMaxWindowLayers], s_classes;
     const int tid = threadIdx.x;
-    int32_t *tpre = plan + kPlanHeader, *tstart = tpre + num_agents + 1, *nlen = tstart + num_agents;
+    PlanView pv;
+    pv.plan = plan;
+    pv.A = num_agents;
+    pv.L = layers;
+    // ---- classes of equal windows (a handful at most in practice)
+    if (tid == 0) {
+        int C = 0;
+        if (lw.uniform) {
+            s_win[0] = lw.window > 0 ? lw.window : 0;
+            C = 1;
+        } else {
+            for (int li = 0; li < layers; ++li) {
+                const int w = lw.w[li] > 0 ? lw.w[li] : 0;
+                int c = 0;
+                while (c < C && s_win[c] != w) ++c;
+                if (c == C) s_win[C++] = w;
+                s_cls[li] = c;
+            }
+        }
+        s_classes = C;
+    }
+    __syncthreads();
+    const int C = s_classes;
+    for (int li = tid; li < layers; li += kThreads) plan[pv.cls_off() + li] = lw.uniform ? 0 : s_cls[li];
     const int per_thread = (num_agents + kThreads - 1) / kThreads;
     const int a0 = tid * per_thread, a1 = min(num_agents, a0 + per_thread);
-    int local = 0;
+    int32_t *nlen = plan + pv.nlen_off();
     for (int a = a0; a < a1; ++a) {
-        int n = seq_len[a];
-        n = n < 0 ? 0 : (n > max_seq_len ? max_seq_len : n);
-        const int first = (window > 0 && n > window) ? n - window : 0;
-        const int start = first & ~(kWave - 1);
-        nlen[a] = n;
-        tstart[a] = start;
-        local += n > 0 ? (n - start + kWave - 1) / kWave : 0;
+        const int n = seq_len[a];
+        nlen[a] = n < 0 ? 0 : (n > max_seq_len ? max_seq_len : n);
     }
-    chunk_sum[tid] = local;
+    // ---- per class: first visible tile and tile count of every agent, prefix sum over the agents
+    for (int c = 0; c < C; ++c) {
+        const int cb = pv.class_off(c);
+        const int window = s_win[c];
+        int32_t *tpre = plan + cb + 1, *tstart = plan + cb + 2 + num_agents;
+        int local = 0;
+        for (int a = a0; a < a1; ++a) {
+            const int n = nlen[a];
+            const int first = (window > 0 && n > window) ? n - window : 0;
+            const int start = first & ~(kWave - 1);
+            tstart[a] = start;
+            local += n > 0 ? (n - start + kWave - 1) / kWave : 0;
+        }
+        __syncthreads(); // chunk_sum is free again
+        chunk_sum[tid] = local;
+        __syncthreads();
+        for (int off = 1; off < kThreads; off <<= 1) { // inclusive scan, log2(256) rounds
+            const int add = tid >= off ? chunk_sum[tid - off] : 0;
+            __syncthreads();
+            chunk_sum[tid] += add;
+            __syncthreads();
+        }
+        if (tid == kThreads - 1) {
+            plan[cb] = window;
+            tpre[num_agents] = chunk_sum[tid];
+            s_tt[c] = chunk_sum[tid];
+        }
+        int run = chunk_sum[tid] - local; // exclusive prefix of this thread's chunk
+        for (int a = a0; a < a1; ++a) {
+            tpre[a] = run;
+            const int n = nlen[a];
+            run += n > 0 ? (n - tstart[a] + kWave - 1) / kWave : 0;
+        }
+    }
     __syncthreads();
-    for (int off = 1; off < kThreads; off <<= 1) { // inclusive scan, log2(256) rounds
-        const int add = tid >= off ? chunk_sum[tid - off] : 0;
-        __syncthreads();
-        chunk_sum[tid] += add;
-        __syncthreads();
-    }
-    if (tid == kThreads - 1) {
-        const int all = chunk_sum[tid];
-        const long long total = (long long)all * units_per_agent;
+    // ---- tiles before every layer, the waves' share
+    if (tid == 0) {
+        long long total = 0;
+        for (int li = 0; li < layers; ++li) {
+            plan[pv.lt_off() + li] = (int)total;
+            total += (long long)s_tt[lw.uniform ? 0 : s_cls[li]] * kv_heads;
+        }
+        plan[pv.lt_off() + layers] = (int)total;
         long long per = (total + total_waves - 1) / total_waves;
         if (per < min_tiles_per_wave) per = min_tiles_per_wave;
-        plan[0] = all;
+        plan[0] = (int)total;
         plan[1] = (int)per;
-        plan[2] = (int)total;
-        plan[3] = 0;
-        tpre[num_agents] = all;
-    }
-    int run = chunk_sum[tid] - local; // exclusive prefix of this thread's chunk
-    for (int a = a0; a < a1; ++a) {
-        tpre[a] = run;
-        const int n = nlen[a];
-        run += n > 0 ? (n - tstart[a] + kWave - 1) / kWave : 0;
+        plan[2] = C;
+        plan[3] = layers;
     }
 }
 
@@ -513,12 +564,17 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const float *__restri
     const int agent = (int)((unit / q_heads) % num_agents);
     const int li = (int)(unit / ((long long)q_heads * num_agents));
     const int kvh = qh / (q_heads / kv_heads);
-    const int TT = plan[0], per = plan[1];
-    const int32_t *tpre = plan + kPlanHeader;
+    PlanView pv;
+    pv.plan = plan;
+    pv.A = num_agents;
+    pv.L = plan[3];
+    const int per = plan[1];
+    const int cb = pv.layer_class_off(li);
+    const int32_t *tpre = pv.tpre(cb);
     const int tiles = tpre[agent + 1] - tpre[agent];
     int slots = 0;
     if (tiles > 0) {
-        const long long u0 = (long long)(li * kv_heads + kvh) * TT + tpre[agent];
+        const long long u0 = (long long)plan[pv.lt_off() + li] + (long long)kvh * pv.tiles_per_head(cb) + tpre[agent];
         slots = (int)((u0 + tiles - 1) / per - u0 / per) + 1;
     }
     const float *ml = part_ml + unit * max_slots * 2;
@@ -584,21 +640,26 @@ StreamParams stream_params(const AttentionArgs &a)
     s.kv_heads = a.spec.num_kv_heads;
     s.num_blocks = a.k.num_blocks;
     s.layer_begin = a.layer_begin;
-    s.window = a.window;
+    s.layers = a.layers_in_call;
     return s;
 }
 
 hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream)
 {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len,
-                       a.window, a.layers_in_call * a.spec.num_kv_heads, a.grid_workgroups * kWaves,
-                       a.split_tokens / kWave, a.plan);
+    LayerWindows lw;
+    lw.uniform = a.layer_window == nullptr;
+    lw.window = a.window;
+    for (int i = 0; i < kMaxWindowLayers; ++i) lw.w[i] = (!lw.uniform && i < a.layers_in_call) ? a.layer_window[i] : 0;
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len, lw,
+                       a.layers_in_call, a.spec.num_kv_heads, a.grid_workgroups * kWaves, a.split_tokens / kWave, a.plan);
     return hipGetLastError();
 }
 
 int decode_waves_per_workgroup() { return kWaves; }
 
-size_t decode_plan_ints(int num_agents) { return (size_t)kPlanHeader + 3 * (size_t)num_agents + 1; }
+int max_window_layers() { return kMaxWindowLayers; }
+
+size_t decode_plan_ints(int num_agents, int layers) { return PlanView::ints(num_agents, layers); }
 
 bool decode_supported(const q4kv_spec &s)
 {

@@ -24,6 +24,7 @@ struct AttentionArgs {
     const int32_t *block_table;
     const int32_t *seq_len;
     int max_blocks, num_agents, q_len, max_seq_len, window;
+    const int32_t *layer_window; // host, [layers_in_call]: one window per layer of the call, or nullptr: `window` for all
     int split_tokens;           // smallest token range one wave takes (multiple of 256)
     int max_slots;              // partial records reserved per (layer, agent, query head)
     int grid_workgroups;        // workgroups of the attention launch (two per compute unit)
@@ -41,7 +42,8 @@ hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream);   // needs g
 // true when a decode (q_len == 1) kernel exists for these head shapes
 bool decode_supported(const q4kv_spec &spec);
 int decode_waves_per_workgroup();
-size_t decode_plan_ints(int num_agents);
+size_t decode_plan_ints(int num_agents, int layers);
+int max_window_layers();   // layers per call when every layer brings its own window
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream);
 

@@ -10,17 +10,41 @@
 
 namespace q4kv {
 
-// Plan written by plan_kernel into the workspace (int32):
-//   [0] TT = tiles of all agents of one (layer, KV head)   [1] per = tiles per wave   [2] N = total tiles
-//   [4 .. 4+A]        tpre[a]   tile prefix sum over agents (tpre[A] == TT)
-//   [.. +A]           tstart[a] first visible token rounded down to a tile boundary
-//   [.. +A]           nlen[a]   seq_len clamped to [0, max_seq_len]
+// Plan written by plan_kernel into the workspace (int32).  Layers with the same sliding window form a class; the
+// per-agent arrays exist once per class.  A = agents, L = layers in the call, C <= L classes.
+//   [0] N = total tiles   [1] per = tiles per wave   [2] C   [3] L
+//   LT[L + 1]    tiles before layer li of the call (all KV heads and agents), LT[L] = N
+//   cls[L]       class of layer li
+//   C_max = L class blocks of 2A + 2 ints:  window (0 = global), tpre[A + 1] (tile prefix sum over agents, tpre[A] =
+//                tiles of one (layer, KV head) of the class), tstart[A] (first visible token rounded down to a tile)
+//   nlen[A]      seq_len clamped to [0, max_seq_len]
 constexpr int kPlanHeader = 4;
+constexpr int kMaxWindowLayers = 128; // layers per call when every layer brings its own window
+
+struct PlanView {
+    const int32_t *plan;
+    int A, L;
+    __device__ __host__ __forceinline__ static size_t ints(int A, int L)
+    {
+        return (size_t)kPlanHeader + 2 * (size_t)L + 1 + (size_t)L * (2 * (size_t)A + 2) + (size_t)A;
+    }
+    __device__ __forceinline__ int class_stride() const { return 2 * A + 2; }
+    __device__ __forceinline__ int lt_off() const { return kPlanHeader; }
+    __device__ __forceinline__ int cls_off() const { return kPlanHeader + L + 1; }
+    __device__ __forceinline__ int class_off(int c) const { return kPlanHeader + 2 * L + 1 + c * class_stride(); }
+    __device__ __forceinline__ int nlen_off() const { return class_off(L); }
+    __device__ __forceinline__ int layer_class_off(int li) const { return class_off(plan[cls_off() + li]); }
+    // inside a class block
+    __device__ __forceinline__ int window(int cb) const { return plan[cb]; }
+    __device__ __forceinline__ const int32_t *tpre(int cb) const { return plan + cb + 1; }
+    __device__ __forceinline__ const int32_t *tstart(int cb) const { return plan + cb + 2 + A; }
+    __device__ __forceinline__ int tiles_per_head(int cb) const { return plan[cb + 1 + A]; }
+};
 
 struct StreamParams {
     const int32_t *plan;
     const int32_t *block_table;
-    int num_agents, max_blocks, kv_heads, num_blocks, layer_begin, window;
+    int num_agents, max_blocks, kv_heads, num_blocks, layer_begin, layers;
 };
 
 // Position of a wave in the tile stream; every field is wave-uniform and lives in scalar registers.
@@ -30,6 +54,7 @@ struct StreamParams {
 template <typename Flag>
 struct CursorT {
     int li, kvh, agent;  // unit: layer in call, KV head, agent
+    int cb;              // plan offset of the class block of layer li
     int j, tiles;        // tile inside the unit, tiles of the unit
     int t0;              // first token of the tile
     int n, first;        // visible tokens of the agent, first visible token (sliding window)
@@ -43,17 +68,16 @@ typedef CursorT<bool> Cursor;
 
 struct TileStream {
     StreamParams sp;
-    const int32_t *tpre, *tstart, *nlen;
-    int TT, per, N;
+    PlanView pv;
+    int per, N;
 
     __device__ __forceinline__ explicit TileStream(const StreamParams &s) : sp(s)
     {
-        TT = s.plan[0];
+        pv.plan = s.plan;
+        pv.A = s.num_agents;
+        pv.L = s.layers;
+        N = s.plan[0];
         per = s.plan[1];
-        N = s.plan[2];
-        tpre = s.plan + kPlanHeader;
-        tstart = tpre + s.num_agents + 1;
-        nlen = tstart + s.num_agents;
     }
 
     template <typename C>
@@ -87,9 +111,11 @@ struct TileStream {
     template <typename C>
     __device__ __forceinline__ void enter_unit(C &c) const
     {
+        const int32_t *tpre = pv.tpre(c.cb);
+        const int window = pv.window(c.cb);
         c.tiles = tpre[c.agent + 1] - tpre[c.agent];
-        c.n = nlen[c.agent];
-        c.first = (sp.window > 0 && c.n > sp.window) ? c.n - sp.window : 0;
+        c.n = pv.plan[pv.nlen_off() + c.agent];
+        c.first = (window > 0 && c.n > window) ? c.n - window : 0;
         c.unit_row = (((int64_t)(sp.layer_begin + c.li) * sp.num_blocks) * sp.kv_heads + c.kvh) * kBlockTokens;
     }
 
@@ -102,37 +128,51 @@ struct TileStream {
             if (c.t0 % kBlockTokens == 0) next_block(c); else c.row += kWave;
             return;
         }
+        const int32_t *tpre = pv.tpre(c.cb);
         do {
             if (++c.agent >= sp.num_agents) {
                 c.agent = 0;
                 if (++c.kvh >= sp.kv_heads) {
                     c.kvh = 0;
                     ++c.li;
+                    c.cb = pv.layer_class_off(c.li);
+                    tpre = pv.tpre(c.cb);
                 }
             }
         } while (tpre[c.agent + 1] == tpre[c.agent]);
         c.j = 0;
-        c.t0 = tstart[c.agent];
+        c.t0 = pv.tstart(c.cb)[c.agent];
         enter_unit(c);
         enter_block(c);
     }
 
-    // where tile x lies: unit by binary search over the agents' tile prefix sums
+    // where tile x lies: layer by binary search over the layer prefix, agent by binary search over the class's
+    // per-agent prefix
     template <typename C = Cursor>
     __device__ __forceinline__ C locate(int x) const
     {
         C c;
-        const int lu = x / TT, r = x - lu * TT;
-        int lo = 0, hi = sp.num_agents - 1; // largest a with tpre[a] <= r and at least one tile
+        const int32_t *LT = pv.plan + pv.lt_off();
+        int lo = 0, hi = sp.layers - 1; // largest li with LT[li] <= x (layers without tiles are stepped over)
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (LT[mid] <= x) lo = mid; else hi = mid - 1;
+        }
+        c.li = lo;
+        c.cb = pv.layer_class_off(lo);
+        const int TT = pv.tiles_per_head(c.cb);
+        const int32_t *tpre = pv.tpre(c.cb);
+        const int in_layer = x - LT[lo];
+        c.kvh = in_layer / TT;
+        const int r = in_layer - c.kvh * TT;
+        lo = 0, hi = sp.num_agents - 1; // largest a with tpre[a] <= r and at least one tile
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
             if (tpre[mid] <= r) lo = mid; else hi = mid - 1;
         }
-        c.li = lu / sp.kv_heads;
-        c.kvh = lu % sp.kv_heads;
         c.agent = lo;
         c.j = r - tpre[lo];
-        c.t0 = tstart[lo] + c.j * kWave;
+        c.t0 = pv.tstart(c.cb)[lo] + c.j * kWave;
         enter_unit(c);
         enter_block(c);
         return c;
@@ -142,7 +182,8 @@ struct TileStream {
     template <typename C>
     __device__ __forceinline__ int slot_of(const C &c, int gw) const
     {
-        const int unit_first_tile = (c.li * sp.kv_heads + c.kvh) * TT + tpre[c.agent];
+        const int unit_first_tile =
+            pv.plan[pv.lt_off() + c.li] + c.kvh * pv.tiles_per_head(c.cb) + pv.tpre(c.cb)[c.agent];
         return gw - unit_first_tile / per;
     }
 };

@@ -83,6 +83,20 @@ def test_chunk_rows_equal_decode_steps_and_window():
     assert np.array_equal(again.cpu().numpy().view(np.uint16), got.view(np.uint16))
 
 
+def test_chunk_per_layer_windows_match_oracle():
+    w = synth.small(45, 3, 4, 2, 128, 128, False, (300, 40), q_len=70)
+    got, (spec, kpool, vpool, table_d) = append_chunk_and_attend(w)
+    ospec, okp, ovp, otable = host_cache(w)
+    sl = torch.tensor(w.final_lens(), dtype=torch.int32, device=DEV)
+    for windows in ([0, 16, 200], [1000, 1, 64]):
+        g = b.q4kv_batched_attention(spec, kpool, vpool, w.q_all(DEV), table_d, sl, max(w.final_lens()), w.sm_scale,
+                                     windows)
+        torch.cuda.synchronize()
+        want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, w.final_lens(), w.sm_scale,
+                                window_per_layer=windows)
+        assert_close(g.cpu().numpy(), want, f"windows {windows}")
+
+
 def test_poisoned_slots_past_the_chunk_are_never_used():
     # the last block of every agent is only partly filled; everything else in the pool decodes to NaN
     w = synth.small(43, 1, 4, 2, 64, 64, False, (130, 255), q_len=10)

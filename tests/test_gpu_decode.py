@@ -93,6 +93,33 @@ def test_edge_cases_zero_length_poison_window_and_layer_range():
     assert_close(g, want[1:3], "layers 1..2")
 
 
+def test_per_layer_windows_match_oracle():
+    """Global and sliding-window layers interleaved (Sec. 3.6), several distinct windows, also a layer sub-range
+    and windows that hide whole shares of the tile stream."""
+    w = synth.small(37, 6, 8, 2, 128, 128, False, (1500, 0, 300, 77, 2100))
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    ospec, okp, ovp, otable = host_cache(w)
+    lens = list(w.seq_lens)
+    q = w.q_all().numpy()
+    for windows in ([0, 256, 256, 0, 1, 1000], [64] * 6, [0] * 6, [5000, 100, 0, 100, 5000, 300]):
+        for st in (0, 256):
+            got = run_gpu(w, spec, kpool, vpool, table_d, lens, split_tokens=st, window=windows)
+            want = oracle.attention(ospec, okp, ovp, q, otable, lens, w.sm_scale, window_per_layer=windows)
+            assert_close(got, want, f"windows {windows} split {st}")
+    same = run_gpu(w, spec, kpool, vpool, table_d, lens, window=[64] * 6)
+    one = run_gpu(w, spec, kpool, vpool, table_d, lens, window=64)
+    assert np.array_equal(same.view(np.uint16), one.view(np.uint16)), "equal windows = the single-window call"
+    windows = [0, 256, 256, 0, 1, 1000]
+    part = run_gpu(w, spec, kpool, vpool, table_d, lens, window=windows[2:5], layer_begin=2, layer_end=5)
+    want = oracle.attention(ospec, okp, ovp, q[2:5], otable, lens, w.sm_scale, window_per_layer=windows,
+                            layer_begin=2, layer_end=5)
+    assert_close(part, want, "layers 2..4 with their windows")
+    with pytest.raises(ValueError):
+        b.q4kv_batched_attention(spec, kpool, vpool, w.q_all(DEV), table_d,
+                                 torch.tensor(lens, dtype=torch.int32, device=DEV), max(lens), w.sm_scale,
+                                 [0] * 5)                                  # 5 windows for 6 layers
+
+
 def test_split_invariance_and_determinism():
     w = synth.small(34, 1, 8, 2, 128, 128, False, (2000, 900))
     spec, kpool, vpool, table, table_d = gpu_cache(w)

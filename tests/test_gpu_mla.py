@@ -79,6 +79,18 @@ def test_latent_edge_cases_zero_length_poison_window_layer_range_and_bad_blocks(
     assert_close(got_bad[:, :3], want[:, :3], "agents beside the masked block")
 
 
+def test_latent_per_layer_windows_match_oracle():
+    w = mla(44, 4, (700, 90, 0, 1300))
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    ospec, okp, ovp, otable = host_cache(w)
+    lens = list(w.seq_lens)
+    q = w.q_all().numpy()
+    for windows in ([0, 128, 0, 1000], [1, 64, 65, 5000]):
+        got = run_gpu(w, spec, kpool, vpool, table_d, lens, split_tokens=256, window=windows)
+        want = oracle.attention(ospec, okp, ovp, q, otable, lens, w.sm_scale, window_per_layer=windows)
+        assert_close(got, want, f"windows {windows}")
+
+
 def test_latent_outliers_and_large_scores():
     """Sharp softmax (scores far apart, running maximum moving late) and large-magnitude channels."""
     w = mla(43, 1, (900, 130))
