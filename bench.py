@@ -102,7 +102,8 @@ def bench_append(args, torch, b, synth, build_device_cache):
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "q4 codes + f16 scale/bias dequantized to f16, f32 accumulate, f16 out", "data": "synthetic",
-        "config": {"workload": w.name, "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
+        "config": {"workload": w.name if args.layer_windows == "global" else w.name + " + 5:1 window-1024 layers",
+                   "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
                    "kv_heads": w.num_kv_heads, "head_dim": w.k_dim, "seq_lens_before": w.seq_lens, "chunk": C},
         "agent_tokens_per_s": w.num_agents * C / ((att_ms + app_ms) * 1e-3),
         "attention_ms": att_ms, "attention_flops": flops, "q4_bytes_if_read_once": q4_bytes,
@@ -163,7 +164,8 @@ def bench_latent(args, torch, b, synth, build_device_cache):
         "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "q4 codes + f16 scale/bias, f16 matrix operands, f32 accumulate, f16 out", "data": "synthetic",
-        "config": {"workload": w.name, "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
+        "config": {"workload": w.name if args.layer_windows == "global" else w.name + " + 5:1 window-1024 layers",
+                   "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
                    "kv_heads": w.num_kv_heads, "k_dim": w.k_dim, "v_dim": w.v_dim, "seq_lens": w.seq_lens,
                    "split_tokens": split, "launch": "all layers in one q4kv_batched_attention call"},
         "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
@@ -191,6 +193,10 @@ def main():
                     help="decode (default): the headline configuration; append: the chunked-append configuration "
                          "(10 agents, 4,096..32,768 cached tokens, 512-token chunk), reported as TFLOP/s; latent: "
                          "decode over the shared-latent (MLA-shaped) cache, 5 agents x 32,768 tokens x 27 layers")
+    ap.add_argument("--layer-windows", choices=["global", "mixed"], default="global",
+                    help="decode workload only.  global (default, the headline configuration): every layer attends "
+                         "to the whole cache; mixed: five layers with a 1,024-token sliding window, then one global "
+                         "layer, repeated (8 global + 40 windowed of 48, Sec. 3.6) through the per-layer window entry")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (agents would shard across GPUs with no exchange step); "
@@ -222,18 +228,29 @@ def main():
     codes, scale, bias = b.q4kv_quantize(fresh)
     restored = torch.empty_like(fresh)
     quant_bytes = fresh.numel() * 2 + codes.numel() * 4 + scale.numel() * 4
-    decode_bytes = sum(w.seq_lens) * w.num_layers * w.q4_bytes_per_token_layer()
+    if args.layer_windows == "mixed":
+        window = [0 if l % 6 == 5 else 1024 for l in range(w.num_layers)]
+    else:
+        window = 0
+    visible = sum(sum(min(n, wl) if wl > 0 else n for n in w.seq_lens)
+                  for wl in (window if isinstance(window, list) else [0] * w.num_layers))
+    decode_bytes = visible * w.q4_bytes_per_token_layer()
 
+    # Row order inside a step: dequantize, quantize, attention.  A kernel that writes much leaves dirty lines in the
+    # caches (up to the 256 MB of the memory-side cache), and their write-back is charged to whatever runs next:
+    # directly after the dequantize row (1.6 GB written) the attention call measures 6 % slower than after itself,
+    # after the quantize row (0.45 GB written) 2 % slower.
     def step(ev=None):
         if ev:
             ev[0].record()
-        b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, seq, max_len, w.sm_scale, 0, split, 0, None, out, ws)
+        b.q4kv_dequantize(codes, scale, bias, restored)
         if ev:
             ev[1].record()
         b.q4kv_quantize(fresh, codes, scale, bias)
         if ev:
             ev[2].record()
-        b.q4kv_dequantize(codes, scale, bias, restored)
+        b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, seq, max_len, w.sm_scale, window, split, 0, None,
+                                 out, ws)
         if ev:
             ev[3].record()
 
@@ -248,9 +265,9 @@ def main():
         step(events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    dec = [e[0].elapsed_time(e[1]) for e in events]
+    deq = [e[0].elapsed_time(e[1]) for e in events]
     qua = [e[1].elapsed_time(e[2]) for e in events]
-    deq = [e[2].elapsed_time(e[3]) for e in events]
+    dec = [e[2].elapsed_time(e[3]) for e in events]
     dec_ms = sum(dec) / len(dec)
     qua_ms = sum(qua) / len(qua)
     deq_ms = sum(deq) / len(deq)
@@ -261,7 +278,8 @@ def main():
         "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "q4 codes + f16 scale/bias, f32 accumulate, f16 out", "data": "synthetic",
-        "config": {"workload": w.name, "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
+        "config": {"workload": w.name if args.layer_windows == "global" else w.name + " + 5:1 window-1024 layers",
+                   "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
                    "kv_heads": w.num_kv_heads, "head_dim": w.k_dim, "seq_lens": w.seq_lens,
                    "split_tokens": split, "launch": "all layers in one q4kv_batched_attention call"},
         "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,

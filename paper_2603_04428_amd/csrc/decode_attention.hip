@@ -46,6 +46,12 @@ namespace {
 #ifndef Q4KV_DEC_WAVES_PER_EU
 #define Q4KV_DEC_WAVES_PER_EU 2 // resident waves per SIMD the register budget is sized for
 #endif
+#ifndef Q4KV_DEC_PRIO_SHIFT
+#define Q4KV_DEC_PRIO_SHIFT 12 // log2 of the priority time slice in 10 ns ticks (0: waves keep the default priority)
+#endif
+#ifndef Q4KV_DEC_PRIO_LEVEL
+#define Q4KV_DEC_PRIO_LEVEL 2
+#endif
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr float kNegBig = -1.0e30f; // "minus infinity" that survives subtraction
@@ -332,9 +338,19 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    // Two workgroups share a compute unit, and at equal priority the older wave wins every arbitration, also the
+    // one for the memory pipeline: the workgroups launched first would finish their equal shares about 13 % ahead
+    // of the others and leave half of the waves to stream alone at the end.  The two halves of the launch
+    // therefore take turns at a raised priority, in time slices read from the chip-wide clock.  (Which half is the
+    // older one on a compute unit is a guess from the launch order; if it is wrong nothing but this balance is lost.)
+    const bool second_half = blockIdx.x >= gridDim.x / 2;
     bool unit_begins = true; // the wave's first tile, or tile 0 of a unit
     int64_t unit0 = 0;
     for (int x = x0; x < x1; ++x) {
+        if (Q4KV_DEC_PRIO_SHIFT > 0) {
+            const bool turn = ((wall_clock64() >> Q4KV_DEC_PRIO_SHIFT) & 1) != 0;
+            if (turn != second_half) __builtin_amdgcn_s_setprio(Q4KV_DEC_PRIO_LEVEL); else __builtin_amdgcn_s_setprio(0);
+        }
         const bool last_of_wave = x + 1 >= x1;
         Cursor nxt = cur;
         if (!last_of_wave) ts_.step(nxt); // the wave's last tile re-reads itself: a valid address, the data is ignored

@@ -177,15 +177,19 @@ def test_block_ids_outside_the_pool_are_masked():
     assert_close(got, want, "masked block")
 
 
-@pytest.mark.parametrize("cfg", [1, 2])
-def test_full_size_configs_sampled_units(cfg):
+@pytest.mark.parametrize("cfg,split_tokens", [(1, 0), (2, 0), (2, 256), (2, 2048)])
+def test_full_size_configs_sampled_units(cfg, split_tokens):
     """Configs 1 (Llama-shaped, 5 x 4,096, 32 layers) and 2 (Gemma-shaped, 10 ragged agents, 48 layers) at full
-    size, in the launch configuration the benchmark times (all layers in one call, default split).  The oracle
+    size, in the launch configuration the benchmark times (all layers in one call, default split), and config 2
+    also with the smallest and a larger chunk (waves then fetch many / a few chunks from the queues).  The oracle
     recomputes a seeded sample of (layer, agent, kv head) units from the generator alone."""
     w = synth.config(cfg)
     spec, kpool, vpool, table, table_d = gpu_cache(w, poison=False, extra_blocks=0)
-    got = run_gpu(w, spec, kpool, vpool, table_d, w.seq_lens)
+    got = run_gpu(w, spec, kpool, vpool, table_d, w.seq_lens, split_tokens)
     assert not np.isnan(got.astype(np.float32)).any()
+    # which wave computes which chunk varies from run to run; the result does not
+    again = run_gpu(w, spec, kpool, vpool, table_d, w.seq_lens, split_tokens)
+    assert np.array_equal(got.view(np.uint16), again.view(np.uint16)), "run-to-run identical"
     rng = np.random.default_rng(cfg)
     shortest, longest = int(np.argmin(w.seq_lens)), int(np.argmax(w.seq_lens))
     units = {(0, shortest, 0), (w.num_layers - 1, longest, w.num_kv_heads - 1), (0, longest, 3),
