@@ -82,9 +82,9 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
                                                         int kv_heads, int total_waves, int min_tiles_per_wave,
                                                         int32_t *__restrict__ plan)
 {
-    __shared__ int chunk_sum[kThreads];
+    __shared__ int s_wave_sum[kWaves];
     __shared__ int s_cls[kMaxWindowLayers], s_win[kMaxWindowLayers], s_tt[kMaxWindowLayers], s_classes;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     PlanView pv;
     pv.plan = plan;
     pv.A = num_agents;
@@ -112,10 +112,17 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
     const int per_thread = (num_agents + kThreads - 1) / kThreads;
     const int a0 = tid * per_thread, a1 = min(num_agents, a0 + per_thread);
     int32_t *nlen = plan + pv.nlen_off();
-    for (int a = a0; a < a1; ++a) {
+    // Nothing written to the plan is read back here: every value comes from seq_len (cached after its first read)
+    // and registers, so the kernel's length is a few memory round trips.
+    auto length = [&](int a) {
         const int n = seq_len[a];
-        nlen[a] = n < 0 ? 0 : (n > max_seq_len ? max_seq_len : n);
-    }
+        return n < 0 ? 0 : (n > max_seq_len ? max_seq_len : n);
+    };
+    auto first_tile_token = [](int n, int window) {
+        const int first = (window > 0 && n > window) ? n - window : 0;
+        return first & ~(kWave - 1);
+    };
+    for (int a = a0; a < a1; ++a) nlen[a] = length(a);
     // ---- per class: first visible tile and tile count of every agent, prefix sum over the agents
     for (int c = 0; c < C; ++c) {
         const int cb = pv.class_off(c);
@@ -123,31 +130,37 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
         int32_t *tpre = plan + cb + 1, *tstart = plan + cb + 2 + num_agents;
         int local = 0;
         for (int a = a0; a < a1; ++a) {
-            const int n = nlen[a];
-            const int first = (window > 0 && n > window) ? n - window : 0;
-            const int start = first & ~(kWave - 1);
+            const int n = length(a);
+            const int start = first_tile_token(n, window);
             tstart[a] = start;
             local += n > 0 ? (n - start + kWave - 1) / kWave : 0;
         }
-        __syncthreads(); // chunk_sum is free again
-        chunk_sum[tid] = local;
+        int incl = local; // inclusive scan inside the wave, then over the waves through LDS
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
+        }
+        if (lane == kWave - 1) s_wave_sum[wave] = incl;
         __syncthreads();
-        for (int off = 1; off < kThreads; off <<= 1) { // inclusive scan, log2(256) rounds
-            const int add = tid >= off ? chunk_sum[tid - off] : 0;
-            __syncthreads();
-            chunk_sum[tid] += add;
-            __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const int t = s_wave_sum[w];
+            if (w < wave) before += t;
+            total += t;
         }
-        if (tid == kThreads - 1) {
+        __syncthreads(); // s_wave_sum is free again
+        if (tid == 0) {
             plan[cb] = window;
-            tpre[num_agents] = chunk_sum[tid];
-            s_tt[c] = chunk_sum[tid];
+            tpre[num_agents] = total;
+            s_tt[c] = total;
         }
-        int run = chunk_sum[tid] - local; // exclusive prefix of this thread's chunk
+        int run = before + incl - local; // exclusive prefix of this thread's chunk
         for (int a = a0; a < a1; ++a) {
             tpre[a] = run;
-            const int n = nlen[a];
-            run += n > 0 ? (n - tstart[a] + kWave - 1) / kWave : 0;
+            const int n = length(a);
+            run += n > 0 ? (n - first_tile_token(n, window) + kWave - 1) / kWave : 0;
         }
     }
     __syncthreads();
@@ -570,7 +583,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const float *__restri
                                                            const float *__restrict__ part_ml,
                                                            const int32_t *__restrict__ plan, uint16_t *__restrict__ out,
                                                            int q_heads, int kv_heads, int num_agents, int v_dim,
-                                                           int max_slots, long long units)
+                                                           int max_slots, int layers, long long units)
 {
     const int threads_per_unit = v_dim / 4;
     const long long unit = (long long)blockIdx.x * (kThreads / threads_per_unit) + threadIdx.x / threads_per_unit;
@@ -583,7 +596,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const float *__restri
     PlanView pv;
     pv.plan = plan;
     pv.A = num_agents;
-    pv.L = plan[3];
+    pv.L = layers;
     const int per = plan[1];
     const int cb = pv.layer_class_off(li);
     const int32_t *tpre = pv.tpre(cb);
@@ -706,7 +719,7 @@ hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream)
     const int64_t blocks = (units + units_per_block - 1) / units_per_block;
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, a.part_acc, a.part_ml, a.plan,
                        a.out, a.spec.num_q_heads, a.spec.num_kv_heads, a.num_agents, a.spec.v_dim, a.max_slots,
-                       (long long)units);
+                       a.layers_in_call, (long long)units);
     return hipGetLastError();
 }
 
