@@ -152,6 +152,14 @@ int32_t q4kv_default_split_tokens(const q4kv_spec *spec, int32_t num_agents, int
  * Negative on bad arguments. */
 int64_t q4kv_cache_bytes(const q4kv_spec *spec, int64_t tokens);
 
+/* Measurement helper, no part of the method: a kernel that only reads.  Reads the first
+ * floor(bytes / 16384) * 16384 bytes of the device buffer `src` (16-byte aligned) exactly once, in the launch
+ * shape and with the load width of the decode kernel, and writes nothing except, possibly, the one device word
+ * `sink` (its value means nothing).  Timing it gives the read bandwidth the memory system sustains, against which
+ * the benchmark quotes the decode kernel next to the published peak.  Enqueues on hip_stream; no allocation, no
+ * synchronisation.  Fewer than 16,384 bytes: nothing happens.  Q4KV_EINVAL on a NULL or misaligned pointer. */
+int q4kv_read_probe(const void *src, size_t bytes, uint32_t *sink, void *hip_stream);
+
 /* Message of this thread's most recent failing call ("" if none). */
 const char *q4kv_last_error(void);
 

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libq4kv.so")
 
 EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_append", "q4kv_batched_attention",
-           "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_last_error",
+           "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_read_probe", "q4kv_last_error",
            "q4kv_version"]
 
 
@@ -62,6 +62,7 @@ def lib():
         l.q4kv_default_split_tokens.argtypes = [C.POINTER(Spec), i32, i32, i32, i32]
         l.q4kv_cache_bytes.restype = i64
         l.q4kv_cache_bytes.argtypes = [C.POINTER(Spec), i64]
+        l.q4kv_read_probe.argtypes = [vp, C.c_size_t, vp, vp]
         l.q4kv_last_error.restype = C.c_char_p
         l.q4kv_version.restype = C.c_int
         _lib = l
@@ -118,6 +119,14 @@ def q4kv_cache_bytes(spec, tokens):
     if r < 0:
         _check(-1)
     return r
+
+
+def q4kv_read_probe(buf, sink):
+    """Measurement helper: read the contiguous GPU tensor `buf` once (nothing is written); sink: int32 [1] on the GPU."""
+    if not (buf.is_cuda and buf.is_contiguous() and sink.is_cuda and sink.numel() >= 1 and sink.element_size() == 4):
+        raise ValueError("q4kv_read_probe: contiguous GPU tensors, sink of at least one 4-byte element")
+    _check(lib().q4kv_read_probe(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), C.c_void_p(sink.data_ptr()),
+                                 _stream()))
 
 
 def q4kv_quantize(x, codes=None, scale=None, bias=None):

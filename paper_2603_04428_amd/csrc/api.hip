@@ -290,4 +290,13 @@ int q4kv_batched_attention_windows(const q4kv_spec *spec, const q4kv_pool *k, co
                             hip_stream);
 }
 
+int q4kv_read_probe(const void *src, size_t bytes, uint32_t *sink, void *hip_stream)
+{
+    if (bytes < 16384) return Q4KV_OK; // nothing to read
+    if (!src || !sink) return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!aligned16(src)) return fail(Q4KV_EINVAL, "src must be 16-byte aligned");
+    hipError_t e = q4kv::launch_read_probe(src, bytes, sink, 2 * compute_units(), (hipStream_t)hip_stream);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "read probe launch: %s", hipGetErrorString(e));
+}
+
 } // extern "C"

@@ -56,4 +56,7 @@ hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t strea
 bool chunk_supported(const q4kv_spec &spec);
 hipError_t launch_chunk_attention(const AttentionArgs &a, hipStream_t stream);
 
+// read_probe.hip: reads bytes / 16,384 * 16,384 bytes of `src` once; `sink` is one device word that may be written
+hipError_t launch_read_probe(const void *src, size_t bytes, uint32_t *sink, int workgroups, hipStream_t stream);
+
 } // namespace q4kv

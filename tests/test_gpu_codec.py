@@ -192,3 +192,17 @@ def test_full_size_cache_quantize_sampled_rows():
             err = (xh.float() - x.float()).abs()
             ulp = torch.ldexp(torch.ones_like(err), torch.frexp(xh.float().abs().clamp_min(2.0 ** -14))[1] - 12)
             assert bool((err <= s / 2 * 1.001 + ulp).all())
+
+
+def test_read_probe_reads_only():
+    """The measurement helper touches nothing but (possibly) its sink word, for sizes below, at and off its 16 KiB step."""
+    g = torch.Generator(device="cpu").manual_seed(7)
+    for nbytes in (0, 100, 16384, 16384 * 5 + 48, 16384 * 2049):
+        host = torch.randint(0, 2 ** 31 - 1, (nbytes // 4 + 4,), dtype=torch.int32, generator=g)
+        buf = host.to(DEV)
+        sink = torch.zeros(1, dtype=torch.int32, device=DEV)
+        b.q4kv_read_probe(buf[: nbytes // 4], sink)
+        torch.cuda.synchronize()
+        assert torch.equal(buf.cpu(), host)
+    with pytest.raises(b.Q4KVError):
+        b.q4kv_read_probe(buf.view(torch.uint8)[4:4 + 32768], sink)   # not 16-byte aligned
