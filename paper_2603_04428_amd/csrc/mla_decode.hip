@@ -310,7 +310,11 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
             const float c_code = p.score_scale * kCodeScaleA;
             const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
             SetIn set_in = load_set(0, 0);
-            GroupIn grp_in[2]; // a ring of the next two value steps
+#ifndef Q4KV_MLA_RING
+#define Q4KV_MLA_RING 2
+#endif
+            constexpr int kRing = Q4KV_MLA_RING;
+            GroupIn grp_in[kRing]; // a ring of the next value steps
 #pragma unroll
             for (int set = 0; set < 4; ++set) {
                 const int h2 = set / 2, sub = set % 2;
@@ -318,8 +322,8 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                 if (set < 3) {
                     set_next = load_set((set + 1) / 2, (set + 1) % 2);
                 } else {
-                    grp_in[0] = load_group(0);
-                    grp_in[1] = load_group(1);
+#pragma unroll
+                    for (int i = 0; i < kRing; ++i) grp_in[i] = load_group(i);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 float4_t d[GK];
@@ -426,8 +430,8 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
 #pragma unroll
                 for (int g = 0; g < GV; ++g) {
                     const int step = h2 * GV + g;
-                    const GroupIn in = grp_in[step % 2];
-                    if (step + 2 < 2 * GV) grp_in[step % 2] = load_group(step + 2);
+                    const GroupIn in = grp_in[step % kRing];
+                    if (step + kRing < 2 * GV) grp_in[step % kRing] = load_group(step + kRing);
                     __builtin_amdgcn_sched_barrier(0);
                     const half8_t ps = words_to_half8(half2_to_bits(p16[0] * bits_to_half2(in.s8.x)),
                                                       half2_to_bits(p16[1] * bits_to_half2(in.s8.y)),
