@@ -90,27 +90,36 @@ __device__ __forceinline__ float xor32_sum(float x)
     return __builtin_bit_cast(float, (uint32_t)r[0]) + __builtin_bit_cast(float, (uint32_t)r[1]);
 }
 
+// How the threads of a workgroup share the staging of one 64-row tile of DIM-wide code rows: as many threads per row
+// as fit, each with 2, 4 or 8 consecutive words (never across a quantization group).
+template <int DIM, int THREADS>
+struct Stage {
+    static constexpr int WORDS = DIM / 8; // code words per row
+    static constexpr int WPT = kTile * (WORDS / 2) <= THREADS ? 2 : (kTile * (WORDS / 4) <= THREADS ? 4 : 8);
+    static constexpr int TPR = WORDS / WPT; // threads per row
+    static constexpr int ACTIVE = kTile * TPR;
+    static_assert(WORDS % WPT == 0 && ACTIVE <= THREADS, "tile split");
+};
+
 // QT: 16-row query tiles per wave.  Two tiles halve the LDS operand traffic per matrix instruction; one tile keeps
 // a wave within 256 registers also at D = 256, so that two waves share a SIMD and one wave's dequantization and
 // softmax run under the other's matrix instructions.  The workgroup always owns 128 rows: 128 / (16 QT) waves.
-template <int D, int NREP, int QT>
+template <int DK, int DV, int NREP, int QT>
 __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attention_kernel(ChunkParams p)
 {
     constexpr int kRowsWave = 16 * QT;
     constexpr int kWaves = kRowsWG / kRowsWave;
     constexpr int kThreads = kWaves * kWave;
-    constexpr int G = D / kGroup;
+    constexpr int GK = DK / kGroup, GV = DV / kGroup;
     // halves per row of the dequantized tiles in LDS.  K_hat rows are read 16 bytes per lane by 16 rows at a time
     // (pitch = 16 bytes mod 256), V_hat rows 8 bytes per lane by 4 rows x 32 bytes at a time (pitch = 32 mod 256)
-    constexpr int KPITCH = D + 8;
-    constexpr int VPITCH = D + 16;
+    constexpr int KPITCH = DK + 8;
+    constexpr int VPITCH = DV + 16;
     constexpr int QPOS = kRowsWG / NREP; // chunk positions per workgroup
-    constexpr int KSTEPS = D / 32;     // k-steps of the QK contraction
-    constexpr int ETILES = D / 16;     // 16-row tiles of O^T
-    constexpr int WORDS = D / 8;       // code words per row
-    constexpr int WPT = kTile * WORDS / kThreads; // code words of K (and of V) a thread dequantizes per tile
-    static_assert(WPT == 8 || WPT == 4 || WPT == 2, "tile split");
-    constexpr int THREADS_PER_ROW = WORDS / WPT;  // 4: a thread's words lie inside one quantization group
+    constexpr int KSTEPS = DK / 32;    // k-steps of the QK contraction
+    constexpr int ETILES = DV / 16;    // 16-row tiles of O^T
+    typedef Stage<DK, kThreads> SK;    // staging of the K rows of a tile ...
+    typedef Stage<DV, kThreads> SV;    // ... and of its V rows
 
     // two tiles each: while the waves multiply against one, they dequantize the next into the other
     __shared__ __attribute__((aligned(16))) half_t k_lds[2][kTile * KPITCH];
@@ -153,7 +162,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         const bool live = c < p.q_len;
         row_vis[qi] = live ? n - (p.q_len - 1 - c) : 0;
         row_first[qi] = (window > 0 && row_vis[qi] > window) ? row_vis[qi] - window : 0;
-        const uint16_t *src = p.q + ((q_agent + (live ? c : 0)) * p.q_heads + head) * D;
+        const uint16_t *src = p.q + ((q_agent + (live ? c : 0)) * p.q_heads + head) * DK;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             // dims 32*ks + 8*kb .. +7 in the order the nibble masks emit them: 0,4,1,5,2,6,3,7
@@ -193,24 +202,28 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     }
 
     // ---- KV tile staging: raw Q4 in registers one tile ahead.  A thread takes WPT consecutive words of one token's
-    // K row and the same words of its V row
+    // K row and (the same ones when the rows are equally wide) of one token's V row; with rows that do not divide
+    // evenly the last waves stage nothing
     const int32_t *table = p.block_table + (int64_t)agent * p.max_blocks;
-    uint32_t kraw[WPT], vraw[WPT];
+    uint32_t kraw[SK::WPT], vraw[SV::WPT];
     uint32_t ksb[2], vsb[2]; // scale / bias bits of the group this thread dequantizes
     // 16 consecutive lanes take 16 consecutive tokens (and the same part of the row): their 16-byte LDS stores then
     // fall into 16 different bank groups, like the operand reads
-    const int k_tok = (tid % 16) + 16 * (tid / (16 * THREADS_PER_ROW)), k_w0 = ((tid / 16) % THREADS_PER_ROW) * WPT;
-    const int k_grp = (k_w0 * 8) / kGroup;
+    const bool k_on = SK::ACTIVE == kThreads || tid < SK::ACTIVE, v_on = SV::ACTIVE == kThreads || tid < SV::ACTIVE;
+    const int k_tok = k_on ? (tid % 16) + 16 * (tid / (16 * SK::TPR)) : 0, k_w0 = ((tid / 16) % SK::TPR) * SK::WPT;
+    const int v_tok = v_on ? (tid % 16) + 16 * (tid / (16 * SV::TPR)) : 0, v_w0 = ((tid / 16) % SV::TPR) * SV::WPT;
+    const int k_grp = (k_w0 * 8) / kGroup, v_grp = (v_w0 * 8) / kGroup;
     auto tile_row0 = [&](int t0, bool &ok) {
         const int bi = t0 / kBlockTokens;
         const int blk = bi < p.max_blocks ? table[bi] : -1;
         ok = blk >= 0 && blk < p.num_blocks;
         return (((int64_t)layer * p.num_blocks + (ok ? blk : 0)) * p.kv_heads + kvh) * kBlockTokens + (t0 % kBlockTokens);
     };
-    auto load_words = [&](const uint32_t *src, uint32_t (&dst)[WPT]) {
-        if constexpr (WPT % 4 == 0) {
+    auto load_words = [&](const uint32_t *src, auto &dst) {
+        constexpr int N = sizeof(dst) / sizeof(uint32_t);
+        if constexpr (N % 4 == 0) {
 #pragma unroll
-            for (int i = 0; i < WPT / 4; ++i) {
+            for (int i = 0; i < N / 4; ++i) {
                 const uint4 t = *reinterpret_cast<const uint4 *>(src + 4 * i);
                 dst[4 * i] = t.x; dst[4 * i + 1] = t.y; dst[4 * i + 2] = t.z; dst[4 * i + 3] = t.w;
             }
@@ -219,14 +232,16 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
             dst[0] = t.x; dst[1] = t.y;
         }
     };
+    // threads without a share load row 0 of the tile again (a valid address) and never store
     auto load_tile = [&](int t0, bool &ok) {
-        const int64_t row = tile_row0(t0, ok) + k_tok;
-        load_words(p.k_codes + row * WORDS + k_w0, kraw);
-        load_words(p.v_codes + row * WORDS + k_w0, vraw);
-        ksb[0] = p.k_scale[row * G + k_grp];
-        ksb[1] = p.k_bias[row * G + k_grp];
-        vsb[0] = p.v_scale[row * G + k_grp];
-        vsb[1] = p.v_bias[row * G + k_grp];
+        const int64_t row0 = tile_row0(t0, ok);
+        const int64_t krow = row0 + k_tok, vrow = row0 + v_tok;
+        load_words(p.k_codes + krow * SK::WORDS + (k_on ? k_w0 : 0), kraw);
+        load_words(p.v_codes + vrow * SV::WORDS + (v_on ? v_w0 : 0), vraw);
+        ksb[0] = p.k_scale[krow * GK + (k_on ? k_grp : 0)];
+        ksb[1] = p.k_bias[krow * GK + (k_on ? k_grp : 0)];
+        vsb[0] = p.v_scale[vrow * GV + (v_on ? v_grp : 0)];
+        vsb[1] = p.v_bias[vrow * GV + (v_on ? v_grp : 0)];
     };
     // dequantize the staged words of one row into LDS.  Rows of an unreachable block and rows at or past t_end
     // (never visible, possibly never written) become zeros, so that no stale bit pattern can reach an accumulator.
@@ -257,8 +272,8 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     };
     // rows of an unreachable block and rows at or past t_end (never visible, possibly never written) become zeros,
     // so that no stale bit pattern can reach an accumulator
-    auto row_ok = [&](int t0, bool ok_tile) { return ok_tile && (t0 + k_tok < t_end); };
-    const int k_dst = k_tok * KPITCH + k_w0 * 8, v_dst = k_tok * VPITCH + k_w0 * 8;
+    auto row_ok = [&](int t0, int tok, bool ok_tile) { return ok_tile && (t0 + tok < t_end); };
+    const int k_dst = k_tok * KPITCH + k_w0 * 8, v_dst = v_tok * VPITCH + v_w0 * 8;
 
     // transposing read of V_hat: this lane's address inside a tile for (16-dim tile 0, 32-token block 0, first
     // half): token 4 kb + (lane % 16) / 4, dims 4 (lane % 4) ..
@@ -271,11 +286,15 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     const int t_last = t_begin < t_end ? t_begin + (t_end - 1 - t_begin) / kTile * kTile : 0; // start of the last tile
     if (t_begin < t_end) {
         load_tile(t_begin, ok_next);
-        const RowDequant kr = row_params(ksb, row_ok(t_begin, ok_next)), vr = row_params(vsb, row_ok(t_begin, ok_next));
+        const RowDequant kr = row_params(ksb, row_ok(t_begin, k_tok, ok_next));
+        const RowDequant vr = row_params(vsb, row_ok(t_begin, v_tok, ok_next));
+        if (k_on) {
 #pragma unroll
-        for (int w = 0; w < WPT; ++w) {
-            store_word(k_lds[0] + k_dst + 8 * w, kraw[w], kr);
-            store_word(v_lds[0] + v_dst + 8 * w, vraw[w], vr);
+            for (int w = 0; w < SK::WPT; ++w) store_word(k_lds[0] + k_dst + 8 * w, kraw[w], kr);
+        }
+        if (v_on) {
+#pragma unroll
+            for (int w = 0; w < SV::WPT; ++w) store_word(v_lds[0] + v_dst + 8 * w, vraw[w], vr);
         }
         ok_cur = ok_next;
         if (t_begin + kTile < t_end) load_tile(t_begin + kTile, ok_next);
@@ -290,8 +309,8 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         // idle buffer: straight-line code keeps the mix.
         const bool ok_this = ok_cur;
         const bool more = t0 + kTile < t_end;
-        const RowDequant kr = row_params(ksb, row_ok(t0 + kTile, ok_next && more));
-        const RowDequant vr = row_params(vsb, row_ok(t0 + kTile, ok_next && more));
+        const RowDequant kr = row_params(ksb, row_ok(t0 + kTile, k_tok, ok_next && more));
+        const RowDequant vr = row_params(vsb, row_ok(t0 + kTile, v_tok, ok_next && more));
         float4_t st[QT][kTile / 16]; // [q tile][token tile]: lane column = query row, regs = tokens 4*kb .. 4*kb+3
 #pragma unroll
         for (int qi = 0; qi < QT; ++qi)
@@ -318,8 +337,8 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
                                                                         st[qi][tt], 0, 0, 0);
             // words of the K row spread evenly over the steps
 #pragma unroll
-            for (int w = 0; w < WPT; ++w)
-                if (w * KSTEPS / WPT == ks) store_word(k_lds[buf ^ 1] + k_dst + 8 * w, kraw[w], kr);
+            for (int w = 0; w < SK::WPT; ++w)
+                if (w * KSTEPS / SK::WPT == ks && k_on) store_word(k_lds[buf ^ 1] + k_dst + 8 * w, kraw[w], kr);
             __builtin_amdgcn_sched_barrier(0);
         }
 
@@ -406,8 +425,8 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
                 for (int qi = 0; qi < QT; ++qi)
                     o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va[et % (VA_AHEAD + 1)][tb], pt[qi][tb], o_acc[qi][et], 0, 0, 0);
 #pragma unroll
-            for (int w = 0; w < WPT; ++w)
-                if (w * ETILES / WPT == et) store_word(v_lds[buf ^ 1] + v_dst + 8 * w, vraw[w], vr);
+            for (int w = 0; w < SV::WPT; ++w)
+                if (w * ETILES / SV::WPT == et && v_on) store_word(v_lds[buf ^ 1] + v_dst + 8 * w, vraw[w], vr);
             __builtin_amdgcn_sched_barrier(0);
         }
         ok_cur = ok_next;
@@ -425,7 +444,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         const int r_w = wave * kRowsWave + qi * 16 + qn;
         const int head = kvh * NREP + r_w % NREP;
         const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-        uint16_t *dst = p.out + ((q_agent + row_pos[qi]) * p.q_heads + head) * D;
+        uint16_t *dst = p.out + ((q_agent + row_pos[qi]) * p.q_heads + head) * DV;
 #pragma unroll
         for (int et = 0; et < ETILES; ++et) {
             uint16_t *d8 = dst + et * 16 + 8 * (kb / 2) + 2 * (kb % 2); // the word of 8 dims, dims 0.. or 2..
@@ -437,10 +456,10 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     }
 }
 
-template <int D, int NREP>
+template <int DK, int DV, int NREP>
 hipError_t launch_chunk_t(const AttentionArgs &a, hipStream_t stream)
 {
-    constexpr int QT = D >= 256 ? 1 : 2;
+    constexpr int QT = DK >= 256 ? 1 : 2;
     constexpr int kThreads = kRowsWG / (16 * QT) * kWave;
     ChunkParams p;
     p.k_codes = a.k.codes; p.k_scale = a.k.scale; p.k_bias = a.k.bias;
@@ -461,18 +480,18 @@ hipError_t launch_chunk_t(const AttentionArgs &a, hipStream_t stream)
     const int64_t grid = units_padded * p.q_tiles;
     if (grid <= 0) return hipSuccess;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((chunk_attention_kernel<D, NREP, QT>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((chunk_attention_kernel<DK, DV, NREP, QT>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 
-template <int D>
+template <int DK, int DV>
 hipError_t launch_chunk_d(const AttentionArgs &a, int n_rep, hipStream_t stream)
 {
     switch (n_rep) {
-    case 1: return launch_chunk_t<D, 1>(a, stream);
-    case 2: return launch_chunk_t<D, 2>(a, stream);
-    case 4: return launch_chunk_t<D, 4>(a, stream);
-    case 8: return launch_chunk_t<D, 8>(a, stream);
+    case 1: return launch_chunk_t<DK, DV, 1>(a, stream);
+    case 2: return launch_chunk_t<DK, DV, 2>(a, stream);
+    case 4: return launch_chunk_t<DK, DV, 4>(a, stream);
+    case 8: return launch_chunk_t<DK, DV, 8>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -483,17 +502,19 @@ bool chunk_supported(const q4kv_spec &s)
 {
     const int n_rep = s.num_q_heads / s.num_kv_heads;
     const bool rep_ok = n_rep == 1 || n_rep == 2 || n_rep == 4 || n_rep == 8;
-    const bool dims_ok = (s.k_dim == 64 || s.k_dim == 128 || s.k_dim == 256) && s.v_dim == s.k_dim && !s.v_aliases_k;
-    return rep_ok && dims_ok;
+    const bool square = (s.k_dim == 64 || s.k_dim == 128 || s.k_dim == 256) && s.v_dim == s.k_dim;
+    const bool mla_per_head = s.k_dim == 192 && s.v_dim == 128; // decompressed per-head MLA cache (Sec. 3.6)
+    return rep_ok && (square || mla_per_head) && !s.v_aliases_k;
 }
 
 hipError_t launch_chunk_attention(const AttentionArgs &a, hipStream_t stream)
 {
     const int n_rep = a.spec.num_q_heads / a.spec.num_kv_heads;
     switch (a.spec.k_dim) {
-    case 64: return launch_chunk_d<64>(a, n_rep, stream);
-    case 128: return launch_chunk_d<128>(a, n_rep, stream);
-    case 256: return launch_chunk_d<256>(a, n_rep, stream);
+    case 64: return launch_chunk_d<64, 64>(a, n_rep, stream);
+    case 128: return launch_chunk_d<128, 128>(a, n_rep, stream);
+    case 192: return launch_chunk_d<192, 128>(a, n_rep, stream);
+    case 256: return launch_chunk_d<256, 256>(a, n_rep, stream);
     default: return hipErrorInvalidValue;
     }
 }

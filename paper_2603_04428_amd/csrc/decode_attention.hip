@@ -183,8 +183,8 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
 
 // ---------------------------------------------------------------------------------------------- loads
 
-// One token's scales or biases (N binary16 values, N = 1, 2 or a multiple of 4) as raw bits: loaded with one
-// 2-, 4- or 8-byte load per 4 values and converted only where they are used, so that issuing the load never
+// One token's scales or biases (N binary16 values) as raw bits: loaded with one 2-, 4- or 8-byte load per 4
+// values where the row width allows it and converted only where they are used, so that issuing the load never
 // makes the wave wait for it.
 template <int N>
 struct GroupBits {
@@ -199,14 +199,18 @@ __device__ __forceinline__ GroupBits<N> load_groups(const uint16_t *p)
         r.w[0] = *p;
     } else if constexpr (N == 2) {
         r.w[0] = *reinterpret_cast<const uint32_t *>(p);
-    } else {
-        static_assert(N % 4 == 0, "group count");
+    } else if constexpr (N % 4 == 0) {
 #pragma unroll
         for (int i = 0; i < N / 4; ++i) {
             const uint2 t = reinterpret_cast<const uint2 *>(p)[i];
             r.w[2 * i] = t.x;
             r.w[2 * i + 1] = t.y;
         }
+    } else { // rows of 2 N bytes are only 2-byte aligned: one load per value
+#pragma unroll
+        for (int i = 0; i < (N + 1) / 2; ++i) r.w[i] = 0;
+#pragma unroll
+        for (int i = 0; i < N; ++i) r.w[i / 2] |= (uint32_t)p[i] << (16 * (i & 1));
     }
     return r;
 }
@@ -252,7 +256,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 {
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
     // K side (matrix core): lane = (token j = lane % 16 of a 16-token set, k-block kb = lane / 16)
-    constexpr int KWPL = DK >= 128 ? 4 : 2;        // words a lane loads per chunk (16 or 8 bytes)
+    constexpr int KWPL = DK % 128 == 0 ? 4 : 2;    // words a lane loads per chunk (16 or 8 bytes)
     constexpr int KCHUNKS = DK / (32 * KWPL);      // chunks per row: 4 lanes * KWPL words each
     constexpr int KGPC = KWPL == 4 ? 2 : 1;        // quantization groups per chunk
     constexpr int KSETS = kWave / 16;              // 16-token sets per tile
@@ -694,8 +698,9 @@ bool decode_supported(const q4kv_spec &s)
 {
     const int n_rep = s.num_q_heads / s.num_kv_heads;
     const bool rep_ok = n_rep == 1 || n_rep == 2 || n_rep == 4 || n_rep == 8;
-    const bool dims_ok = (s.k_dim == 64 || s.k_dim == 128 || s.k_dim == 256) && s.v_dim == s.k_dim && !s.v_aliases_k;
-    return rep_ok && dims_ok;
+    const bool square = (s.k_dim == 64 || s.k_dim == 128 || s.k_dim == 256) && s.v_dim == s.k_dim;
+    const bool mla_per_head = s.k_dim == 192 && s.v_dim == 128; // decompressed per-head MLA cache (Sec. 3.6)
+    return rep_ok && (square || mla_per_head) && !s.v_aliases_k;
 }
 
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
@@ -706,6 +711,7 @@ hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
     switch (a.spec.k_dim) {
     case 64: return launch_decode_d<64, 64>(a, n_rep, stream);
     case 128: return launch_decode_d<128, 128>(a, n_rep, stream);
+    case 192: return launch_decode_d<192, 128>(a, n_rep, stream);
     case 256: return launch_decode_d<256, 256>(a, n_rep, stream);
     default: return hipErrorInvalidValue;
     }

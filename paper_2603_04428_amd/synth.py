@@ -226,6 +226,12 @@ def config(i: int) -> Workload:
     raise ValueError(i)
 
 
+def per_head_mla_config() -> Workload:
+    """The decompressed per-head form of the MLA cache (keys 192 = 128 + 64 rotary, values 128, one KV head per
+    query head): 5 agents x 8,192 tokens x 27 layers, 3.2 GB of Q4."""
+    return Workload("dsv2lite_mla_per_head_5agents_27layers_8k_decode", 5, 27, 16, 16, 192, 128, False, [8192] * 5)
+
+
 def small(seed, num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, seq_lens=(300,),
           q_len=1, name="small") -> Workload:
     return Workload(name, seed, num_layers, num_q_heads, num_kv_heads, k_dim, k_dim if v_dim is None else v_dim,

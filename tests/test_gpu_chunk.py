@@ -43,13 +43,19 @@ SHAPES = [
     (1, 2, 2, 256, (513, 64), 129),          # n_rep 1: 128 positions per tile, ragged last tile
     (1, 16, 8, 256, (100,), 64),
     (1, 8, 1, 64, (1000, 40), 33),           # n_rep 8
+    # decompressed per-head MLA cache (Sec. 3.6): keys 192, values 128, one KV head per query head; the K rows of a
+    # tile do not divide evenly among the threads of a workgroup
+    (1, 4, 4, (192, 128), (300, 0), 130),
+    (2, 16, 16, (192, 128), (70, 513), 40),
+    (1, 8, 4, (192, 128), (257,), 64),
 ]
 
 
 @pytest.mark.parametrize("shape", SHAPES)
 def test_chunk_matches_oracle_small(shape):
     L, Hq, Hkv, D, lens, C = shape
-    w = synth.small(41, L, Hq, Hkv, D, D, False, lens, q_len=C)
+    Dk, Dv = D if isinstance(D, tuple) else (D, D)
+    w = synth.small(41, L, Hq, Hkv, Dk, Dv, False, lens, q_len=C)
     got, _ = append_chunk_and_attend(w)
     ospec, okp, ovp, otable = host_cache(w)                  # cache + chunk, quantized by the oracle
     want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, w.final_lens(), w.sm_scale)

@@ -43,11 +43,21 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("shape", SMALL)
+PER_HEAD_MLA = [
+    # the decompressed per-head cache of Sec. 3.6: keys 192 wide (128 + 64 rotary), values 128 wide, one KV head
+    # per query head (K and V pools of different row widths, three K groups per row)
+    (2, 16, 16, (192, 128), (37, 300, 1, 64)),
+    (1, 4, 4, (192, 128), (700, 257)),
+    (1, 8, 4, (192, 128), (513,)),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL + PER_HEAD_MLA)
 @pytest.mark.parametrize("split_tokens", [0, 256, 512])
 def test_decode_matches_oracle_small(shape, split_tokens):
     L, Hq, Hkv, D, lens = shape
-    w = synth.small(31, L, Hq, Hkv, D, D, False, lens)
+    Dk, Dv = D if isinstance(D, tuple) else (D, D)
+    w = synth.small(31, L, Hq, Hkv, Dk, Dv, False, lens)
     spec, kpool, vpool, table, table_d = gpu_cache(w)
     ospec, okp, ovp, otable = host_cache(w)
     # the two quantizers must agree before attention is compared (same Q4 cache on both sides)
@@ -201,4 +211,21 @@ def test_full_size_configs_sampled_units(cfg, split_tokens):
         want = oracle_unit(w, l, a, h, w.seq_lens[a])
         assert_close(got[l, a, :, h * R:(h + 1) * R], want, f"config {cfg} unit layer {l} agent {a} kv head {h}")
     # property at any size: outputs are convex combinations of V rows, so bounded by the cache's value range
+    assert float(np.abs(got.astype(np.float32)).max()) < 6.0
+
+
+def test_per_head_mla_full_size_sampled_units():
+    """The decompressed per-head MLA cache (keys 192, values 128, 16 KV heads, 27 layers, 5 agents x 8,192 tokens) in
+    the launch configuration the benchmark times; the oracle recomputes a seeded sample of units from the generator."""
+    w = synth.per_head_mla_config()
+    spec, kpool, vpool, table, table_d = gpu_cache(w, poison=False, extra_blocks=0)
+    got = run_gpu(w, spec, kpool, vpool, table_d, w.seq_lens)
+    assert not np.isnan(got.astype(np.float32)).any()
+    rng = np.random.default_rng(5)
+    units = {(0, 0, 0), (w.num_layers - 1, w.num_agents - 1, w.num_kv_heads - 1)}
+    while len(units) < 8:
+        units.add((int(rng.integers(w.num_layers)), int(rng.integers(w.num_agents)), int(rng.integers(w.num_kv_heads))))
+    for (l, a, h) in sorted(units):
+        want = oracle_unit(w, l, a, h, w.seq_lens[a])
+        assert_close(got[l, a, :, h:h + 1], want, f"per-head MLA unit layer {l} agent {a} kv head {h}")
     assert float(np.abs(got.astype(np.float32)).max()) < 6.0
