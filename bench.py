@@ -22,6 +22,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
 
+# HBM bytes per launch of each workload's dominant kernel, read + written, from the rocprofv3 --pmc runs whose
+# summaries are under profiles/ (FETCH_SIZE and WRITE_SIZE scaled by what a plain copy of known size reads)
+MEASURED_TRAFFIC = {
+    "decode": 4755095552 + 12307456,
+    "dsv2lite_mla_latent_5agents_27layers_32k_decode": 1444208640 + 53625856,
+    "dsv2lite_mla_per_head_5agents_27layers_8k_decode": 3187363840,   # reads only (no WRITE_SIZE run)
+}
+
+
 def cpu_baseline(w, layers):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: all agents and heads of a few
     layers.  Returns the JSON object; GB/s counts the same algorithmic Q4 bytes as the GPU figure."""
@@ -234,7 +243,9 @@ def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
         "decode_ms_min": min(dec), "decode_bytes": decode_bytes,
         "matrix_TFLOPs": flops / (dec_ms * 1e-3) / 1e12,
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": gbps / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC.get(w.name) if not args.split_tokens else None,
+                     "traffic_source": "profiles/ (FETCH_SIZE + WRITE_SIZE of the kernel, scaled)",
                      "kernel": kernel_name},
     }
     print(json.dumps(res))
@@ -255,6 +266,10 @@ def main():
                          "(10 agents, 4,096..32,768 cached tokens, 512-token chunk), reported as TFLOP/s; latent: "
                          "decode over the shared-latent (MLA-shaped) cache, 5 agents x 32,768 tokens x 27 layers; per-head: "
                          "decode over the decompressed form of that cache (keys 192, values 128, 16 KV heads)")
+    ap.add_argument("--per-layer-graph", action="store_true",
+                    help="decode workload: also time the same step issued as one call per layer, recorded into a graph "
+                         "and replayed (adds 'per_layer_graph_ms'; leave it out of profiler runs, whose per-kernel "
+                         "averages it would mix with the single-launch figures)")
     ap.add_argument("--layer-windows", choices=["global", "mixed"], default="global",
                     help="decode workload only.  global (default, the headline configuration): every layer attends "
                          "to the whole cache; mixed: five layers with a 1,024-token sliding window, then one global "
@@ -353,7 +368,9 @@ def main():
     probe_gbps = probe_bytes / (percentile(probe, 50) * 1e-3) / 1e9
 
     # the same step as one call per layer, recorded once into a graph and replayed (launch-bound form of the loop)
-    per_layer_ms = per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, window, out)
+    per_layer_ms = None
+    if args.per_layer_graph:
+        per_layer_ms = per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, window, out)
 
     res = {
         "metric": "Q4 KV decode-attention achieved HBM GB/s (% of peak) + agent-tokens/s",
@@ -372,8 +389,13 @@ def main():
         "per_layer_graph_ms": per_layer_ms, "seed": w.seed,
         "quantize_ms": qua_ms, "quantize_GBps": quant_bytes / (qua_ms * 1e-3) / 1e9,
         "dequantize_ms": deq_ms, "dequantize_GBps": quant_bytes / (deq_ms * 1e-3) / 1e9,
+        # traffic: HBM bytes of one launch of the dominant kernel, from the committed rocprofv3 counter runs (they
+        # cannot be taken inside this process); only for the exact workload those runs measured
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": gbps / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC["decode"] if args.layer_windows == "global" and not args.split_tokens
+                     else None,
+                     "traffic_source": "profiles/decode_attention_gemma10_ragged.md (FETCH_SIZE + WRITE_SIZE, scaled)",
                      "kernel": "decode_attention_kernel<256,256,2> (+ combine_kernel in the same call)"},
     }
     if not args.skip_cpu_baseline:

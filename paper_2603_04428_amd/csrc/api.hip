@@ -217,6 +217,9 @@ static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4k
     if (!q || !out || !block_table || !seq_len) return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(q) || !aligned16(out)) return fail(Q4KV_EINVAL, "q and out must be 16-byte aligned");
     const int layers = layer_end - layer_begin;
+    // the kernels number the 64-token tiles of a call with 32-bit integers
+    if ((int64_t)layers * spec->num_kv_heads * num_agents * (((int64_t)max_seq_len + 63) / 64 + 1) > 0x7fffffffLL)
+        return fail(Q4KV_ERANGE, "more than 2^31 tiles in one call: split the layer range");
 
     q4kv::AttentionArgs a;
     a.spec = *spec;

@@ -89,22 +89,37 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
     pv.plan = plan;
     pv.A = num_agents;
     pv.L = layers;
-    // ---- classes of equal windows (a handful at most in practice)
-    if (tid == 0) {
-        int C = 0;
-        if (lw.uniform) {
+    // ---- classes of equal windows (a handful at most in practice), numbered in the order of their first layer.
+    // Thread li finds the first layer with its window; the class of a layer is the number of such first layers
+    // before its own.
+    __shared__ int s_first[kMaxWindowLayers];
+    static_assert(kThreads >= kMaxWindowLayers, "one thread per layer");
+    if (lw.uniform) {
+        if (tid == 0) {
             s_win[0] = lw.window > 0 ? lw.window : 0;
-            C = 1;
-        } else {
-            for (int li = 0; li < layers; ++li) {
-                const int w = lw.w[li] > 0 ? lw.w[li] : 0;
-                int c = 0;
-                while (c < C && s_win[c] != w) ++c;
-                if (c == C) s_win[C++] = w;
-                s_cls[li] = c;
+            s_classes = 1;
+        }
+    } else {
+        const int li = tid < layers ? tid : 0; // kThreads >= kMaxWindowLayers
+        const int w_li = lw.w[li] > 0 ? lw.w[li] : 0;
+        int first = li;
+        for (int j = layers - 1; j >= 0; --j) {
+            const int w_j = lw.w[j] > 0 ? lw.w[j] : 0; // wave-uniform
+            if (j < li && w_j == w_li) first = j;
+        }
+        if (tid < layers) s_first[tid] = first;
+        __syncthreads();
+        if (tid < layers) {
+            int c = 0;
+            for (int k = 0; k < first; ++k) c += s_first[k] == k ? 1 : 0;
+            s_cls[tid] = c;
+            if (first == tid) s_win[c] = w_li;
+            if (tid == layers - 1) { // classes in all = first layers up to the last layer
+                int total = c;
+                for (int k = first; k < layers; ++k) total += s_first[k] == k ? 1 : 0;
+                s_classes = total;
             }
         }
-        s_classes = C;
     }
     __syncthreads();
     const int C = s_classes;
@@ -164,18 +179,46 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
         }
     }
     __syncthreads();
-    // ---- tiles before every layer, the waves' share
-    if (tid == 0) {
-        long long total = 0;
-        for (int li = 0; li < layers; ++li) {
-            plan[pv.lt_off() + li] = (int)total;
-            total += (long long)s_tt[lw.uniform ? 0 : s_cls[li]] * kv_heads;
+    // ---- tiles before every layer (prefix sum over the layers, one thread each; the host keeps the total below
+    // 2^31), the waves' share
+    if (layers <= kThreads) {
+        const int mine = tid < layers ? s_tt[lw.uniform ? 0 : s_cls[tid]] * kv_heads : 0;
+        int incl = mine;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
         }
-        plan[pv.lt_off() + layers] = (int)total;
-        long long per = (total + total_waves - 1) / total_waves;
+        if (lane == kWave - 1) s_wave_sum[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const int t = s_wave_sum[w];
+            if (w < wave) before += t;
+            total += t;
+        }
+        if (tid < layers) plan[pv.lt_off() + tid] = before + incl - mine;
+        if (tid == 0) {
+            plan[pv.lt_off() + layers] = total;
+            int per = (int)(((long long)total + total_waves - 1) / total_waves);
+            if (per < min_tiles_per_wave) per = min_tiles_per_wave;
+            plan[0] = total;
+            plan[1] = per;
+            plan[2] = C;
+            plan[3] = layers;
+        }
+    } else if (tid == 0) { // more layers than threads: one window for all of them (see kMaxWindowLayers)
+        int total = 0;
+        for (int li = 0; li < layers; ++li) {
+            plan[pv.lt_off() + li] = total;
+            total += s_tt[0] * kv_heads;
+        }
+        plan[pv.lt_off() + layers] = total;
+        int per = (int)(((long long)total + total_waves - 1) / total_waves);
         if (per < min_tiles_per_wave) per = min_tiles_per_wave;
-        plan[0] = (int)total;
-        plan[1] = (int)per;
+        plan[0] = total;
+        plan[1] = per;
         plan[2] = C;
         plan[3] = layers;
     }
