@@ -196,6 +196,113 @@ def bench_per_head(args, torch, b, synth, build_device_cache):
                              "decode_attention_kernel<192,128,1> (+ combine_kernel in the same call)")
 
 
+def bench_restore(args, torch, b, synth, build_device_cache):
+    """Save / restore of one agent's cache (Sec. 3.1, 3.2 "Q4 at rest"): a Gemma-3-12B-shaped agent of 32,768 tokens
+    (128 blocks x 48 layers, 3.6 GB of Q4) is gathered into a block image and scattered back, device to device and
+    straight to / from pinned host memory, and restored from host memory while ten other agents decode."""
+    dev = "cuda"
+    w = synth.config(2)
+    spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=128)
+    nb = 128
+    ids = torch.arange(kpool.num_blocks - nb, kpool.num_blocks, dtype=torch.int32, device=dev)  # the spare blocks
+    for pool in (kpool, vpool):            # give the agent to be saved some contents
+        pool.codes[:, ids.long()] = torch.randint(-2 ** 31, 2 ** 31 - 1, pool.codes[:, :nb].shape, dtype=torch.int32,
+                                                  device=dev)
+        pool.scale[:, ids.long()] = 0x3000
+        pool.bias[:, ids.long()] = 0x3800
+    nbytes = b.q4kv_block_image_bytes(spec, nb)
+    dev_image = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    host_image = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return percentile(ts, 50)
+
+    reps = max(3, min(args.steps, 10))
+    t_exp_dev = timed(lambda: b.q4kv_export_blocks(spec, kpool, vpool, ids, dev_image), reps)
+    t_imp_dev = timed(lambda: b.q4kv_import_blocks(spec, kpool, vpool, ids, dev_image), reps)
+    t_exp_host = timed(lambda: b.q4kv_export_blocks(spec, kpool, vpool, ids, host_image), reps)
+    t_imp_host = timed(lambda: b.q4kv_import_blocks(spec, kpool, vpool, ids, host_image), reps)
+    assert torch.equal(host_image, dev_image.cpu())
+
+    # restore from host memory on a second stream while the ten resident agents decode on the first
+    q = w.q_all(dev)
+    seq = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
+    max_len = max(w.seq_lens)
+    split = b.q4kv_default_split_tokens(spec, w.num_agents, 1, max_len, w.num_layers)
+    ws = torch.empty(b.q4kv_attention_workspace_bytes(spec, w.num_agents, 1, max_len, split, w.num_layers),
+                     dtype=torch.uint8, device=dev)
+    out = torch.empty((w.num_layers, w.num_agents, 1, w.num_q_heads, w.v_dim), dtype=torch.float16, device=dev)
+
+    def decode():
+        b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, seq, max_len, w.sm_scale, 0, split, 0, None, out, ws)
+
+    def restore_direct():          # the import kernel reads the pinned host image itself
+        b.q4kv_import_blocks(spec, kpool, vpool, ids, host_image)
+
+    def restore_staged():          # a copy engine brings the image over, the import kernel scatters it on the device
+        dev_image.copy_(host_image, non_blocking=True)
+        b.q4kv_import_blocks(spec, kpool, vpool, ids, dev_image)
+
+    t_imp_staged = timed(restore_staged, reps)
+    t_dec_alone = timed(decode, 20)
+    side = torch.cuda.Stream()
+
+    def overlapped(restore):
+        """restore on the side stream while decode steps run on the main one -> (restore ms, ms per decode step, steps)"""
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            r0.record()
+            restore()
+            r1.record()
+        steps = []
+        while not r1.query():
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            decode()
+            e1.record()
+            e1.synchronize()
+            steps.append(e0.elapsed_time(e1))
+        torch.cuda.synchronize()
+        inside = steps[:-1] if len(steps) > 1 else steps   # the last step may outlive the restore
+        return r0.elapsed_time(r1), percentile(inside, 50), len(steps)
+
+    ov_direct = overlapped(restore_direct)
+    ov_staged = overlapped(restore_staged)
+
+    copy_gbps = 2.0 * nbytes / (t_exp_dev * 1e-3) / 1e9
+    res = {
+        "metric": "Q4 KV cache restore: block image -> pool GB/s + restore time of a 32K-token agent",
+        "value": nbytes / (t_imp_host * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": reps, "warmup": 1,
+        "ms_per_step": t_imp_host, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8 (bytes moved as they are)", "data": "synthetic",
+        "config": {"workload": "gemma12b_one_agent_32k_tokens_48layers_restore", "blocks": nb, "layers": w.num_layers,
+                   "image_bytes": nbytes},
+        "restore_from_pinned_host_ms": t_imp_host, "restore_from_pinned_host_GBps": nbytes / (t_imp_host * 1e-3) / 1e9,
+        "save_to_pinned_host_ms": t_exp_host, "save_to_pinned_host_GBps": nbytes / (t_exp_host * 1e-3) / 1e9,
+        "export_device_ms": t_exp_dev, "import_device_ms": t_imp_dev,
+        "device_copy_GBps_read_plus_write": copy_gbps,
+        "restore_via_copy_engine_ms": t_imp_staged,
+        "decode_ms_alone": t_dec_alone,
+        "during_decode_direct": {"restore_ms": ov_direct[0], "decode_ms": ov_direct[1], "decode_steps": ov_direct[2]},
+        "during_decode_copy_engine": {"restore_ms": ov_staged[0], "decode_ms": ov_staged[1], "decode_steps": ov_staged[2]},
+        "roofline": {"bound": "hbm", "achieved": copy_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": copy_gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "image_copy_kernel<true> (pool -> device image; bytes read + written)"},
+    }
+    print(json.dumps(res))
+
+
 def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
     dev = "cuda"
     spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0)
@@ -261,11 +368,12 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (a known-size reference for scaling "
                          "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head", "restore"], default="decode",
                     help="decode (default): the headline configuration; append: the chunked-append configuration "
                          "(10 agents, 4,096..32,768 cached tokens, 512-token chunk), reported as TFLOP/s; latent: "
                          "decode over the shared-latent (MLA-shaped) cache, 5 agents x 32,768 tokens x 27 layers; per-head: "
-                         "decode over the decompressed form of that cache (keys 192, values 128, 16 KV heads)")
+                         "decode over the decompressed form of that cache (keys 192, values 128, 16 KV heads); restore: save "
+                         "and restore of one 32,768-token agent through a block image, also while other agents decode")
     ap.add_argument("--per-layer-graph", action="store_true",
                     help="decode workload: also time the same step issued as one call per layer, recorded into a graph "
                          "and replayed (adds 'per_layer_graph_ms'; leave it out of profiler runs, whose per-kernel "
@@ -291,6 +399,8 @@ def main():
         return bench_latent(args, torch, b, synth, build_device_cache)
     if args.workload == "per-head":
         return bench_per_head(args, torch, b, synth, build_device_cache)
+    if args.workload == "restore":
+        return bench_restore(args, torch, b, synth, build_device_cache)
     w = synth.config(2)
     spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0)
     q = w.q_all(dev)

@@ -152,6 +152,27 @@ int32_t q4kv_default_split_tokens(const q4kv_spec *spec, int32_t num_agents, int
  * Negative on bad arguments. */
 int64_t q4kv_cache_bytes(const q4kv_spec *spec, int64_t tokens);
 
+/* Saving and restoring an agent's cache (Sec. 3.1 block pool; Sec. 3.2 "Q4 at rest"; appendix "safetensors Q4
+ * Format": one tensor per layer, block and array, Q4 on disk exactly as in memory, so that a restore is a copy and
+ * no prefill).  A block image is the contiguous form of `num_blocks` listed blocks of every layer of the spec:
+ *   for layer l = 0 .. num_layers-1, for i = 0 .. num_blocks-1 (block block_ids[i]):
+ *     K codes uint32 [kv_heads][256][k_dim/8], K scale binary16 [kv_heads][256][k_dim/64], K bias (same shape),
+ *     V codes, V scale, V bias likewise with v_dim (absent when v_aliases_k)
+ * i.e. the pool's own bytes of that (layer, block), array after array.  q4kv_block_image_bytes gives its size
+ * (0 on bad arguments).  q4kv_export_blocks gathers pool -> image, q4kv_import_blocks scatters image -> pool
+ * (into whatever blocks block_ids names now: a restored agent need not get its old blocks back).
+ *   block_ids  device, int32 [num_blocks]; an id outside [0, pool.num_blocks) is skipped (its records are left
+ *              untouched on export, nothing is written on import)
+ *   image      device (or pinned host memory the GPU can address), 16-byte aligned, at least image_bytes long
+ *              With the image in host memory the launch is kept small (the host link, not the chip, is the
+ *              limit), so that it can run beside a decode step on another stream.
+ * Enqueue on hip_stream, allocate nothing, never synchronise.  Q4KV_EWORKSPACE when image_bytes is too small. */
+size_t q4kv_block_image_bytes(const q4kv_spec *spec, int32_t num_blocks);
+int q4kv_export_blocks(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const int32_t *block_ids,
+                       int32_t num_blocks, void *image, size_t image_bytes, void *hip_stream);
+int q4kv_import_blocks(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const int32_t *block_ids,
+                       int32_t num_blocks, const void *image, size_t image_bytes, void *hip_stream);
+
 /* Measurement helper, no part of the method: a kernel that only reads.  Reads the first
  * floor(bytes / 16384) * 16384 bytes of the device buffer `src` (16-byte aligned) exactly once, in the launch
  * shape and with the load width of the decode kernel, and writes nothing except, possibly, the one device word

@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libq4kv.so")
 
 EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_append", "q4kv_batched_attention",
-           "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_read_probe", "q4kv_last_error",
+           "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_block_image_bytes", "q4kv_export_blocks", "q4kv_import_blocks", "q4kv_read_probe",
+           "q4kv_last_error",
            "q4kv_version"]
 
 
@@ -63,6 +64,10 @@ def lib():
         l.q4kv_cache_bytes.restype = i64
         l.q4kv_cache_bytes.argtypes = [C.POINTER(Spec), i64]
         l.q4kv_read_probe.argtypes = [vp, C.c_size_t, vp, vp]
+        l.q4kv_block_image_bytes.restype = C.c_size_t
+        l.q4kv_block_image_bytes.argtypes = [C.POINTER(Spec), i32]
+        for f in (l.q4kv_export_blocks, l.q4kv_import_blocks):
+            f.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, i32, vp, C.c_size_t, vp]
         l.q4kv_last_error.restype = C.c_char_p
         l.q4kv_version.restype = C.c_int
         _lib = l
@@ -119,6 +124,33 @@ def q4kv_cache_bytes(spec, tokens):
     if r < 0:
         _check(-1)
     return r
+
+
+def q4kv_block_image_bytes(spec, num_blocks):
+    return lib().q4kv_block_image_bytes(C.byref(spec), num_blocks)
+
+
+def _image_call(fn, spec, kpool, vpool, block_ids, image):
+    """block_ids: int32 tensor on the GPU; image: uint8 tensor on the GPU or in pinned host memory."""
+    if not (image.dtype == torch.uint8 and image.is_contiguous() and (image.is_cuda or image.is_pinned())):
+        raise ValueError("image: contiguous uint8 tensor on the GPU or in pinned host memory")
+    kp = kpool.c()
+    vp = None if spec.v_aliases_k else vpool.c()
+    _check(fn(C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp), _dev(block_ids, torch.int32, "block_ids"),
+              block_ids.numel(), C.c_void_p(image.data_ptr()), image.numel(), _stream()))
+
+
+def q4kv_export_blocks(spec, kpool, vpool, block_ids, image=None):
+    """Gather the listed blocks of every layer into a block image (see include/q4kv.h); returns the image."""
+    if image is None:
+        image = torch.empty(q4kv_block_image_bytes(spec, block_ids.numel()), dtype=torch.uint8, device=block_ids.device)
+    _image_call(lib().q4kv_export_blocks, spec, kpool, vpool, block_ids, image)
+    return image
+
+
+def q4kv_import_blocks(spec, kpool, vpool, block_ids, image):
+    """Scatter a block image into the listed blocks of every layer."""
+    _image_call(lib().q4kv_import_blocks, spec, kpool, vpool, block_ids, image)
 
 
 def q4kv_read_probe(buf, sink):

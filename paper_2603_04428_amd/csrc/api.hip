@@ -293,6 +293,51 @@ int q4kv_batched_attention_windows(const q4kv_spec *spec, const q4kv_pool *k, co
                             hip_stream);
 }
 
+size_t q4kv_block_image_bytes(const q4kv_spec *spec, int32_t num_blocks)
+{
+    if (check_spec(spec) != Q4KV_OK) return 0;
+    if (num_blocks < 0) {
+        fail(Q4KV_EINVAL, "num_blocks < 0");
+        return 0;
+    }
+    return q4kv::image_record_bytes(*spec) * (size_t)spec->num_layers * (size_t)num_blocks;
+}
+
+static int block_image_common(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const int32_t *block_ids,
+                              int32_t num_blocks, void *image, size_t image_bytes, bool to_image, void *hip_stream)
+{
+    int rc = check_spec(spec);
+    if (rc) return rc;
+    if ((rc = check_pool(k, "K"))) return rc;
+    if (spec->v_aliases_k) {
+        if (v) return fail(Q4KV_EINVAL, "V pool must be NULL when v_aliases_k is set");
+    } else {
+        if ((rc = check_pool(v, "V"))) return rc;
+        if (v->num_blocks != k->num_blocks) return fail(Q4KV_EINVAL, "K and V pools differ in num_blocks");
+    }
+    if (num_blocks < 0) return fail(Q4KV_EINVAL, "num_blocks < 0");
+    if (num_blocks == 0) return Q4KV_OK;
+    if (!block_ids || !image) return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!aligned16(image)) return fail(Q4KV_EINVAL, "image must be 16-byte aligned");
+    if (image_bytes < q4kv_block_image_bytes(spec, num_blocks)) return fail(Q4KV_EWORKSPACE, "image buffer too small");
+    hipError_t e = q4kv::launch_image_copy(*spec, *k, spec->v_aliases_k ? nullptr : v, block_ids, num_blocks, image,
+                                          to_image, 8 * compute_units(), (hipStream_t)hip_stream);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "block image launch: %s", hipGetErrorString(e));
+}
+
+int q4kv_export_blocks(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const int32_t *block_ids,
+                       int32_t num_blocks, void *image, size_t image_bytes, void *hip_stream)
+{
+    return block_image_common(spec, k, v, block_ids, num_blocks, image, image_bytes, true, hip_stream);
+}
+
+int q4kv_import_blocks(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const int32_t *block_ids,
+                       int32_t num_blocks, const void *image, size_t image_bytes, void *hip_stream)
+{
+    return block_image_common(spec, k, v, block_ids, num_blocks, const_cast<void *>(image), image_bytes, false,
+                              hip_stream);
+}
+
 int q4kv_read_probe(const void *src, size_t bytes, uint32_t *sink, void *hip_stream)
 {
     if (bytes < 16384) return Q4KV_OK; // nothing to read

@@ -56,6 +56,13 @@ hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t strea
 bool chunk_supported(const q4kv_spec &spec);
 hipError_t launch_chunk_attention(const AttentionArgs &a, hipStream_t stream);
 
+// persist.hip: bytes of one (layer, block) record of a block image; gather (to_image) or scatter of `num_blocks`
+// listed blocks of every layer between the pools and the image (v: null when V aliases K)
+size_t image_record_bytes(const q4kv_spec &s);
+hipError_t launch_image_copy(const q4kv_spec &s, const q4kv_pool &k, const q4kv_pool *v, const int32_t *block_ids,
+                             int num_blocks, void *image, bool to_image, int workgroups_when_on_device,
+                             hipStream_t stream);
+
 // read_probe.hip: reads bytes / 16,384 * 16,384 bytes of `src` once; `sink` is one device word that may be written
 hipError_t launch_read_probe(const void *src, size_t bytes, uint32_t *sink, int workgroups, hipStream_t stream);
 

@@ -1,0 +1,98 @@
+"""GPU parity of the block image entry points (save / restore of an agent's cache): the exported bytes are the
+oracle-side cache's bytes, tensor by tensor through a file read back with the safetensors library; a cache restored
+into other physical blocks attends bit-identically."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_04428_amd import binding as b
+from paper_2603_04428_amd import persist, synth
+from tests.gpu_util import DEV, bits, gpu_cache, host_cache
+
+pytestmark = pytest.mark.gpu
+
+
+def attend(w, spec, kpool, vpool, table_d):
+    sl = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    out = b.q4kv_batched_attention(spec, kpool, vpool, w.q_all(DEV), table_d, sl, max(w.seq_lens), w.sm_scale)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("shape", [(2, 4, 2, 128, 128, False), (1, 16, 16, 192, 128, False), (2, 16, 1, 576, 512, True)])
+def test_export_file_import_round_trip(tmp_path, shape):
+    from safetensors.numpy import load_file
+    L, Hq, Hkv, dk, dv, alias = shape
+    w = synth.small(61, L, Hq, Hkv, dk, dv, alias, (700, 130))
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    ospec, okp, ovp, otable = host_cache(w)
+    before = attend(w, spec, kpool, vpool, table_d)
+    agent, nb = 0, 3                                                  # 700 tokens: three blocks
+    ids = table_d[agent, :nb].contiguous()
+    image = b.q4kv_export_blocks(spec, kpool, vpool, ids)
+    assert image.numel() == persist.image_bytes(spec, nb) == b.q4kv_block_image_bytes(spec, nb)
+    path = os.path.join(tmp_path, "agent0.safetensors")
+    persist.save_agent(path, spec, image.cpu(), nb, 700)
+    # every tensor of the file is the oracle-side cache's array of that (layer, block)
+    tensors = load_file(path)
+    for l in range(L):
+        for i in range(nb):
+            blk = otable[agent, i]
+            for tag, pool in (("K", okp),) + ((() if alias else (("V", ovp),))):
+                assert np.array_equal(tensors[f"L{l}_B{i}_{tag}_weights"], pool.codes[l, blk])
+                assert np.array_equal(tensors[f"L{l}_B{i}_{tag}_scales"].view(np.uint16), pool.scale[l, blk])
+                assert np.array_equal(tensors[f"L{l}_B{i}_{tag}_biases"].view(np.uint16), pool.bias[l, blk])
+    # restore into a fresh, poisoned pool at other physical blocks, through pinned host memory
+    meta, img = persist.open_agent(path)
+    assert meta["seq_len"] == 700 and meta["num_blocks"] == nb
+    pinned = torch.empty(img.size, dtype=torch.uint8, pin_memory=True)
+    persist.load_agent_into(path, pinned)
+    nb_pool = kpool.num_blocks
+    k2 = b.Pool(spec, dk, nb_pool + 2, DEV, True)
+    v2 = None if alias else b.Pool(spec, dv, nb_pool + 2, DEV, True)
+    new_ids = torch.tensor([nb_pool + 1, 0, nb_pool], dtype=torch.int32, device=DEV)
+    b.q4kv_import_blocks(spec, k2, v2, new_ids, pinned)               # the kernel reads the host image directly
+    torch.cuda.synchronize()
+    for name in ("codes", "scale", "bias"):
+        for src, dst in ((kpool, k2),) + (() if alias else ((vpool, v2),)):
+            assert torch.equal(getattr(dst, name)[:, new_ids.long()], getattr(src, name)[:, ids.long()])
+    # the second agent keeps its blocks: copy them over by hand, then both pools must attend identically
+    other = table_d[1, :1].long()
+    for name in ("codes", "scale", "bias"):
+        for src, dst in ((kpool, k2),) + (() if alias else ((vpool, v2),)):
+            getattr(dst, name)[:, other] = getattr(src, name)[:, other]
+    table2 = table_d.clone()
+    table2[agent, :nb] = new_ids
+    after = attend(w, spec, k2, v2, table2)
+    assert np.array_equal(before.view(np.uint16), after.view(np.uint16))
+
+
+def test_export_into_pinned_host_memory_and_skipped_ids():
+    w = synth.small(62, 2, 4, 2, 64, 64, False, (300,))
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    ids = table_d[0, :2].contiguous()
+    dev_image = b.q4kv_export_blocks(spec, kpool, vpool, ids)
+    pinned = torch.zeros(dev_image.numel(), dtype=torch.uint8, pin_memory=True)
+    b.q4kv_export_blocks(spec, kpool, vpool, ids, pinned)
+    torch.cuda.synchronize()
+    assert torch.equal(pinned, dev_image.cpu())
+    # an id outside the pool: its records keep whatever the image held
+    bad = ids.clone()
+    bad[1] = 10_000
+    marked = torch.full_like(dev_image, 0xA5)
+    b.q4kv_export_blocks(spec, kpool, vpool, bad, marked)
+    torch.cuda.synchronize()
+    rec = persist.image_bytes(spec, 1) // spec.num_layers
+    got, want = marked.cpu().view(spec.num_layers, 2, rec), dev_image.cpu().view(spec.num_layers, 2, rec)
+    assert torch.equal(got[:, 0], want[:, 0]) and bool((got[:, 1] == 0xA5).all())
+    before = [getattr(p, n).clone() for p in (kpool, vpool) for n in ("codes", "scale", "bias")]
+    b.q4kv_import_blocks(spec, kpool, vpool, torch.tensor([-1, 99], dtype=torch.int32, device=DEV), dev_image)
+    torch.cuda.synchronize()
+    after = [getattr(p, n) for p in (kpool, vpool) for n in ("codes", "scale", "bias")]
+    assert all(torch.equal(x, y) for x, y in zip(before, after))
+    with pytest.raises(b.Q4KVError):
+        b.q4kv_export_blocks(spec, kpool, vpool, ids, dev_image[:-16])          # image too small
+    assert b.q4kv_export_blocks(spec, kpool, vpool, ids[:0]).numel() == 0         # nothing to do
