@@ -303,6 +303,95 @@ def bench_restore(args, torch, b, synth, build_device_cache):
     print(json.dumps(res))
 
 
+def bench_mixed_step(args, torch, b, synth, build_device_cache):
+    """Iteration-level interleave of a prefill chunk with decode steps (the paper's concurrent scheduler, Sec. 3.4):
+    one more agent appends a 512-token chunk to a 16,384-token cache and attends to it (all 48 layers, matrix cores)
+    on a second stream while the ten agents of the headline workload keep decoding (HBM) on the first."""
+    dev = "cuda"
+    wd = synth.config(2)
+    spec, kpool, vpool, table, table_d = build_device_cache(wd, dev, poison=False, extra_blocks=0)
+    q = wd.q_all(dev)
+    seq = torch.tensor(wd.seq_lens, dtype=torch.int32, device=dev)
+    max_len = max(wd.seq_lens)
+    split = b.q4kv_default_split_tokens(spec, wd.num_agents, 1, max_len, wd.num_layers)
+    ws = torch.empty(b.q4kv_attention_workspace_bytes(spec, wd.num_agents, 1, max_len, split, wd.num_layers),
+                     dtype=torch.uint8, device=dev)
+    out = torch.empty((wd.num_layers, wd.num_agents, 1, wd.num_q_heads, wd.v_dim), dtype=torch.float16, device=dev)
+
+    def decode():
+        b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, seq, max_len, wd.sm_scale, 0, split, 0, None, out, ws)
+
+    wa = synth.small(6, wd.num_layers, wd.num_q_heads, wd.num_kv_heads, wd.k_dim, wd.v_dim, False, (16384,), q_len=512,
+                     name="gemma12b_1agent_16k_append512")
+    aspec, akp, avp, atable, atable_d = build_device_cache(wa, dev, poison=False, extra_blocks=0, tokens=wa.seq_lens)
+    C = wa.q_len
+    before = torch.tensor(wa.seq_lens, dtype=torch.int32, device=dev)
+    after = torch.tensor(wa.final_lens(), dtype=torch.int32, device=dev)
+    k_new = torch.stack([torch.stack([wa.k_rows(l, 0, 16384, 16384 + C, dev)]) for l in range(wa.num_layers)])
+    v_new = torch.stack([torch.stack([wa.v_rows(l, 0, 16384, 16384 + C, dev)]) for l in range(wa.num_layers)])
+    aq = wa.q_all(dev)
+    aout = torch.empty((wa.num_layers, 1, C, wa.num_q_heads, wa.v_dim), dtype=torch.float16, device=dev)
+    aws = torch.empty(16, dtype=torch.uint8, device=dev)
+    flops = 4.0 * wa.num_q_heads * wa.k_dim * (C * 16384 + C * (C + 1) / 2) * wa.num_layers
+
+    def chunk():
+        b.q4kv_append(aspec, akp, avp, k_new, v_new, atable_d, before)
+        b.q4kv_batched_attention(aspec, akp, avp, aq, atable_d, after, 16384 + C, wa.sm_scale, 0, 0, 0, None, aout, aws)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return percentile(ts, 50)
+
+    t_dec = timed(decode, 30)
+    t_chunk = timed(chunk, 10)
+    side = torch.cuda.Stream()
+    chunk_ms, dec_ms, dec_steps = [], [], []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            r0.record()
+            chunk()
+            r1.record()
+        steps = []
+        while not r1.query():
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            decode()
+            e1.record()
+            e1.synchronize()
+            steps.append(e0.elapsed_time(e1))
+        torch.cuda.synchronize()
+        chunk_ms.append(r0.elapsed_time(r1))
+        dec_ms.append(sum(steps) / len(steps))
+        dec_steps.append(len(steps))
+    t_chunk_mixed, t_dec_mixed = percentile(chunk_ms, 50), percentile(dec_ms, 50)
+    # work done per second when interleaved, relative to running the two one after the other
+    n = percentile(dec_steps, 50)
+    serial_ms = t_chunk + n * t_dec
+    res = {
+        "metric": "mixed step: decode steps of 10 agents beside one agent's 512-token append (speed-up over serial)",
+        "value": serial_ms / t_chunk_mixed, "unit": "x", "n_gpus": 1, "steps": 5, "warmup": 1,
+        "ms_per_step": t_chunk_mixed, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "q4 codes + f16 scale/bias, f32 accumulate, f16 out", "data": "synthetic",
+        "config": {"workload": wd.name + " + " + wa.name, "layers": wd.num_layers},
+        "decode_ms_alone": t_dec, "chunk_ms_alone": t_chunk, "chunk_TFLOPs_alone": flops / (t_chunk * 1e-3) / 1e12,
+        "decode_ms_beside_chunk": t_dec_mixed, "chunk_ms_beside_decode": t_chunk_mixed,
+        "decode_steps_per_chunk": n, "serial_ms_for_the_same_work": serial_ms,
+        "roofline": None,
+    }
+    print(json.dumps(res))
+
+
 def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
     dev = "cuda"
     spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0)
@@ -368,12 +457,13 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (a known-size reference for scaling "
                          "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head", "restore"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head", "restore", "mixed-step"], default="decode",
                     help="decode (default): the headline configuration; append: the chunked-append configuration "
                          "(10 agents, 4,096..32,768 cached tokens, 512-token chunk), reported as TFLOP/s; latent: "
                          "decode over the shared-latent (MLA-shaped) cache, 5 agents x 32,768 tokens x 27 layers; per-head: "
                          "decode over the decompressed form of that cache (keys 192, values 128, 16 KV heads); restore: save "
-                         "and restore of one 32,768-token agent through a block image, also while other agents decode")
+                         "and restore of one 32,768-token agent through a block image, also while other agents decode; mixed-step: "
+                         "one agent's 512-token append on a second stream beside the decode steps of ten others")
     ap.add_argument("--per-layer-graph", action="store_true",
                     help="decode workload: also time the same step issued as one call per layer, recorded into a graph "
                          "and replayed (adds 'per_layer_graph_ms'; leave it out of profiler runs, whose per-kernel "
@@ -401,6 +491,8 @@ def main():
         return bench_per_head(args, torch, b, synth, build_device_cache)
     if args.workload == "restore":
         return bench_restore(args, torch, b, synth, build_device_cache)
+    if args.workload == "mixed-step":
+        return bench_mixed_step(args, torch, b, synth, build_device_cache)
     w = synth.config(2)
     spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0)
     q = w.q_all(dev)
