@@ -654,21 +654,41 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const float *__restri
         slots = (int)((u0 + tiles - 1) / per - u0 / per) + 1;
     }
     const float *ml = part_ml + unit * max_slots * 2;
-    float m = kNegBig;
-    for (int s = 0; s < slots; ++s)
-        if (ml[2 * s + 1] > 0.0f) m = fmaxf(m, ml[2 * s]);
-    float denom = 0.0f;
-    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     const float *acc = part_acc + unit * max_slots * v_dim + e;
-    for (int s = 0; s < slots; ++s) {
-        if (!(ml[2 * s + 1] > 0.0f)) continue;
-        const float wgt = __builtin_amdgcn_exp2f(ml[2 * s] - m);
-        denom = fmaf(wgt, ml[2 * s + 1], denom);
-        const float4 a = *reinterpret_cast<const float4 *>(acc + (long long)s * v_dim);
-        o.x = fmaf(wgt, a.x, o.x);
-        o.y = fmaf(wgt, a.y, o.y);
-        o.z = fmaf(wgt, a.z, o.z);
-        o.w = fmaf(wgt, a.w, o.w);
+    // Four slots at a time: every load of a group is issued before anything is computed, so a unit costs one
+    // memory round trip per group instead of two dependent ones per slot.  The running reference moves group by
+    // group (with at most four slots: exactly the maximum over all slots, then one weighted sum in slot order).
+    float m = kNegBig, denom = 0.0f;
+    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int s0 = 0; s0 < slots; s0 += 4) {
+        float mm[4], ll[4];
+        float4 a[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const bool in = s0 + k < slots;
+            const float2 t = in ? *reinterpret_cast<const float2 *>(ml + 2 * (s0 + k)) : make_float2(kNegBig, 0.0f);
+            mm[k] = t.x;
+            ll[k] = t.y;
+            a[k] = in ? *reinterpret_cast<const float4 *>(acc + (long long)(s0 + k) * v_dim) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+        float m_new = m;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (ll[k] > 0.0f) m_new = fmaxf(m_new, mm[k]);
+        const float keep = __builtin_amdgcn_exp2f(m - m_new); // 1 when the reference stays, 0 while nothing was added yet
+        denom *= keep;
+        o.x *= keep; o.y *= keep; o.z *= keep; o.w *= keep;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (!(ll[k] > 0.0f)) continue;
+            const float wgt = __builtin_amdgcn_exp2f(mm[k] - m_new);
+            denom = fmaf(wgt, ll[k], denom);
+            o.x = fmaf(wgt, a[k].x, o.x);
+            o.y = fmaf(wgt, a[k].y, o.y);
+            o.z = fmaf(wgt, a[k].z, o.z);
+            o.w = fmaf(wgt, a[k].w, o.w);
+        }
+        m = m_new;
     }
     const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
     const uint32_t lo = (uint32_t)float_to_half_bits(o.x * inv) | ((uint32_t)float_to_half_bits(o.y * inv) << 16);
