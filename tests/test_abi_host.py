@@ -104,6 +104,46 @@ def test_append_argument_errors():
     assert call(spec=mla, vp=vp) == -1 and "NULL" in _err()                     # aliased V takes no V pool
 
 
+def test_window_array_and_block_image_argument_errors():
+    """The later entry points find their argument errors on the host, before anything is launched (fake pointers)."""
+    l = b.lib()
+    spec = b.make_spec(2, 4, 2, 128)
+    kp, vp = _pool(), _pool()
+    windows = (C.c_int32 * 2)(0, 16)
+
+    def attend(win=windows, spec=spec, lb=0, le=2):
+        return l.q4kv_batched_attention_windows(C.byref(spec), C.byref(kp), C.byref(vp), 0x4000, 0x5000, 0x6000, 4,
+                                                0x7000, 2, 1, 1024, 0.1, win, 0, lb, le, 0x8000, 1 << 30, None)
+
+    assert attend(win=None) == -1 and "window" in _err()
+    big = b.make_spec(200, 4, 2, 128)
+    assert attend(win=(C.c_int32 * 200)(), spec=big, le=200) == -1 and "128" in _err()      # one window per layer: 128 at most
+    assert attend(lb=1, le=1) == 0                                                         # nothing to do
+
+    def image(fn=l.q4kv_export_blocks, spec=spec, kp=kp, vp=vp, ids=0x4000, n=3, img=0x9000, nbytes=1 << 30):
+        return fn(C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp), ids, n, img, nbytes, None)
+
+    need = l.q4kv_block_image_bytes(C.byref(spec), 3)
+    rows = 2 * 256                                            # per (layer, block): K and V codes, scales, biases
+    assert need == 2 * 3 * 2 * (rows * 16 * 4 + 2 * rows * 2 * 2)
+    assert l.q4kv_block_image_bytes(C.byref(spec), -1) == 0
+    for fn in (l.q4kv_export_blocks, l.q4kv_import_blocks):
+        assert image(fn, nbytes=need - 1) == -4 and "image" in _err()
+        assert image(fn, ids=None) == -1 and image(fn, img=None) == -1
+        assert image(fn, img=0x9004) == -1                                                 # misaligned image
+        assert image(fn, n=-1) == -1
+        assert image(fn, vp=None) == -1                                                    # V pool missing
+        assert image(fn, vp=_pool(5)) == -1                                                # pools of different sizes
+        assert image(fn, n=0, ids=None, img=None) == 0                                     # nothing to do
+    mla = b.make_spec(2, 16, 1, 576, 512, True)
+    assert image(spec=mla, vp=vp) == -1                                                    # aliased V takes no V pool
+    assert l.q4kv_block_image_bytes(C.byref(mla), 1) == 2 * (256 * 72 * 4 + 2 * 256 * 9 * 2)
+    assert l.q4kv_read_probe(None, 1 << 20, 0x4000, None) == -1
+    assert l.q4kv_read_probe(0x4000, 1 << 20, None, None) == -1
+    assert l.q4kv_read_probe(0x4004, 1 << 20, 0x4000, None) == -1
+    assert l.q4kv_read_probe(None, 100, None, None) == 0                                   # below one step: nothing to read
+
+
 def test_workspace_and_split_queries():
     gemma = b.make_spec(48, 16, 8, 256)
     st = b.q4kv_default_split_tokens(gemma, 10, 1, 8192, 48)
