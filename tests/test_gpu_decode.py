@@ -229,3 +229,47 @@ def test_per_head_mla_full_size_sampled_units():
         want = oracle_unit(w, l, a, h, w.seq_lens[a])
         assert_close(got[l, a, :, h:h + 1], want, f"per-head MLA unit layer {l} agent {a} kv head {h}")
     assert float(np.abs(got.astype(np.float32)).max()) < 6.0
+
+
+def test_decode_call_replays_from_a_graph():
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a call can be recorded
+    into a graph; every replay, with eager work between the replays, gives the eager call's bits."""
+    w = synth.small(37, 3, 8, 2, 128, 128, False, (700, 90, 257))
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    q = w.q_all(DEV)
+    sl = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    msl = max(w.seq_lens)
+    ws = torch.empty(b.q4kv_attention_workspace_bytes(spec, w.num_agents, 1, msl, 256, w.num_layers), dtype=torch.uint8,
+                     device=DEV)
+    out = torch.empty((w.num_layers, w.num_agents, 1, w.num_q_heads, w.v_dim), dtype=torch.float16, device=DEV)
+
+    def call():
+        b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, sl, msl, w.sm_scale, [0, 64, 0], 256, 0, None, out, ws)
+
+    call()
+    torch.cuda.synchronize()
+    eager = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for i in range(4):
+        out.zero_()
+        ws.fill_(0xFF)                        # eager work between replays; the call must not depend on old workspace bits
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {i}"
+    # new lengths are picked up by a replay: the plan is rebuilt on the device from seq_len every time
+    sl.copy_(torch.tensor([300, 90, 1], dtype=torch.int32))
+    graph.replay()
+    torch.cuda.synchronize()
+    replayed = out.clone()
+    call()
+    torch.cuda.synchronize()
+    assert torch.equal(out, replayed)
