@@ -47,8 +47,6 @@ int check_pool(const q4kv_pool *p, const char *name)
     return Q4KV_OK;
 }
 
-int round_up(int x, int m) { return (x + m - 1) / m * m; }
-
 // Compute units of the current device (cached per device); the attention launch is two workgroups per unit.
 int compute_units()
 {

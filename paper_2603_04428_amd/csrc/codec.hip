@@ -107,40 +107,10 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
     return word;
 }
 
-// rows are addressed through `map`, which turns a source row index into a destination row index
-// (or -1 to skip the row).
-struct FlatRows {
-    static constexpr bool kIdentity = true; // destination group = source group: no row arithmetic at all
-    __device__ __forceinline__ int64_t operator()(int64_t row) const { return row; }
-};
-
-struct PagedRows { // source rows [layers_in_call][A][C][H] -> pool rows [layer][block][H][slot]
-    static constexpr bool kIdentity = false;
-    const int32_t *block_table;
-    const int32_t *seq_len_before;
-    int max_blocks, num_agents, chunk_len, heads, layer_begin, num_blocks;
-    __device__ __forceinline__ int64_t operator()(int64_t row) const
-    {
-        const int h = (int)(row % heads);
-        int64_t r = row / heads;
-        const int c = (int)(r % chunk_len);
-        r /= chunk_len;
-        const int a = (int)(r % num_agents);
-        const int li = (int)(r / num_agents);
-        const int t = seq_len_before[a] + c;
-        const int bi = t / kBlockTokens;
-        if (t < 0 || bi >= max_blocks) return -1;
-        const int blk = block_table[(int64_t)a * max_blocks + bi];
-        if (blk < 0 || blk >= num_blocks) return -1;
-        return (((int64_t)(layer_begin + li) * num_blocks + blk) * heads + h) * kBlockTokens + (t % kBlockTokens);
-    }
-};
-
-template <class RowMap>
+// Flat form: destination group = source group, no row arithmetic at all.
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__restrict__ x, int64_t total_groups,
-                                                            int groups_per_row, uint32_t *__restrict__ codes,
-                                                            uint16_t *__restrict__ scale,
-                                                            uint16_t *__restrict__ bias, RowMap map)
+                                                            uint32_t *__restrict__ codes, uint16_t *__restrict__ scale,
+                                                            uint16_t *__restrict__ bias)
 {
     const int sub = threadIdx.x & 7;
     const int64_t stride = (int64_t)gridDim.x * (kThreads / 8);
@@ -148,14 +118,47 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
         const uint4 raw = *reinterpret_cast<const uint4 *>(x + grp * kGroup + sub * 8);
         uint16_t sb, bb;
         const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
-        int64_t dgrp = grp;
-        if constexpr (!RowMap::kIdentity) {
-            const int64_t row = grp / groups_per_row;
-            const int g = (int)(grp % groups_per_row);
-            const int64_t drow = map(row);
-            if (drow < 0) continue;
-            dgrp = drow * groups_per_row + g;
+        codes[grp * 8 + sub] = word;
+        if (sub == 0) {
+            scale[grp] = sb;
+            bias[grp] = bb;
         }
+    }
+}
+
+// Paged form (Sec. 3.4 update_and_fetch, first half): source rows [layer in call][agent][chunk token][kv head],
+// destination the agent's blocks.  Layer and agent come from the launch grid, so that a lane's index arithmetic is
+// two 32-bit divisions (by the groups per row and by the heads) instead of a chain of 64-bit ones; a token outside
+// the table or a block id outside the pool is skipped.
+struct AppendParams {
+    const int32_t *block_table;
+    const int32_t *seq_len_before;
+    int max_blocks, chunk_len, heads, layer_begin, num_blocks, groups_per_row;
+};
+
+__global__ __launch_bounds__(kThreads) void append_kernel(const uint16_t *__restrict__ x, uint32_t *__restrict__ codes,
+                                                          uint16_t *__restrict__ scale, uint16_t *__restrict__ bias,
+                                                          AppendParams p)
+{
+    const int sub = threadIdx.x & 7;
+    const int a = blockIdx.y, li = blockIdx.z, agents = gridDim.y;
+    const uint32_t per_unit = (uint32_t)p.chunk_len * p.heads * p.groups_per_row; // groups of one (layer, agent)
+    const int64_t src0 = ((int64_t)li * agents + a) * per_unit;
+    const int n0 = p.seq_len_before[a];
+    const int32_t *table = p.block_table + (int64_t)a * p.max_blocks;
+    for (uint32_t gi = blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); gi < per_unit; gi += gridDim.x * (kThreads / 8)) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(x + (src0 + gi) * kGroup + sub * 8);
+        uint16_t sb, bb;
+        const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
+        const uint32_t row = gi / (uint32_t)p.groups_per_row, g = gi - row * p.groups_per_row;
+        const uint32_t c = row / (uint32_t)p.heads, h = row - c * p.heads;
+        const int t = n0 + (int)c;
+        const int bi = t / kBlockTokens;
+        if (t < 0 || bi >= p.max_blocks) continue;
+        const int blk = table[bi];
+        if (blk < 0 || blk >= p.num_blocks) continue;
+        const int64_t drow = (((int64_t)(p.layer_begin + li) * p.num_blocks + blk) * p.heads + h) * kBlockTokens + (t % kBlockTokens);
+        const int64_t dgrp = drow * p.groups_per_row + g;
         codes[dgrp * 8 + sub] = word;
         if (sub == 0) {
             scale[dgrp] = sb;
@@ -203,8 +206,8 @@ hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, uint32_t *c
     const int G = dim / kGroup;
     const int64_t groups = rows * G;
     if (groups == 0) return hipSuccess;
-    hipLaunchKernelGGL(quantize_kernel<FlatRows>, dim3(grid_for(groups, kThreads / 8)), dim3(kThreads), 0, stream, x,
-                       groups, G, codes, scale, bias, FlatRows{});
+    hipLaunchKernelGGL(quantize_kernel, dim3(grid_for(groups, kThreads / 8)), dim3(kThreads), 0, stream, x, groups, codes,
+                       scale, bias);
     return hipGetLastError();
 }
 
@@ -223,13 +226,18 @@ hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &pool, int dim, 
                          int chunk_len, int layer_begin, int layer_end, hipStream_t stream)
 {
     const int G = dim / kGroup;
-    const int64_t rows = (int64_t)(layer_end - layer_begin) * num_agents * chunk_len * spec.num_kv_heads;
-    const int64_t groups = rows * G;
-    if (groups == 0) return hipSuccess;
-    PagedRows map{block_table, seq_len_before, max_blocks, num_agents, chunk_len, spec.num_kv_heads, layer_begin,
-                  pool.num_blocks};
-    hipLaunchKernelGGL(quantize_kernel<PagedRows>, dim3(grid_for(groups, kThreads / 8)), dim3(kThreads), 0, stream,
-                       x_new, groups, G, pool.codes, pool.scale, pool.bias, map);
+    const int layers = layer_end - layer_begin;
+    const int64_t per_unit = (int64_t)chunk_len * spec.num_kv_heads * G;
+    if (layers <= 0 || num_agents <= 0 || per_unit == 0) return hipSuccess;
+    if (per_unit > 0x7fffffffLL || num_agents > 65535 || layers > 65535) return hipErrorInvalidValue;
+    AppendParams p{block_table, seq_len_before, max_blocks, chunk_len, spec.num_kv_heads, layer_begin, pool.num_blocks, G};
+    // workgroups per (layer, agent): enough for the chunk, and about 8 per compute unit over the whole launch
+    int64_t gx = (per_unit + kThreads / 8 - 1) / (kThreads / 8);
+    const int64_t cap = (256LL * Q4KV_CODEC_WG_PER_CU + (int64_t)layers * num_agents - 1) / ((int64_t)layers * num_agents);
+    if (gx > cap) gx = cap;
+    if (gx < 1) gx = 1;
+    hipLaunchKernelGGL(append_kernel, dim3((unsigned)gx, (unsigned)num_agents, (unsigned)layers), dim3(kThreads), 0, stream,
+                       x_new, pool.codes, pool.scale, pool.bias, p);
     return hipGetLastError();
 }
 
