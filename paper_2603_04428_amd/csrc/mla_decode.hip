@@ -246,14 +246,23 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
             __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
             const int tok = cur.t0 + lane;
             const bool tok_valid = cur.reachable && tok >= cur.first && tok < cur.n;
+            // wave-uniform: some token of the tile lies outside the agent's visible range
+            const bool edge = !(cur.reachable && cur.t0 >= cur.first && cur.t0 + kWave <= cur.n);
             {
                 // rows outside the agent's range may hold anything: their scale and bias become zero so that no NaN
                 // or infinity reaches a matrix operand (codes are nibbles and always finite)
                 uint32_t s[GK], b[BTP];
 #pragma unroll
                 for (int g = 0; g < GK; ++g) {
-                    s[g] = tok_valid ? sraw[g] : 0u;
-                    b[g] = tok_valid ? braw[g] : 0u;
+                    s[g] = sraw[g];
+                    b[g] = braw[g];
+                }
+                if (edge) { // interior tiles (nearly all) skip the selects
+#pragma unroll
+                    for (int g = 0; g < GK; ++g) {
+                        s[g] = tok_valid ? s[g] : 0u;
+                        b[g] = tok_valid ? b[g] : 0u;
+                    }
                 }
 #pragma unroll
                 for (int g = GK; g < BTP; ++g) b[g] = 0u;
@@ -362,7 +371,6 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
             // kSlack (in log2 units), so p <= 2^kSlack and p * s stays far inside binary16 for any binary16 scale,
             // and the accumulators are rescaled a handful of times per unit instead of in every other tile.
             constexpr float kSlack = 3.0f;
-            const bool edge = !(cur.reachable && cur.t0 >= cur.first && cur.t0 + kWave <= cur.n); // wave-uniform
             if (edge) {
 #pragma unroll
                 for (int h2 = 0; h2 < 2; ++h2)
