@@ -114,7 +114,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
 {
     const int sub = threadIdx.x & 7;
     const int64_t stride = (int64_t)gridDim.x * (kThreads / 8);
+    const int generation = blockIdx.x / max(1u, gridDim.x / Q4KV_CODEC_WG_PER_CU);
     for (int64_t grp = (int64_t)blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); grp < total_groups; grp += stride) {
+        rotate_wave_priority(generation);
         const uint4 raw = *reinterpret_cast<const uint4 *>(x + grp * kGroup + sub * 8);
         uint16_t sb, bb;
         const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
@@ -146,7 +148,11 @@ __global__ __launch_bounds__(kThreads) void append_kernel(const uint16_t *__rest
     const int64_t src0 = ((int64_t)li * agents + a) * per_unit;
     const int n0 = p.seq_len_before[a];
     const int32_t *table = p.block_table + (int64_t)a * p.max_blocks;
+    // generations of the launch: workgroups in launch order (x fastest), about 256 of them per generation
+    const uint32_t linear = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    const int generation = linear / max(1u, gridDim.x * gridDim.y * gridDim.z / Q4KV_CODEC_WG_PER_CU);
     for (uint32_t gi = blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); gi < per_unit; gi += gridDim.x * (kThreads / 8)) {
+        rotate_wave_priority(generation);
         const uint4 raw = *reinterpret_cast<const uint4 *>(x + (src0 + gi) * kGroup + sub * 8);
         uint16_t sb, bb;
         const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
@@ -174,7 +180,9 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
                                                               uint16_t *__restrict__ x)
 {
     const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int generation = blockIdx.x / max(1u, gridDim.x / Q4KV_CODEC_WG_PER_CU);
     for (int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x; w < total_words; w += stride) {
+        rotate_wave_priority(generation);
         const uint32_t word = codes[w];
         const float s = half_bits_to_float(scale[w >> 3]);
         const float b = half_bits_to_float(bias[w >> 3]);

@@ -36,7 +36,9 @@ __global__ __launch_bounds__(kCopyThreads) void image_copy_kernel(ImageParams p)
 {
     const long long chunks_per_record = (p.record_bytes + kChunkBytes - 1) / kChunkBytes;
     const long long items = (long long)p.layers * p.num_blocks * chunks_per_record;
+    const int generation = blockIdx.x / max(1u, gridDim.x / 8); // the device launch stacks eight workgroups per compute unit
     for (long long item = blockIdx.x; item < items; item += gridDim.x) {
+        rotate_wave_priority(generation);
         const long long rec = item / chunks_per_record;
         const long long off = (item % chunks_per_record) * kChunkBytes + threadIdx.x * 16; // inside the record
         const int l = (int)(rec / p.num_blocks), i = (int)(rec % p.num_blocks);

@@ -35,7 +35,9 @@ __global__ __launch_bounds__(kProbeThreads, 2) void read_probe_kernel(const uint
     };
     load_a(t0);
     load_b(t0);
+    const int generation = blockIdx.x / max(1u, gridDim.x / 2); // two workgroups per compute unit
     for (long long t = t0; t < t1; ++t) {
+        rotate_wave_priority(generation);
         const long long tn = t + 1 < t1 ? t + 1 : t; // the last step re-reads itself
 #pragma unroll
         for (int i = 0; i < 8; ++i) x ^= a[i].x ^ a[i].y ^ a[i].z ^ a[i].w;
