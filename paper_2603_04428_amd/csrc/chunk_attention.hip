@@ -344,24 +344,31 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
 
         // ---- online softmax per query row (lane column), then P^T in binary16 as the next B operand
         const bool masked = !(ok_this && t0 >= all_first && t0 + kTile <= all_vis); // wave-uniform
+        const bool general = masked || !(p.score_scale > 0.0f); // the path that assumes nothing
         half8_t pt[QT][kTile / 32]; // [q tile][32-token block]: tokens 4*kb..+3 of both 16-token tiles of the block
         bool any_moved = false;
         float alpha[QT];
 #pragma unroll
         for (int qi = 0; qi < QT; ++qi) {
             float mx = kNegBig;
+            if (general) {
 #pragma unroll
-            for (int tt = 0; tt < kTile / 16; ++tt)
+                for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float z = st[qi][tt][e] * p.score_scale;
-                    if (masked) {
+                    for (int e = 0; e < 4; ++e) {
+                        float z = st[qi][tt][e] * p.score_scale;
                         const int t = t0 + tt * 16 + 4 * kb + e;
                         if (!(ok_this && t < row_vis[qi] && t >= row_first[qi])) z = kNegBig;
+                        st[qi][tt][e] = z;
+                        mx = fmaxf(mx, z);
                     }
-                    st[qi][tt][e] = z;
-                    mx = fmaxf(mx, z);
-                }
+            } else { // interior tile, positive scale: the maximum can be taken before the scale is applied
+#pragma unroll
+                for (int tt = 0; tt < kTile / 16; ++tt)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) mx = fmaxf(mx, st[qi][tt][e]);
+                mx *= p.score_scale;
+            }
             // the row's tokens live in the 4 lanes qn, qn+16, qn+32, qn+48
             mx = xor32_max(xor16_max(mx));
             const bool moved = mx > m_run[qi] + kSlack;
@@ -370,15 +377,26 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
             any_moved |= moved;
             m_run[qi] = m_new;
             float sum = 0.0f;
+            if (general) {
 #pragma unroll
-            for (int tt = 0; tt < kTile / 16; ++tt)
+                for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float pr = __builtin_amdgcn_exp2f(st[qi][tt][e] - m_new);
-                    if (masked) pr = st[qi][tt][e] > 0.5f * kNegBig ? pr : 0.0f; // also a row with nothing visible yet
-                    st[qi][tt][e] = pr;
-                    sum += pr;
-                }
+                    for (int e = 0; e < 4; ++e) {
+                        float pr = __builtin_amdgcn_exp2f(st[qi][tt][e] - m_new);
+                        pr = st[qi][tt][e] > 0.5f * kNegBig ? pr : 0.0f; // also a row with nothing visible yet
+                        st[qi][tt][e] = pr;
+                        sum += pr;
+                    }
+            } else {
+#pragma unroll
+                for (int tt = 0; tt < kTile / 16; ++tt)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float pr = __builtin_amdgcn_exp2f(fmaf(st[qi][tt][e], p.score_scale, -m_new));
+                        st[qi][tt][e] = pr;
+                        sum += pr;
+                    }
+            }
             l_run[qi] = fmaf(l_run[qi], alpha[qi], sum); // this lane's tokens only; lanes are added up at the end
 #pragma unroll
             for (int tb = 0; tb < kTile / 32; ++tb)
