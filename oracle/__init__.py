@@ -21,7 +21,7 @@ class Spec(C.Structure):
     """Mirror of oracle_spec (the ModelCacheSpec of Sec. 3.1/3.6)."""
     _fields_ = [("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
                 ("k_dim", C.c_int32), ("v_dim", C.c_int32), ("v_aliases_k", C.c_int32),
-                ("block_tokens", C.c_int32), ("group_size", C.c_int32)]
+                ("block_tokens", C.c_int32), ("group_size", C.c_int32), ("param_format", C.c_int32)]
 
 
 class _Pool(C.Structure):
@@ -42,8 +42,14 @@ def lib():
         for f in (_lib.oracle_fp16_layer_bytes, _lib.oracle_q4_layer_bytes):
             f.restype = C.c_int64
             f.argtypes = [C.c_int64] * 4
-        _lib.oracle_q4_quantize.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
-        _lib.oracle_q4_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
+        _lib.oracle_bf2f.restype = C.c_float
+        _lib.oracle_bf2f.argtypes = [C.c_uint16]
+        _lib.oracle_f2bf.restype = C.c_uint16
+        _lib.oracle_f2bf.argtypes = [C.c_float]
+        _lib.oracle_q4_quantize_fmt.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                                C.c_void_p]
+        _lib.oracle_q4_dequantize_fmt.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int,
+                                                  C.c_void_p]
         _lib.oracle_append.argtypes = [C.POINTER(Spec), C.POINTER(_Pool), C.POINTER(_Pool), C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         _lib.oracle_attention.argtypes = [C.POINTER(Spec), C.POINTER(_Pool), C.POINTER(_Pool), C.c_void_p,
@@ -70,9 +76,13 @@ def _bits(x):
     return x
 
 
-def make_spec(num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, block_tokens=256):
+F16_PARAMS, BF16_PARAMS = 0, 1   # type of the stored scale and bias (Sec. 3.1, appendix "safetensors Q4 Format")
+
+
+def make_spec(num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, block_tokens=256,
+              param_format=F16_PARAMS):
     return Spec(num_layers, num_q_heads, num_kv_heads, k_dim, k_dim if v_dim is None else v_dim,
-                1 if v_aliases_k else 0, block_tokens, GROUP)
+                1 if v_aliases_k else 0, block_tokens, GROUP, param_format)
 
 
 class Pool:
@@ -106,6 +116,14 @@ def f2h(x):
     return int(lib().oracle_f2h(float(np.float32(x))))
 
 
+def bf2f(bits):
+    return float(lib().oracle_bf2f(int(bits)))
+
+
+def f2bf(x):
+    return int(lib().oracle_f2bf(float(np.float32(x))))
+
+
 def fp16_layer_bytes(kv_heads, k_dim, v_dim, tokens):
     return int(lib().oracle_fp16_layer_bytes(kv_heads, k_dim, v_dim, tokens))
 
@@ -114,8 +132,9 @@ def q4_layer_bytes(kv_heads, k_dim, v_dim, tokens):
     return int(lib().oracle_q4_layer_bytes(kv_heads, k_dim, v_dim, tokens))
 
 
-def quantize(x):
-    """x: [..., dim] float16/uint16 -> (codes uint32 [..., dim/8], scale uint16 [..., dim/64], bias same)."""
+def quantize(x, param_format=F16_PARAMS):
+    """x: [..., dim] float16/uint16 -> (codes uint32 [..., dim/8], scale uint16 [..., dim/64], bias same).
+    scale / bias are bit patterns of binary16 or, with param_format=BF16_PARAMS, of bfloat16."""
     xb = _bits(x)
     dim = xb.shape[-1]
     rows = xb.size // dim if dim else 0
@@ -123,22 +142,22 @@ def quantize(x):
     codes = np.empty(lead + (dim // 8,), np.uint32)
     scale = np.empty(lead + (dim // GROUP,), np.uint16)
     bias = np.empty(lead + (dim // GROUP,), np.uint16)
-    rc = lib().oracle_q4_quantize(_ptr(xb), rows, dim, _ptr(codes), _ptr(scale), _ptr(bias))
+    rc = lib().oracle_q4_quantize_fmt(_ptr(xb), rows, dim, int(param_format), _ptr(codes), _ptr(scale), _ptr(bias))
     if rc:
-        raise ValueError(f"oracle_q4_quantize rc={rc}")
+        raise ValueError(f"oracle_q4_quantize_fmt rc={rc}")
     return codes, scale, bias
 
 
-def dequantize(codes, scale, bias):
+def dequantize(codes, scale, bias, param_format=F16_PARAMS):
     """Inverse layout of quantize(); returns float16 [..., dim]."""
     codes = np.ascontiguousarray(codes, np.uint32)
     scale, bias = _bits(scale), _bits(bias)
     dim = codes.shape[-1] * 8
     rows = codes.size // codes.shape[-1] if codes.shape[-1] else 0
     out = np.empty(codes.shape[:-1] + (dim,), np.uint16)
-    rc = lib().oracle_q4_dequantize(_ptr(codes), _ptr(scale), _ptr(bias), rows, dim, _ptr(out))
+    rc = lib().oracle_q4_dequantize_fmt(_ptr(codes), _ptr(scale), _ptr(bias), rows, dim, int(param_format), _ptr(out))
     if rc:
-        raise ValueError(f"oracle_q4_dequantize rc={rc}")
+        raise ValueError(f"oracle_q4_dequantize_fmt rc={rc}")
     return out.view(np.float16)
 
 

@@ -26,6 +26,13 @@
  *   binary16 (round to nearest even); code = clamp(rint((x - min)/scale_stored),
  *   0, 15) with a true binary32 division and ties-to-even; element d of a row
  *   sits in word d/8, bits 4*(d%8) .. 4*(d%8)+3.
+ * Sec. 3.1, Sec. 3.2 and the appendix "safetensors Q4 Format" name bfloat16 as the
+ * type of scale and bias for one model family and binary16 for another.  The
+ * bfloat16 form (param_format 1) is read as the same formula with both parameters
+ * rounded to bfloat16 (nearest even) and the codes taken against the STORED
+ * parameters: code = clamp(rint((x - bias_stored)/scale_stored), 0, 15).  The
+ * stored bias is then no longer exactly the minimum, so x - bias_stored may be
+ * slightly negative (code 0) and the top of the range may clamp at 15.
  *
  * Attention reaches exactly (up to rounding order) softmax(sm * q K^T) V on the
  * dequantized values, so it is written as that definition in binary64.
@@ -93,6 +100,50 @@ uint16_t oracle_d2h(double d)
 
 uint16_t oracle_f2h(float f) { return oracle_d2h((double)f); }
 
+/* ---------------------------------------------------------------- bfloat16 */
+
+/* bfloat16 = sign, 8 exponent bits (bias 127), 7 fraction bits: the value of the bits. */
+float oracle_bf2f(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 7) & 0xff;
+    int m = h & 0x7f;
+    float v;
+    if (e == 0)
+        v = ldexpf((float)m, -133);                /* zero / subnormal: m * 2^-7 * 2^-126 */
+    else if (e == 255)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexpf((float)(m + 128), e - 134);     /* (1 + m/128) * 2^(e-127) */
+    return sign ? -v : v;
+}
+
+/* binary32 value -> bfloat16 bits, round to nearest, ties to even (arithmetic on the
+ * value, not on the bit pattern). */
+uint16_t oracle_f2bf(float f)
+{
+    uint16_t sign = signbit(f) ? 0x8000u : 0;
+    double a = fabs((double)f);
+    if (isnan(f)) return (uint16_t)(sign | 0x7fc0u);
+    if (isinf(f)) return (uint16_t)(sign | 0x7f80u);
+    if (a == 0.0) return sign;
+    int ex;
+    (void)frexp(a, &ex);
+    int e = ex - 1;                        /* a in [2^e, 2^(e+1)) */
+    if (e < -126) e = -126;                /* subnormals share the spacing 2^-133 */
+    double scaled = ldexp(a, 7 - e);       /* exact; spacing of bfloat16 around a is 2^(e-7) */
+    double r = nearbyint(scaled);          /* ties to even */
+    if (r >= 256.0) { e += 1; r = 128.0; }
+    int biased, mant;
+    if (r < 128.0) { biased = 0; mant = (int)r; }
+    else { biased = e + 127; mant = (int)r - 128; }
+    if (biased >= 255) return (uint16_t)(sign | 0x7f80u);
+    return (uint16_t)(sign | (biased << 7) | mant);
+}
+
+/* stored parameter bits -> value, by format (0: binary16, 1: bfloat16) */
+static float param_value(uint16_t bits, int fmt) { return fmt ? oracle_bf2f(bits) : oracle_h2f(bits); }
+
 /* ---------------------------------------------------------------- byte counts */
 
 /* Sec. 3.2: FP16 K+V bytes of one layer = 4*h*d*n when K and V are d wide; written
@@ -112,8 +163,10 @@ int64_t oracle_q4_layer_bytes(int64_t kv_heads, int64_t k_dim, int64_t v_dim, in
 
 /* ---------------------------------------------------------------- quantize */
 
-/* One row of `dim` binary16 values -> dim/8 words, dim/64 scales, dim/64 biases. */
-static void quantize_row(const uint16_t *x, int dim, uint32_t *codes, uint16_t *scale, uint16_t *bias)
+/* One row of `dim` binary16 values -> dim/8 words, dim/64 scales, dim/64 biases.
+ * fmt 0: parameters stored as binary16 (the bias is then exactly the minimum);
+ * fmt 1: stored as bfloat16, codes taken against the stored values. */
+static void quantize_row(const uint16_t *x, int dim, int fmt, uint32_t *codes, uint16_t *scale, uint16_t *bias)
 {
     for (int g = 0; g < dim / ORACLE_GROUP; ++g) {
         const uint16_t *xg = x + g * ORACLE_GROUP;
@@ -126,16 +179,17 @@ static void quantize_row(const uint16_t *x, int dim, uint32_t *codes, uint16_t *
         }
         volatile float range = mx - mn;                /* binary32 */
         volatile float scale32 = range / 15.0f;        /* binary32 division */
-        uint16_t sh = oracle_f2h(scale32);
-        float s = oracle_h2f(sh);
+        uint16_t sh = fmt ? oracle_f2bf(scale32) : oracle_f2h(scale32);
+        float s = param_value(sh, fmt);
         scale[g] = sh;
-        bias[g] = mn_bits;
+        bias[g] = fmt ? oracle_f2bf(mn) : mn_bits;
+        float b = fmt ? oracle_bf2f(bias[g]) : mn;      /* what the decoder will add back */
         for (int w = 0; w < ORACLE_GROUP / 8; ++w) {
             uint32_t word = 0;
             for (int j = 0; j < 8; ++j) {
                 uint32_t c = 0;
                 if (s != 0.0f) {
-                    volatile float diff = oracle_h2f(xg[8 * w + j]) - mn;
+                    volatile float diff = oracle_h2f(xg[8 * w + j]) - b;
                     volatile float ratio = diff / s;   /* binary32 division */
                     float r = nearbyintf(ratio);       /* ties to even */
                     if (r < 0.0f) r = 0.0f;
@@ -151,15 +205,21 @@ static void quantize_row(const uint16_t *x, int dim, uint32_t *codes, uint16_t *
 
 /* x: [rows][dim] binary16 bits.  codes: [rows][dim/8], scale/bias: [rows][dim/64].
  * Returns 0, or -1 on a bad argument. */
-int oracle_q4_quantize(const uint16_t *x, int64_t rows, int dim, uint32_t *codes, uint16_t *scale,
-                       uint16_t *bias)
+int oracle_q4_quantize_fmt(const uint16_t *x, int64_t rows, int dim, int fmt, uint32_t *codes, uint16_t *scale,
+                           uint16_t *bias)
 {
-    if (dim <= 0 || dim % ORACLE_GROUP || rows < 0) return -1;
+    if (dim <= 0 || dim % ORACLE_GROUP || rows < 0 || (fmt != 0 && fmt != 1)) return -1;
     int G = dim / ORACLE_GROUP;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r)
-        quantize_row(x + r * dim, dim, codes + r * (dim / 8), scale + r * G, bias + r * G);
+        quantize_row(x + r * dim, dim, fmt, codes + r * (dim / 8), scale + r * G, bias + r * G);
     return 0;
+}
+
+int oracle_q4_quantize(const uint16_t *x, int64_t rows, int dim, uint32_t *codes, uint16_t *scale,
+                       uint16_t *bias)
+{
+    return oracle_q4_quantize_fmt(x, rows, dim, 0, codes, scale, bias);
 }
 
 /* ---------------------------------------------------------------- dequantize */
@@ -167,21 +227,27 @@ int oracle_q4_quantize(const uint16_t *x, int64_t rows, int dim, uint32_t *codes
 static inline uint32_t code_at(const uint32_t *codes, int d) { return (codes[d >> 3] >> (4 * (d & 7))) & 0xfu; }
 
 /* x_hat = code * scale + bias in binary32 (the product is exact), rounded to binary16. */
-int oracle_q4_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
-                         int dim, uint16_t *x)
+int oracle_q4_dequantize_fmt(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
+                             int dim, int fmt, uint16_t *x)
 {
-    if (dim <= 0 || dim % ORACLE_GROUP || rows < 0) return -1;
+    if (dim <= 0 || dim % ORACLE_GROUP || rows < 0 || (fmt != 0 && fmt != 1)) return -1;
     int G = dim / ORACLE_GROUP;
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < rows; ++r)
         for (int d = 0; d < dim; ++d) {
-            float s = oracle_h2f(scale[r * G + d / ORACLE_GROUP]);
-            float b = oracle_h2f(bias[r * G + d / ORACLE_GROUP]);
+            float s = param_value(scale[r * G + d / ORACLE_GROUP], fmt);
+            float b = param_value(bias[r * G + d / ORACLE_GROUP], fmt);
             volatile float prod = (float)code_at(codes + r * (dim / 8), d) * s;
             volatile float v = prod + b;
             x[r * dim + d] = oracle_f2h(v);
         }
     return 0;
+}
+
+int oracle_q4_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
+                         int dim, uint16_t *x)
+{
+    return oracle_q4_dequantize_fmt(codes, scale, bias, rows, dim, 0, x);
 }
 
 /* ---------------------------------------------------------------- paged cache */
@@ -192,6 +258,7 @@ typedef struct {
     int32_t v_aliases_k;   /* 1: V row = first v_dim elements of the K row (shared latent) */
     int32_t block_tokens;  /* 256 */
     int32_t group_size;    /* 64 */
+    int32_t param_format;  /* type of the stored scale and bias: 0 binary16, 1 bfloat16 */
 } oracle_spec;
 
 typedef struct {           /* [num_layers][num_blocks][kv_heads][block_tokens][dim/8 | dim/64] */
@@ -208,11 +275,11 @@ static int64_t pool_row(const oracle_spec *sp, const oracle_pool *p, int layer, 
 }
 
 /* unrounded dequantized element d of a pool row, exact in binary64 */
-static double pool_value(const oracle_pool *p, int64_t row, int dim, int d)
+static double pool_value(const oracle_pool *p, int fmt, int64_t row, int dim, int d)
 {
     int G = dim / ORACLE_GROUP;
-    double s = (double)oracle_h2f(p->scale[row * G + d / ORACLE_GROUP]);
-    double b = (double)oracle_h2f(p->bias[row * G + d / ORACLE_GROUP]);
+    double s = (double)param_value(p->scale[row * G + d / ORACLE_GROUP], fmt);
+    double b = (double)param_value(p->bias[row * G + d / ORACLE_GROUP], fmt);
     return (double)code_at(p->codes + row * (dim / 8), d) * s + b;
 }
 
@@ -221,7 +288,8 @@ static int spec_ok(const oracle_spec *sp)
     return sp && sp->num_layers > 0 && sp->num_kv_heads > 0 && sp->num_q_heads > 0 &&
            sp->num_q_heads % sp->num_kv_heads == 0 && sp->group_size == ORACLE_GROUP && sp->k_dim > 0 &&
            sp->v_dim > 0 && sp->k_dim % ORACLE_GROUP == 0 && sp->v_dim % ORACLE_GROUP == 0 &&
-           sp->block_tokens > 0 && (!sp->v_aliases_k || sp->v_dim <= sp->k_dim);
+           sp->block_tokens > 0 && (!sp->v_aliases_k || sp->v_dim <= sp->k_dim) &&
+           (sp->param_format == 0 || sp->param_format == 1);
 }
 
 /* Sec. 3.4 update_and_fetch, first half: quantize each new token's K and V rows and
@@ -244,12 +312,12 @@ int oracle_append(const oracle_spec *sp, oracle_pool *k, oracle_pool *v, const u
                 for (int h = 0; h < H; ++h) {
                     int64_t src = ((((int64_t)(l - layer_begin) * num_agents + a) * chunk_len + c) * H + h);
                     int64_t row = pool_row(sp, k, l, blk, h, t % B);
-                    quantize_row(k_new + src * sp->k_dim, sp->k_dim, k->codes + row * (sp->k_dim / 8),
+                    quantize_row(k_new + src * sp->k_dim, sp->k_dim, sp->param_format, k->codes + row * (sp->k_dim / 8),
                                  k->scale + row * (sp->k_dim / ORACLE_GROUP),
                                  k->bias + row * (sp->k_dim / ORACLE_GROUP));
                     if (!sp->v_aliases_k) {
                         row = pool_row(sp, v, l, blk, h, t % B);
-                        quantize_row(v_new + src * sp->v_dim, sp->v_dim, v->codes + row * (sp->v_dim / 8),
+                        quantize_row(v_new + src * sp->v_dim, sp->v_dim, sp->param_format, v->codes + row * (sp->v_dim / 8),
                                      v->scale + row * (sp->v_dim / ORACLE_GROUP),
                                      v->bias + row * (sp->v_dim / ORACLE_GROUP));
                     }
@@ -279,7 +347,7 @@ static int attention_unit(const oracle_spec *sp, const oracle_pool *k, const ora
         if (blk < 0 || blk >= k->num_blocks) return -3;
         int64_t row = pool_row(sp, k, layer, blk, kv_head, t % B);
         double acc = 0.0;
-        for (int d = 0; d < sp->k_dim; ++d) acc += (double)oracle_h2f(q_row[d]) * pool_value(k, row, sp->k_dim, d);
+        for (int d = 0; d < sp->k_dim; ++d) acc += (double)oracle_h2f(q_row[d]) * pool_value(k, sp->param_format, row, sp->k_dim, d);
         z[t] = sm_scale * acc;
         if (z[t] > zmax) zmax = z[t];
     }
@@ -292,7 +360,7 @@ static int attention_unit(const oracle_spec *sp, const oracle_pool *k, const ora
         z[t] /= denom;                                  /* softmax weight p_t, left in z for the caller */
         int blk = table_row[t / B];
         int64_t row = pool_row(sp, vp, layer, blk, kv_head, t % B);
-        for (int e = 0; e < sp->v_dim; ++e) out_d[e] += z[t] * pool_value(vp, row, v_row_dim, e);
+        for (int e = 0; e < sp->v_dim; ++e) out_d[e] += z[t] * pool_value(vp, sp->param_format, row, v_row_dim, e);
     }
     return 0;
 }

@@ -239,9 +239,10 @@ def test_synthetic_workload_rows_roundtrip():
 
 # ----------------------------------------------------------------------------- helpers for attention pins
 
-def build_cache(w, poison=None, extra_blocks=0, table=None):
+def build_cache(w, poison=None, extra_blocks=0, table=None, param_format=oracle.F16_PARAMS):
     """Fill host pools for workload w through oracle.append (tokens 0..final_len-1 of every agent)."""
-    spec = oracle.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k)
+    spec = oracle.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k,
+                            param_format=param_format)
     if table is None:
         table, nblocks = w.block_table()
     else:
@@ -258,15 +259,24 @@ def build_cache(w, poison=None, extra_blocks=0, table=None):
     return spec, kpool, vpool, table
 
 
+def param_values(bits, param_format=oracle.F16_PARAMS):
+    """Stored scale / bias bit patterns -> float64, decoded by numpy (binary16) or torch (bfloat16)."""
+    bits = np.ascontiguousarray(bits, np.uint16)
+    if param_format == oracle.BF16_PARAMS:
+        return torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).double().numpy()
+    return bits.view(F16).astype(np.float64)
+
+
 def dense_rows(w, spec, pool, table, layer, agent, n, dim):
     """Explicitly dequantized [n][kv_heads][dim] float64 of one agent/layer, decoded here with numpy."""
     out = np.zeros((n, spec.num_kv_heads, dim))
+    fmt = spec.param_format
     for t in range(n):
         blk = table[agent, t // w.block_tokens]
         slot = t % w.block_tokens
         c = unpack_codes(pool.codes[layer, blk, :, slot]).astype(np.float64)
-        s = np.repeat(pool.scale[layer, blk, :, slot].view(F16).astype(np.float64), 64, axis=-1)
-        b = np.repeat(pool.bias[layer, blk, :, slot].view(F16).astype(np.float64), 64, axis=-1)
+        s = np.repeat(param_values(pool.scale[layer, blk, :, slot], fmt), 64, axis=-1)
+        b = np.repeat(param_values(pool.bias[layer, blk, :, slot], fmt), 64, axis=-1)
         out[t] = c * s + b
     return out
 
