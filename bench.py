@@ -110,7 +110,7 @@ def bench_append(args, torch, b, synth, build_device_cache):
         "metric": "Q4 KV chunked-append attention TFLOP/s (% of dense fp16 MFMA peak) + agent-tokens/s",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "q4 codes + f16 scale/bias dequantized to f16, f32 accumulate, f16 out", "data": "synthetic",
+        "dtype": "f16 matrix operands (K codes exact, scales applied in f32; V dequantized to f16), f32 accumulate, f16 out", "data": "synthetic",
         "config": {"workload": w.name if args.layer_windows == "global" else w.name + " + 5:1 window-1024 layers",
                    "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
                    "kv_heads": w.num_kv_heads, "head_dim": w.k_dim, "seq_lens_before": w.seq_lens, "chunk": C},
@@ -119,7 +119,7 @@ def bench_append(args, torch, b, synth, build_device_cache):
         "append_ms": app_ms, "append_GBps": app_bytes / (app_ms * 1e-3) / 1e9,
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
-                     "kernel": "chunk_attention_kernel<256,2>"},
+                     "kernel": "chunk_attention_kernel<256,256,2,1,false>"},
     }
     print(json.dumps(res))
 

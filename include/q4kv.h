@@ -24,6 +24,13 @@
  *     code  = clamp(rint((x - min) / scale_stored), 0, 15)   binary32 division, ties to even;
  *             all codes 0 when scale_stored == 0
  * Element d of a row lives in 32-bit word d/8, bits 4*(d%8) .. 4*(d%8)+3.
+ * The paper stores scale and bias as bfloat16 for one model family and as binary16 for another (Sec. 3.1, Sec. 3.2,
+ * appendix "safetensors Q4 Format").  Q4KV_PARAMS_BF16 selects the bfloat16 form: the same formula with both
+ * parameters rounded to bfloat16 (nearest even) and the codes taken against the STORED parameters,
+ *     code = clamp(rint((x - bias_stored) / scale_stored), 0, 15),
+ * so a reader needs nothing but the stored values.  The stored bias is then in general not the minimum itself:
+ * |x - x_hat| <= scale_stored/2 + |bias_stored - min| + 15 |scale_stored - scale|.  Parameters must stay inside the
+ * binary16 range (they do for binary16 data).
  * Bytes per row: dim/2 (codes) + 2*dim/64 (scale) + 2*dim/64 (bias), i.e. K+V of a
  * layer take h*d*n*(1 + 8/64) bytes, the paper's count.
  */
@@ -46,6 +53,12 @@ typedef enum {
     Q4KV_EHIP = -5        /* the HIP runtime refused a launch */
 } q4kv_status;
 
+/* Type of the stored scale and bias values (both 16 bits wide, so layouts and byte counts do not change). */
+typedef enum {
+    Q4KV_PARAMS_F16 = 0,  /* IEEE binary16 */
+    Q4KV_PARAMS_BF16 = 1  /* bfloat16 */
+} q4kv_param_format;
+
 /* Shape descriptor of one model's cache: the paper's ModelCacheSpec (Sec. 3.1, and
  * Sec. 3.6 for v_dim != k_dim).  The library reads nothing model-specific beyond it. */
 typedef struct {
@@ -58,11 +71,12 @@ typedef struct {
                                latent per token); the V pool argument must then be NULL */
     int32_t block_tokens;   /* 256, the paper's block size (Sec. 3.1) */
     int32_t group_size;     /* 64 */
+    int32_t param_format;   /* q4kv_param_format of every pool used with this spec */
 } q4kv_spec;
 
 /* One paged Q4 pool (K or V) for all layers, device memory, row-major:
  *   codes [num_layers][num_blocks][num_kv_heads][block_tokens][dim/8]   uint32
- *   scale [num_layers][num_blocks][num_kv_heads][block_tokens][dim/64]  binary16 bits
+ *   scale [num_layers][num_blocks][num_kv_heads][block_tokens][dim/64]  binary16 (or bfloat16) bits
  *   bias  same shape as scale
  * All three base pointers must be 16-byte aligned.  A block id indexes the second axis;
  * an agent owns the blocks its block-table row lists (Sec. 3.1, per-agent isolation). */
@@ -84,6 +98,13 @@ int q4kv_quantize(const uint16_t *x, int64_t rows, int32_t dim, uint32_t *codes,
  * binary32, rounded to binary16.  Arguments mirror q4kv_quantize; x is the device output. */
 int q4kv_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows, int32_t dim,
                     uint16_t *x, void *hip_stream);
+
+/* The two calls above with the type of scale and bias chosen by `param_format` (a q4kv_param_format; anything
+ * else -> Q4KV_EINVAL).  Q4KV_PARAMS_F16 is exactly q4kv_quantize / q4kv_dequantize. */
+int q4kv_quantize_fmt(const uint16_t *x, int64_t rows, int32_t dim, int32_t param_format, uint32_t *codes,
+                      uint16_t *scale, uint16_t *bias, void *hip_stream);
+int q4kv_dequantize_fmt(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows, int32_t dim,
+                        int32_t param_format, uint16_t *x, void *hip_stream);
 
 /* Sec. 3.4, first half of update_and_fetch: quantize new K/V rows and store them behind
  * each agent's cached tokens.

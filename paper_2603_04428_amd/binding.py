@@ -12,7 +12,7 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libq4kv.so")
 
-EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_append", "q4kv_batched_attention",
+EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_quantize_fmt", "q4kv_dequantize_fmt", "q4kv_append", "q4kv_batched_attention",
            "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_block_image_bytes", "q4kv_export_blocks", "q4kv_import_blocks", "q4kv_read_probe",
            "q4kv_last_error",
            "q4kv_version"]
@@ -28,7 +28,10 @@ class Spec(C.Structure):
     """q4kv_spec"""
     _fields_ = [("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
                 ("k_dim", C.c_int32), ("v_dim", C.c_int32), ("v_aliases_k", C.c_int32),
-                ("block_tokens", C.c_int32), ("group_size", C.c_int32)]
+                ("block_tokens", C.c_int32), ("group_size", C.c_int32), ("param_format", C.c_int32)]
+
+
+PARAMS_F16, PARAMS_BF16 = 0, 1   # q4kv_param_format: type of the stored scale and bias
 
 
 class _CPool(C.Structure):
@@ -50,6 +53,8 @@ def lib():
         vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
         l.q4kv_quantize.argtypes = [vp, i64, i32, vp, vp, vp, vp]
         l.q4kv_dequantize.argtypes = [vp, vp, vp, i64, i32, vp, vp]
+        l.q4kv_quantize_fmt.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
+        l.q4kv_dequantize_fmt.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp]
         l.q4kv_append.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32, vp, i32, i32,
                                   i32, i32, vp]
         l.q4kv_batched_attention.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32, vp,
@@ -91,9 +96,10 @@ def _dev(t, dtype, name):
     return C.c_void_p(t.data_ptr())
 
 
-def make_spec(num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, block_tokens=256):
+def make_spec(num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, block_tokens=256,
+              param_format=PARAMS_F16):
     return Spec(num_layers, num_q_heads, num_kv_heads, k_dim, k_dim if v_dim is None else v_dim,
-                1 if v_aliases_k else 0, block_tokens, 64)
+                1 if v_aliases_k else 0, block_tokens, 64, param_format)
 
 
 class Pool:
@@ -107,9 +113,10 @@ class Pool:
         self.scale = torch.zeros(shp + (dim // 64,), dtype=torch.int16, device=device)
         self.bias = torch.zeros(shp + (dim // 64,), dtype=torch.int16, device=device)
         if poison:                      # every slot decodes to NaN until it is written
+            nan_bits = 0x7FC0 if spec.param_format == PARAMS_BF16 else 0x7E00
             self.codes.fill_(-1)
-            self.scale.fill_(0x7E00)
-            self.bias.fill_(0x7E00)
+            self.scale.fill_(nan_bits)
+            self.bias.fill_(nan_bits)
 
     def c(self):
         return _CPool(self.codes.data_ptr(), self.scale.data_ptr(), self.bias.data_ptr(), self.num_blocks)
@@ -161,8 +168,9 @@ def q4kv_read_probe(buf, sink):
                                  _stream()))
 
 
-def q4kv_quantize(x, codes=None, scale=None, bias=None):
-    """x: fp16 [..., dim] on the GPU -> (codes int32 [..., dim/8], scale int16 [..., dim/64], bias same)."""
+def q4kv_quantize(x, codes=None, scale=None, bias=None, param_format=None):
+    """x: fp16 [..., dim] on the GPU -> (codes int32 [..., dim/8], scale int16 [..., dim/64], bias same).
+    param_format None: q4kv_quantize; PARAMS_F16 / PARAMS_BF16: q4kv_quantize_fmt."""
     dim = x.shape[-1]
     rows = x.numel() // dim if dim else 0
     lead = tuple(x.shape[:-1])
@@ -170,19 +178,24 @@ def q4kv_quantize(x, codes=None, scale=None, bias=None):
         codes = torch.empty(lead + (dim // 8,), dtype=torch.int32, device=x.device)
         scale = torch.empty(lead + (dim // 64,), dtype=torch.int16, device=x.device)
         bias = torch.empty(lead + (dim // 64,), dtype=torch.int16, device=x.device)
-    _check(lib().q4kv_quantize(_dev(x, torch.float16, "x"), rows, dim, _dev(codes, torch.int32, "codes"),
-                               _dev(scale, torch.int16, "scale"), _dev(bias, torch.int16, "bias"), _stream()))
+    outs = (_dev(codes, torch.int32, "codes"), _dev(scale, torch.int16, "scale"), _dev(bias, torch.int16, "bias"))
+    if param_format is None:
+        _check(lib().q4kv_quantize(_dev(x, torch.float16, "x"), rows, dim, *outs, _stream()))
+    else:
+        _check(lib().q4kv_quantize_fmt(_dev(x, torch.float16, "x"), rows, dim, int(param_format), *outs, _stream()))
     return codes, scale, bias
 
 
-def q4kv_dequantize(codes, scale, bias, out=None):
+def q4kv_dequantize(codes, scale, bias, out=None, param_format=None):
     dim = codes.shape[-1] * 8
     rows = codes.numel() // codes.shape[-1] if codes.shape[-1] else 0
     if out is None:
         out = torch.empty(tuple(codes.shape[:-1]) + (dim,), dtype=torch.float16, device=codes.device)
-    _check(lib().q4kv_dequantize(_dev(codes, torch.int32, "codes"), _dev(scale, torch.int16, "scale"),
-                                 _dev(bias, torch.int16, "bias"), rows, dim, _dev(out, torch.float16, "out"),
-                                 _stream()))
+    ins = (_dev(codes, torch.int32, "codes"), _dev(scale, torch.int16, "scale"), _dev(bias, torch.int16, "bias"))
+    if param_format is None:
+        _check(lib().q4kv_dequantize(*ins, rows, dim, _dev(out, torch.float16, "out"), _stream()))
+    else:
+        _check(lib().q4kv_dequantize_fmt(*ins, rows, dim, int(param_format), _dev(out, torch.float16, "out"), _stream()))
     return out
 
 

@@ -34,6 +34,8 @@ int check_spec(const q4kv_spec *s)
     if (s->k_dim <= 0 || s->v_dim <= 0 || s->k_dim % 64 || s->v_dim % 64)
         return fail(Q4KV_ESHAPE, "k_dim and v_dim must be positive multiples of 64");
     if (s->v_aliases_k && s->v_dim > s->k_dim) return fail(Q4KV_ESHAPE, "v_aliases_k needs v_dim <= k_dim");
+    if (s->param_format != Q4KV_PARAMS_F16 && s->param_format != Q4KV_PARAMS_BF16)
+        return fail(Q4KV_EINVAL, "param_format %d is neither Q4KV_PARAMS_F16 nor Q4KV_PARAMS_BF16", s->param_format);
     return Q4KV_OK;
 }
 
@@ -108,28 +110,46 @@ int64_t q4kv_cache_bytes(const q4kv_spec *spec, int64_t tokens)
     return elems / 2 + 4 * (elems / 64);
 }
 
-int q4kv_quantize(const uint16_t *x, int64_t rows, int32_t dim, uint32_t *codes, uint16_t *scale, uint16_t *bias,
-                  void *hip_stream)
+int q4kv_quantize_fmt(const uint16_t *x, int64_t rows, int32_t dim, int32_t param_format, uint32_t *codes,
+                      uint16_t *scale, uint16_t *bias, void *hip_stream)
 {
+    if (param_format != Q4KV_PARAMS_F16 && param_format != Q4KV_PARAMS_BF16)
+        return fail(Q4KV_EINVAL, "param_format %d is neither Q4KV_PARAMS_F16 nor Q4KV_PARAMS_BF16", param_format);
     if (dim <= 0 || dim % 64) return fail(Q4KV_ESHAPE, "dim must be a positive multiple of 64");
     if (rows < 0) return fail(Q4KV_EINVAL, "rows < 0");
     if (rows == 0) return Q4KV_OK;
     if (!x || !codes || !scale || !bias) return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(x) || !aligned16(codes)) return fail(Q4KV_EINVAL, "x and codes must be 16-byte aligned");
-    hipError_t e = q4kv::launch_quantize(x, rows, dim, codes, scale, bias, (hipStream_t)hip_stream);
+    hipError_t e = q4kv::launch_quantize(x, rows, dim, param_format == Q4KV_PARAMS_BF16, codes, scale, bias,
+                                         (hipStream_t)hip_stream);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "quantize launch: %s", hipGetErrorString(e));
+}
+
+int q4kv_quantize(const uint16_t *x, int64_t rows, int32_t dim, uint32_t *codes, uint16_t *scale, uint16_t *bias,
+                  void *hip_stream)
+{
+    return q4kv_quantize_fmt(x, rows, dim, Q4KV_PARAMS_F16, codes, scale, bias, hip_stream);
+}
+
+int q4kv_dequantize_fmt(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows, int32_t dim,
+                        int32_t param_format, uint16_t *x, void *hip_stream)
+{
+    if (param_format != Q4KV_PARAMS_F16 && param_format != Q4KV_PARAMS_BF16)
+        return fail(Q4KV_EINVAL, "param_format %d is neither Q4KV_PARAMS_F16 nor Q4KV_PARAMS_BF16", param_format);
+    if (dim <= 0 || dim % 64) return fail(Q4KV_ESHAPE, "dim must be a positive multiple of 64");
+    if (rows < 0) return fail(Q4KV_EINVAL, "rows < 0");
+    if (rows == 0) return Q4KV_OK;
+    if (!x || !codes || !scale || !bias) return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!aligned16(x) || !aligned16(codes)) return fail(Q4KV_EINVAL, "x and codes must be 16-byte aligned");
+    hipError_t e = q4kv::launch_dequantize(codes, scale, bias, rows, dim, param_format == Q4KV_PARAMS_BF16, x,
+                                           (hipStream_t)hip_stream);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "dequantize launch: %s", hipGetErrorString(e));
 }
 
 int q4kv_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows, int32_t dim,
                     uint16_t *x, void *hip_stream)
 {
-    if (dim <= 0 || dim % 64) return fail(Q4KV_ESHAPE, "dim must be a positive multiple of 64");
-    if (rows < 0) return fail(Q4KV_EINVAL, "rows < 0");
-    if (rows == 0) return Q4KV_OK;
-    if (!x || !codes || !scale || !bias) return fail(Q4KV_EINVAL, "NULL pointer");
-    if (!aligned16(x) || !aligned16(codes)) return fail(Q4KV_EINVAL, "x and codes must be 16-byte aligned");
-    hipError_t e = q4kv::launch_dequantize(codes, scale, bias, rows, dim, x, (hipStream_t)hip_stream);
-    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "dequantize launch: %s", hipGetErrorString(e));
+    return q4kv_dequantize_fmt(codes, scale, bias, rows, dim, Q4KV_PARAMS_F16, x, hip_stream);
 }
 
 int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *k_new,

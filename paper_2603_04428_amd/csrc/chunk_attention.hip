@@ -9,10 +9,17 @@
 //  * A workgroup (4 waves) owns 128 query rows of one (layer, agent, KV head): 128/n_rep consecutive chunk
 //    positions times the n_rep query heads of the group.  Each wave owns 32 rows.
 //  * KV tiles of 64 tokens are fetched as Q4 (codes + scale/bias, coalesced 16-byte loads, prefetched one
-//    tile ahead into registers), dequantized ONCE per workgroup into LDS as binary16 and reused by all 128
+//    tile ahead into registers), unpacked ONCE per workgroup into LDS as binary16 and reused by all 128
 //    rows, both row-major with the dims inside a word in the order the nibble masks deliver them
-//    (0,4,1,5,2,6,3,7): the query operand uses the same order for K_hat, the output store undoes it for V_hat.
-//  * The wave computes S^T = K_hat Q^T (tokens are the M rows), so that the probabilities come out of the
+//    (0,4,1,5,2,6,3,7): the query operand uses the same order for K, the output store undoes it for V_hat.
+//  * K stays factored, S^T = sum_g s[t,g] (C_g Q_g^T) + b Qsum^T: the K rows in LDS are the bare codes (binary16
+//    subnormals c 2^-24, odd nibbles 16 c 2^-24 against q/16), the matrix core multiplies them exactly, and the
+//    per-(token, group) scale meets the binary32 result of each group; the bias term is one more matrix
+//    instruction per 16 tokens whose contraction runs over the groups (group sums of q split into a binary16 high
+//    and low part).  A K row dequantized to binary16 would carry an absolute rounding error of 2^-11 |K_hat|,
+//    which the large channels of real key caches turn into score errors of several 1e-3.  V_hat is dequantized
+//    to binary16 (its rounding error is relative to the values that are averaged).
+//  * The wave computes S^T (tokens are the M rows), so that the probabilities come out of the
 //    matrix core already in the register layout the second GEMM wants for its B operand (P^T); no shuffle
 //    or LDS round trip between the GEMMs.  O^T = V_hat^T P^T accumulates in binary32; its A operand wants 8
 //    tokens of one dim per lane, which the transposing LDS read (ds_read_b64_tr_b16) delivers straight from the
@@ -104,14 +111,15 @@ struct Stage {
 // QT: 16-row query tiles per wave.  Two tiles halve the LDS operand traffic per matrix instruction; one tile keeps
 // a wave within 256 registers also at D = 256, so that two waves share a SIMD and one wave's dequantization and
 // softmax run under the other's matrix instructions.  The workgroup always owns 128 rows: 128 / (16 QT) waves.
-template <int DK, int DV, int NREP, int QT>
+// BF: scale and bias are stored as bfloat16 (converted to binary16 when a row is staged).
+template <int DK, int DV, int NREP, int QT, bool BF>
 __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attention_kernel(ChunkParams p)
 {
     constexpr int kRowsWave = 16 * QT;
     constexpr int kWaves = kRowsWG / kRowsWave;
     constexpr int kThreads = kWaves * kWave;
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
-    // halves per row of the dequantized tiles in LDS.  K_hat rows are read 16 bytes per lane by 16 rows at a time
+    // halves per row of the unpacked tiles in LDS.  K rows (codes) are read 16 bytes per lane by 16 rows at a time
     // (pitch = 16 bytes mod 256), V_hat rows 8 bytes per lane by 4 rows x 32 bytes at a time (pitch = 32 mod 256)
     constexpr int KPITCH = DK + 8;
     constexpr int VPITCH = DV + 16;
@@ -121,9 +129,12 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     typedef Stage<DK, kThreads> SK;    // staging of the K rows of a tile ...
     typedef Stage<DV, kThreads> SV;    // ... and of its V rows
 
-    // two tiles each: while the waves multiply against one, they dequantize the next into the other
-    __shared__ __attribute__((aligned(16))) half_t k_lds[2][kTile * KPITCH];
-    __shared__ __attribute__((aligned(16))) half_t v_lds[2][kTile * VPITCH];
+    // two tiles each: while the waves multiply against one, they unpack the next into the other
+    __shared__ __attribute__((aligned(16))) half_t k_lds[2][kTile * KPITCH]; // codes (c or 16 c) * 2^-24
+    __shared__ __attribute__((aligned(16))) half_t v_lds[2][kTile * VPITCH]; // V_hat
+    __shared__ __attribute__((aligned(16))) half_t ks_lds[2][GK * kTile];    // K scale [group][token]
+    // K bias [token][8]: groups 0..3 (zero padded) twice, against the high and the low parts of the group sums of q
+    __shared__ __attribute__((aligned(16))) half_t kb_lds[2][kTile * 8];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -153,6 +164,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     const int qn = lane % 16, kb = lane / 16;
     int row_pos[QT], row_vis[QT], row_first[QT];
     half8_t qop[QT][KSTEPS];
+    half8_t qsop[QT]; // lanes kb == 0: group sums of this row's q, high parts in slots 0..3, low parts in 4..7; else 0
     const int64_t q_agent = ((int64_t)li * p.num_agents + agent) * p.q_len;
 #pragma unroll
     for (int qi = 0; qi < QT; ++qi) {
@@ -163,14 +175,31 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         row_vis[qi] = live ? n - (p.q_len - 1 - c) : 0;
         row_first[qi] = (window > 0 && row_vis[qi] > window) ? row_vis[qi] - window : 0;
         const uint16_t *src = p.q + ((q_agent + (live ? c : 0)) * p.q_heads + head) * DK;
+        float qs[GK];
+#pragma unroll
+        for (int g = 0; g < GK; ++g) qs[g] = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
-            // dims 32*ks + 8*kb .. +7 in the order the nibble masks emit them: 0,4,1,5,2,6,3,7
+            // dims 32*ks + 8*kb .. +7 in the order the nibble masks emit them: 0,4,1,5,2,6,3,7; the odd ones divided
+            // by 16 because their codes arrive 16 times larger
             const uint4 raw = *reinterpret_cast<const uint4 *>(src + 32 * ks + 8 * kb);
             const half2_t e01 = bits_to_half2(raw.x), e23 = bits_to_half2(raw.y);
             const half2_t e45 = bits_to_half2(raw.z), e67 = bits_to_half2(raw.w);
-            qop[qi][ks] = half8_t{e01.x, e45.x, e01.y, e45.y, e23.x, e67.x, e23.y, e67.y};
+            const half_t sixteenth = (half_t)0.0625f;
+            qop[qi][ks] = half8_t{e01.x, e45.x, e01.y * sixteenth, e45.y * sixteenth,
+                                  e23.x, e67.x, e23.y * sixteenth, e67.y * sixteenth};
+            qs[ks / 2] += ((float)e01.x + (float)e01.y) + ((float)e23.x + (float)e23.y) +
+                          ((float)e45.x + (float)e45.y) + ((float)e67.x + (float)e67.y);
         }
+        half_t part[8];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float v = g < GK ? xor32_sum(xor16_sum(qs[g < GK ? g : 0])) : 0.0f; // over the four lanes of the row
+            const half_t hi = (half_t)v;
+            part[g] = kb == 0 ? hi : (half_t)0.0f;
+            part[4 + g] = kb == 0 ? (half_t)(v - (float)hi) : (half_t)0.0f;
+        }
+        qsop[qi] = half8_t{part[0], part[1], part[2], part[3], part[4], part[5], part[6], part[7]};
     }
     // what every row of this wave sees / hides (rows differ along lane % 16): tiles inside [all_first, all_vis)
     // need no masks
@@ -206,7 +235,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     // evenly the last waves stage nothing
     const int32_t *table = p.block_table + (int64_t)agent * p.max_blocks;
     uint32_t kraw[SK::WPT], vraw[SV::WPT];
-    uint32_t ksb[2], vsb[2]; // scale / bias bits of the group this thread dequantizes
+    uint32_t ksb[2], vsb[2]; // scale / bias bits of the group this thread unpacks
     // 16 consecutive lanes take 16 consecutive tokens (and the same part of the row): their 16-byte LDS stores then
     // fall into 16 different bank groups, like the operand reads
     const bool k_on = SK::ACTIVE == kThreads || tid < SK::ACTIVE, v_on = SV::ACTIVE == kThreads || tid < SV::ACTIVE;
@@ -243,7 +272,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         vsb[0] = p.v_scale[vrow * GV + (v_on ? v_grp : 0)];
         vsb[1] = p.v_bias[vrow * GV + (v_on ? v_grp : 0)];
     };
-    // dequantize the staged words of one row into LDS.  Rows of an unreachable block and rows at or past t_end
+    // unpack the staged words of one row into LDS (V: dequantized; K: codes, see store_codes).  Rows of an unreachable block and rows at or past t_end
     // (never visible, possibly never written) become zeros, so that no stale bit pattern can reach an accumulator.
     // Dequantization of the staged rows happens one code word (8 dims, one 16-byte store) at a time, so that the
     // matrix loops below can take a word between their steps: a wave cannot overlap its own vector and matrix
@@ -254,8 +283,12 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     };
     auto row_params = [&](const uint32_t (&sb)[2], bool ok) {
         RowDequant r;
-        const half_t s = ok ? __builtin_bit_cast(half_t, (uint16_t)sb[0]) : (half_t)0.0f;
-        const half_t b = ok ? __builtin_bit_cast(half_t, (uint16_t)sb[1]) : (half_t)0.0f;
+        // bfloat16 parameters of binary16-range data convert exactly (8 significant bits into 11) unless they are
+        // below 2^-14, where the difference is far below what binary16 operands resolve anyway
+        const half_t s_in = BF ? (half_t)bf16_bits_to_float((uint16_t)sb[0]) : __builtin_bit_cast(half_t, (uint16_t)sb[0]);
+        const half_t b_in = BF ? (half_t)bf16_bits_to_float((uint16_t)sb[1]) : __builtin_bit_cast(half_t, (uint16_t)sb[1]);
+        const half_t s = ok ? s_in : (half_t)0.0f;
+        const half_t b = ok ? b_in : (half_t)0.0f;
         r.s2 = half2_t{s, s};
         r.b2 = half2_t{b, b};
         r.s16 = r.s2 * half2_t{(half_t)0.0625f, (half_t)0.0625f};
@@ -270,6 +303,23 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         const half2_t v3 = pk_fma(nibbles_hi16(w8), r.s16, r.b2);   // dims 3, 7
         *reinterpret_cast<uint4 *>(dst) = make_uint4(half2_to_bits(v0), half2_to_bits(v1), half2_to_bits(v2), half2_to_bits(v3));
     };
+    // K rows keep their codes: the nibbles masked in place are binary16 subnormals c 2^-24 (dims 0, 4, 2, 6 of a
+    // word) and 16 c 2^-24 (dims 1, 5, 3, 7); the row's scale and bias go to LDS beside them, written by the thread
+    // that holds the first word of the group
+    auto store_codes = [&](half_t *dst, uint32_t raw, bool ok) {
+        const uint32_t word = ok ? raw : 0u, w8 = word >> 8;
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(word & 0x000F000Fu, word & 0x00F000F0u, w8 & 0x000F000Fu, w8 & 0x00F000F0u);
+    };
+    const bool k_params_writer = k_on && (k_w0 * 8) % kGroup == 0;
+    auto store_k_params = [&](int b, const RowDequant &r) {
+        ks_lds[b][k_grp * kTile + k_tok] = r.s2.x;
+        kb_lds[b][k_tok * 8 + k_grp] = r.b2.x;
+        kb_lds[b][k_tok * 8 + 4 + k_grp] = r.b2.x;
+    };
+    if constexpr (GK < 4) { // bias slots of groups the rows do not have: zero once (their q sums are zero too)
+        for (int i = tid; i < 2 * kTile * 8 / 2; i += kThreads) reinterpret_cast<uint32_t *>(&kb_lds[0][0])[i] = 0u;
+        __syncthreads();
+    }
     // rows of an unreachable block and rows at or past t_end (never visible, possibly never written) become zeros,
     // so that no stale bit pattern can reach an accumulator
     auto row_ok = [&](int t0, int tok, bool ok_tile) { return ok_tile && (t0 + tok < t_end); };
@@ -280,7 +330,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     const int v_lane = (4 * kb + qn / 4) * VPITCH + 4 * (qn % 4);
 
     // One barrier per tile: tile i is multiplied out of buffer i % 2 while tile i + 1 (already in registers) is
-    // dequantized into the other buffer and tile i + 2 is fetched.
+    // unpacked into the other buffer and tile i + 2 is fetched.
     bool ok_next = false, ok_cur = false;
     int buf = 0;
     const int t_last = t_begin < t_end ? t_begin + (t_end - 1 - t_begin) / kTile * kTile : 0; // start of the last tile
@@ -290,8 +340,9 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         const RowDequant vr = row_params(vsb, row_ok(t_begin, v_tok, ok_next));
         if (k_on) {
 #pragma unroll
-            for (int w = 0; w < SK::WPT; ++w) store_word(k_lds[0] + k_dst + 8 * w, kraw[w], kr);
+            for (int w = 0; w < SK::WPT; ++w) store_codes(k_lds[0] + k_dst + 8 * w, kraw[w], kr.ok);
         }
+        if (k_params_writer) store_k_params(0, kr);
         if (v_on) {
 #pragma unroll
             for (int w = 0; w < SV::WPT; ++w) store_word(v_lds[0] + v_dst + 8 * w, vraw[w], vr);
@@ -303,44 +354,101 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
         const half_t *k_cur = k_lds[buf], *v_cur = v_lds[buf];
 
-        // ---- S^T = K_hat Q^T : [64 tokens][16 QT query rows] per wave, binary32.  Step ks multiplies the four
-        // 16-token tiles against dims 32 ks .. 32 ks + 31 (operands fetched one step ahead), then takes its share of
-        // the next tile's K rows: registers -> LDS (other buffer).  Past the last tile that stores zeros into the
-        // idle buffer: straight-line code keeps the mix.
+        // ---- S^T = sum_g s_g (C_g Q_g^T) + b Qsum^T : [64 tokens][16 QT query rows] per wave, binary32, in units of
+        // 2^-24.  An item is one (group, 16-token tile): two matrix instructions per query tile over the group's 64
+        // dims into a fresh accumulator; while they run, the item before meets its scales (one fused multiply-add
+        // per score).  Operands and scales are fetched two items ahead; the next tile's K rows go registers -> LDS
+        // (other buffer) between the items.  Past the last tile that stores zeros into the idle buffer:
+        // straight-line code keeps the mix.
         const bool ok_this = ok_cur;
         const bool more = t0 + kTile < t_end;
         const RowDequant kr = row_params(ksb, row_ok(t0 + kTile, k_tok, ok_next && more));
         const RowDequant vr = row_params(vsb, row_ok(t0 + kTile, v_tok, ok_next && more));
+        const half_t *ks_cur = ks_lds[buf], *kb_cur = kb_lds[buf];
+        const float4_t zero4 = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
         float4_t st[QT][kTile / 16]; // [q tile][token tile]: lane column = query row, regs = tokens 4*kb .. 4*kb+3
 #pragma unroll
-        for (int qi = 0; qi < QT; ++qi)
+        for (int tt = 0; tt < kTile / 16; ++tt) { // bias term: A = b[token][group slots], B = group sums of q
+            const half8_t ba = *reinterpret_cast<const half8_t *>(kb_cur + (tt * 16 + qn) * 8);
 #pragma unroll
-            for (int tt = 0; tt < kTile / 16; ++tt) st[qi][tt] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-        constexpr int KA_AHEAD = KSTEPS > 2 ? 2 : 1; // steps the operand reads run ahead
-        half8_t ka[KA_AHEAD + 1][kTile / 16];
-        auto load_ka = [&](int ks) {
-#pragma unroll
-            for (int tt = 0; tt < kTile / 16; ++tt)
-                ka[ks % (KA_AHEAD + 1)][tt] =
-                    *reinterpret_cast<const half8_t *>(k_cur + (tt * 16 + qn) * KPITCH + 32 * ks + 8 * kb);
+            for (int qi = 0; qi < QT; ++qi) st[qi][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ba, qsop[qi], zero4, 0, 0, 0);
+        }
+        // TPI token tiles per item.  One: the two dependent matrix instructions of an item follow each other
+        // directly, which measured faster than pairing token tiles for two independent chains (742 against 732
+        // TFLOP/s at D = 256) because the operand ring stays small.
+        constexpr int TPI = 1;
+        constexpr int kItemsPerGroup = kTile / 16 / TPI;
+        constexpr int kItems = GK * kItemsPerGroup;
+        constexpr int kAhead = TPI == 2 ? 1 : 2; // items the operand reads run ahead (the ring must fit the registers)
+        struct ItemIn {
+            half8_t a0[TPI], a1[TPI]; // codes of token 16 tt + qn, dims 64 g + 8 kb .. and 64 g + 32 + 8 kb ..
+            uint2 s4[TPI];            // scales of tokens 16 tt + 4 kb .. + 3, group g
         };
+        auto load_item = [&](int it) {
+            const int g = it / kItemsPerGroup, tt0 = (it % kItemsPerGroup) * TPI;
+            ItemIn in;
 #pragma unroll
-        for (int ks = 0; ks < KA_AHEAD; ++ks) load_ka(ks);
+            for (int j = 0; j < TPI; ++j) {
+                const half_t *row = k_cur + ((tt0 + j) * 16 + qn) * KPITCH + 64 * g + 8 * kb;
+                in.a0[j] = *reinterpret_cast<const half8_t *>(row);
+                in.a1[j] = *reinterpret_cast<const half8_t *>(row + 32);
+                in.s4[j] = *reinterpret_cast<const uint2 *>(ks_cur + g * kTile + (tt0 + j) * 16 + 4 * kb);
+            }
+            return in;
+        };
+        ItemIn item[kAhead + 1];
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            if (ks + KA_AHEAD < KSTEPS) load_ka(ks + KA_AHEAD);
+        for (int it = 0; it < kAhead; ++it) item[it] = load_item(it);
+        float4_t dq[2][TPI][QT]; // raw group products of the item in flight and of the one before
+        uint2 s_prev[TPI];
 #pragma unroll
-            for (int tt = 0; tt < kTile / 16; ++tt)
+        for (int it = 0; it <= kItems; ++it) {
+            if (it + kAhead < kItems) item[(it + kAhead) % (kAhead + 1)] = load_item(it + kAhead);
+            if (it < kItems) {
+                const int g = it / kItemsPerGroup;
+                const ItemIn &in = item[it % (kAhead + 1)];
 #pragma unroll
-                for (int qi = 0; qi < QT; ++qi)
-                    st[qi][tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[ks % (KA_AHEAD + 1)][tt], qop[qi][ks],
-                                                                        st[qi][tt], 0, 0, 0);
-            // words of the K row spread evenly over the steps
+                for (int j = 0; j < TPI; ++j)
+#pragma unroll
+                    for (int qi = 0; qi < QT; ++qi)
+                        dq[it & 1][j][qi] = __builtin_amdgcn_mfma_f32_16x16x32_f16(in.a0[j], qop[qi][2 * g], zero4, 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < TPI; ++j)
+#pragma unroll
+                    for (int qi = 0; qi < QT; ++qi)
+                        dq[it & 1][j][qi] =
+                            __builtin_amdgcn_mfma_f32_16x16x32_f16(in.a1[j], qop[qi][2 * g + 1], dq[it & 1][j][qi], 0, 0, 0);
+            }
+            if (it > 0) { // the item before: scores += scale * product
+                const int g = (it - 1) / kItemsPerGroup, tt0 = ((it - 1) % kItemsPerGroup) * TPI;
+#pragma unroll
+                for (int j = 0; j < TPI; ++j) {
+                    const half2_t s01 = bits_to_half2(s_prev[j].x), s23 = bits_to_half2(s_prev[j].y);
+#pragma unroll
+                    for (int qi = 0; qi < QT; ++qi) {
+                        float4_t acc = st[qi][tt0 + j];
+                        if (g == 0) acc = acc * 0x1p-24f; // the bias term enters in the products' unit
+                        const float4_t d = dq[(it - 1) & 1][j][qi];
+                        acc[0] = fmaf((float)s01.x, d[0], acc[0]);
+                        acc[1] = fmaf((float)s01.y, d[1], acc[1]);
+                        acc[2] = fmaf((float)s23.x, d[2], acc[2]);
+                        acc[3] = fmaf((float)s23.y, d[3], acc[3]);
+                        st[qi][tt0 + j] = acc;
+                    }
+                }
+            }
+            if (it < kItems) {
+#pragma unroll
+                for (int j = 0; j < TPI; ++j) s_prev[j] = item[it % (kAhead + 1)].s4[j];
+            }
+            // words of the K row spread evenly over the items
 #pragma unroll
             for (int w = 0; w < SK::WPT; ++w)
-                if (w * KSTEPS / SK::WPT == ks && k_on) store_word(k_lds[buf ^ 1] + k_dst + 8 * w, kraw[w], kr);
+                if (w * kItems / SK::WPT == it && k_on) store_codes(k_lds[buf ^ 1] + k_dst + 8 * w, kraw[w], kr.ok);
+            if (it == 1 && k_params_writer) store_k_params(buf ^ 1, kr);
             __builtin_amdgcn_sched_barrier(0);
         }
+        const float zscale = p.score_scale * 16777216.0f; // scores are in units of 2^-24
 
         // ---- online softmax per query row (lane column), then P^T in binary16 as the next B operand
         const bool masked = !(ok_this && t0 >= all_first && t0 + kTile <= all_vis); // wave-uniform
@@ -356,7 +464,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
                 for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        float z = st[qi][tt][e] * p.score_scale;
+                        float z = st[qi][tt][e] * zscale;
                         const int t = t0 + tt * 16 + 4 * kb + e;
                         if (!(ok_this && t < row_vis[qi] && t >= row_first[qi])) z = kNegBig;
                         st[qi][tt][e] = z;
@@ -367,7 +475,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
                 for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) mx = fmaxf(mx, st[qi][tt][e]);
-                mx *= p.score_scale;
+                mx *= zscale;
             }
             // the row's tokens live in the 4 lanes qn, qn+16, qn+32, qn+48
             mx = xor32_max(xor16_max(mx));
@@ -392,7 +500,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
                 for (int tt = 0; tt < kTile / 16; ++tt)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float pr = __builtin_amdgcn_exp2f(fmaf(st[qi][tt][e], p.score_scale, -m_new));
+                        const float pr = __builtin_amdgcn_exp2f(fmaf(st[qi][tt][e], zscale, -m_new));
                         st[qi][tt][e] = pr;
                         sum += pr;
                     }
@@ -405,23 +513,18 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
                                      (half_t)st[qi][2 * tb + 1][2], (half_t)st[qi][2 * tb + 1][3]};
         }
         if (__builtin_amdgcn_ballot_w64(any_moved) != 0ull) {
-            // Rare after a row's first tiles.  The empty asm statements tie the accumulators to the accumulator
-            // registers on entry and the products return through a matrix instruction with zero operands
-            // (0*0 + C = C), so that on the path that skips this block they never leave those registers.
-            const half8_t none = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+            // Rare after a row's first tiles.  (This file is compiled with matrix results in vector registers, so
+            // the accumulators are ordinary operands here.)
 #pragma unroll
             for (int qi = 0; qi < QT; ++qi)
 #pragma unroll
-                for (int et = 0; et < ETILES; ++et) {
-                    asm volatile("" : "+a"(o_acc[qi][et]));
-                    o_acc[qi][et] = __builtin_amdgcn_mfma_f32_16x16x32_f16(none, none, o_acc[qi][et] * alpha[qi], 0, 0, 0);
-                }
+                for (int et = 0; et < ETILES; ++et) o_acc[qi][et] = o_acc[qi][et] * alpha[qi];
         }
 
         // ---- O^T += V_hat^T P^T : A operand = 8 tokens of one dim in P^T's token order (tokens 4 kb .. + 3 of
         // both 16-token tiles of a 32-token block), fetched with two transposing reads one step ahead; the next
         // tile's V rows are dequantized between the steps
-        constexpr int VA_AHEAD = 3; // steps the operand reads run ahead
+        constexpr int VA_AHEAD = 2; // steps the operand reads run ahead
         half8_t va[VA_AHEAD + 1][2]; // [step in the ring][32-token block]
         auto load_va = [&](int et) {
 #pragma unroll
@@ -477,7 +580,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
 template <int DK, int DV, int NREP>
 hipError_t launch_chunk_t(const AttentionArgs &a, hipStream_t stream)
 {
-    constexpr int QT = DK >= 256 ? 1 : 2;
+    constexpr int QT = (DK == 128 || DK >= 256) ? 1 : 2; // two tiles where the registers allow it without scratch
     constexpr int kThreads = kRowsWG / (16 * QT) * kWave;
     ChunkParams p;
     p.k_codes = a.k.codes; p.k_scale = a.k.scale; p.k_bias = a.k.bias;
@@ -498,7 +601,10 @@ hipError_t launch_chunk_t(const AttentionArgs &a, hipStream_t stream)
     const int64_t grid = units_padded * p.q_tiles;
     if (grid <= 0) return hipSuccess;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((chunk_attention_kernel<DK, DV, NREP, QT>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    if (a.spec.param_format == Q4KV_PARAMS_BF16)
+        hipLaunchKernelGGL((chunk_attention_kernel<DK, DV, NREP, QT, true>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
+    else
+        hipLaunchKernelGGL((chunk_attention_kernel<DK, DV, NREP, QT, false>), dim3((unsigned)grid), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -33,7 +33,10 @@ __device__ __forceinline__ half2_t octet_pk_min(half2_t v)
 }
 
 // Quantize the 8 elements held by this lane; the 8 lanes of an octet form one group.
-// Returns the packed word; *scale_bits / *bias_bits are the group's stored parameters.
+// Returns the packed word; *scale_bits / *bias_bits are the group's stored parameters: binary16, or bfloat16 when
+// BF.  The codes are taken against the stored parameters; a bfloat16 bias is in general not the minimum itself, so
+// quotients may fall below 0 or above 15 and are clamped.
+template <bool BF>
 __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet, uint16_t *scale_bits,
                                                    uint16_t *bias_bits)
 {
@@ -67,9 +70,11 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
         for (int off = 4; off >= 1; off >>= 1) key = min(key, (uint32_t)__shfl_xor((int)key, off, 8));
         bb = (key & 1u) ? 0x8000u : 0x0000u;
     }
+    if (BF && mn != 0.0f) bb = float_to_bf16_bits(mn); // +-0 has the same bits in both types
+    const float b = BF ? bf16_bits_to_float(bb) : mn;  // what a decoder adds back
     const float scale32 = (mx - mn) / 15.0f;      // IEEE binary32 division
-    const uint16_t sb = float_to_half_bits(scale32);
-    const float s = half_bits_to_float(sb);
+    const uint16_t sb = BF ? float_to_bf16_bits(scale32) : float_to_half_bits(scale32);
+    const float s = param_bits_to_float<BF>(sb);
     uint32_t word = 0;
     if (s != 0.0f) {
         // code = clamp(rint(fl(d / s)), 0, 15) with a correctly rounded binary32 division.  The division is the
@@ -79,20 +84,23 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
         // rint(fl(d / s)) only if a half-integer lies within that distance of t; such octets (about one element in
         // 2^15) redo all eight codes with the true division.  v_cvt_pk_u8_f32 rounds to nearest even and saturates
         // at 0 (checked on the device); quotients reach 15.5 only in the careful path, which clamps them first.
+        // With bfloat16 parameters the bias may lie above the minimum or far below it (|d / s| is then unbounded):
+        // groups whose quotients leave [-0.4, 15.4] take the careful path as well.
         const float inv = __builtin_amdgcn_rcpf(s);
         float d[8], t[8];
         // the upper clamp only matters when the stored scale was rounded down a lot (a binary16 subnormal); then too
         // the lane takes the careful path
-        bool careful = (mx - mn) * inv >= 15.4f;
+        bool careful = (mx - b) * inv >= 15.4f;
+        if (BF) careful |= (mn - b) * inv <= -0.4f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            d[i] = x[i] - mn;
+            d[i] = x[i] - b;
             t[i] = d[i] * inv;
             careful |= fabsf(__builtin_amdgcn_fractf(t[i]) - 0.5f) <= 0x1p-16f;
         }
         if (careful) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) t[i] = fminf(d[i] / s, 15.0f);
+            for (int i = 0; i < 8; ++i) t[i] = fminf(BF ? fmaxf(d[i] / s, 0.0f) : d[i] / s, 15.0f);
         }
         uint32_t even = 0, odd = 0; // codes 0,2,4,6 and 1,3,5,7 as bytes
 #pragma unroll
@@ -108,6 +116,7 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
 }
 
 // Flat form: destination group = source group, no row arithmetic at all.
+template <bool BF>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__restrict__ x, int64_t total_groups,
                                                             uint32_t *__restrict__ codes, uint16_t *__restrict__ scale,
                                                             uint16_t *__restrict__ bias)
@@ -119,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
         rotate_wave_priority(generation);
         const uint4 raw = *reinterpret_cast<const uint4 *>(x + grp * kGroup + sub * 8);
         uint16_t sb, bb;
-        const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
+        const uint32_t word = quantize_octet<BF>(raw, sub, &sb, &bb);
         codes[grp * 8 + sub] = word;
         if (sub == 0) {
             scale[grp] = sb;
@@ -138,6 +147,7 @@ struct AppendParams {
     int max_blocks, chunk_len, heads, layer_begin, num_blocks, groups_per_row;
 };
 
+template <bool BF>
 __global__ __launch_bounds__(kThreads) void append_kernel(const uint16_t *__restrict__ x, uint32_t *__restrict__ codes,
                                                           uint16_t *__restrict__ scale, uint16_t *__restrict__ bias,
                                                           AppendParams p)
@@ -155,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void append_kernel(const uint16_t *__rest
         rotate_wave_priority(generation);
         const uint4 raw = *reinterpret_cast<const uint4 *>(x + (src0 + gi) * kGroup + sub * 8);
         uint16_t sb, bb;
-        const uint32_t word = quantize_octet(raw, sub, &sb, &bb);
+        const uint32_t word = quantize_octet<BF>(raw, sub, &sb, &bb);
         const uint32_t row = gi / (uint32_t)p.groups_per_row, g = gi - row * p.groups_per_row;
         const uint32_t c = row / (uint32_t)p.heads, h = row - c * p.heads;
         const int t = n0 + (int)c;
@@ -174,6 +184,7 @@ __global__ __launch_bounds__(kThreads) void append_kernel(const uint16_t *__rest
 }
 
 // One lane per word: 8 codes -> 8 binary16 values (16 bytes).
+template <bool BF>
 __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__restrict__ codes,
                                                               const uint16_t *__restrict__ scale,
                                                               const uint16_t *__restrict__ bias, int64_t total_words,
@@ -184,8 +195,8 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
     for (int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x; w < total_words; w += stride) {
         rotate_wave_priority(generation);
         const uint32_t word = codes[w];
-        const float s = half_bits_to_float(scale[w >> 3]);
-        const float b = half_bits_to_float(bias[w >> 3]);
+        const float s = param_bits_to_float<BF>(scale[w >> 3]);
+        const float b = param_bits_to_float<BF>(bias[w >> 3]);
         uint32_t o[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -208,24 +219,30 @@ int grid_for(int64_t items, int per_block)
 
 } // namespace
 
-hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, uint32_t *codes, uint16_t *scale,
+hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, bool bf16_params, uint32_t *codes, uint16_t *scale,
                            uint16_t *bias, hipStream_t stream)
 {
     const int G = dim / kGroup;
     const int64_t groups = rows * G;
     if (groups == 0) return hipSuccess;
-    hipLaunchKernelGGL(quantize_kernel, dim3(grid_for(groups, kThreads / 8)), dim3(kThreads), 0, stream, x, groups, codes,
-                       scale, bias);
+    const dim3 grid(grid_for(groups, kThreads / 8));
+    if (bf16_params)
+        hipLaunchKernelGGL(quantize_kernel<true>, grid, dim3(kThreads), 0, stream, x, groups, codes, scale, bias);
+    else
+        hipLaunchKernelGGL(quantize_kernel<false>, grid, dim3(kThreads), 0, stream, x, groups, codes, scale, bias);
     return hipGetLastError();
 }
 
 hipError_t launch_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
-                             int dim, uint16_t *x, hipStream_t stream)
+                             int dim, bool bf16_params, uint16_t *x, hipStream_t stream)
 {
     const int64_t words = rows * (dim / 8);
     if (words == 0) return hipSuccess;
-    hipLaunchKernelGGL(dequantize_kernel, dim3(grid_for(words, kThreads)), dim3(kThreads), 0, stream, codes, scale,
-                       bias, words, x);
+    const dim3 grid(grid_for(words, kThreads));
+    if (bf16_params)
+        hipLaunchKernelGGL(dequantize_kernel<true>, grid, dim3(kThreads), 0, stream, codes, scale, bias, words, x);
+    else
+        hipLaunchKernelGGL(dequantize_kernel<false>, grid, dim3(kThreads), 0, stream, codes, scale, bias, words, x);
     return hipGetLastError();
 }
 
@@ -244,8 +261,11 @@ hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &pool, int dim, 
     const int64_t cap = (256LL * Q4KV_CODEC_WG_PER_CU + (int64_t)layers * num_agents - 1) / ((int64_t)layers * num_agents);
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
-    hipLaunchKernelGGL(append_kernel, dim3((unsigned)gx, (unsigned)num_agents, (unsigned)layers), dim3(kThreads), 0, stream,
-                       x_new, pool.codes, pool.scale, pool.bias, p);
+    const dim3 grid((unsigned)gx, (unsigned)num_agents, (unsigned)layers);
+    if (spec.param_format == Q4KV_PARAMS_BF16)
+        hipLaunchKernelGGL(append_kernel<true>, grid, dim3(kThreads), 0, stream, x_new, pool.codes, pool.scale, pool.bias, p);
+    else
+        hipLaunchKernelGGL(append_kernel<false>, grid, dim3(kThreads), 0, stream, x_new, pool.codes, pool.scale, pool.bias, p);
     return hipGetLastError();
 }
 

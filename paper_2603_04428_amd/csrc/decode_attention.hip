@@ -258,10 +258,10 @@ __device__ __forceinline__ GroupBits<N> load_groups(const uint16_t *p)
     return r;
 }
 
-template <int N>
+template <int N, bool BF>
 __device__ __forceinline__ float group_value(const GroupBits<N> &b, int g)
 {
-    return half_bits_to_float((uint16_t)((g & 1) ? (b.w[g / 2] >> 16) : (b.w[g / 2] & 0xffffu)));
+    return param_bits_to_float<BF>((uint16_t)((g & 1) ? (b.w[g / 2] >> 16) : (b.w[g / 2] & 0xffffu)));
 }
 
 template <int W>
@@ -289,12 +289,13 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 
 // ---------------------------------------------------------------------------------------------- attention
 
-// DK, DV: head widths (multiples of 64); NREP query heads per KV head.
+// DK, DV: head widths (multiples of 64); NREP query heads per KV head; BF: scale and bias are stored as bfloat16
+// instead of binary16 (they are only ever used as binary32 here, so the two differ in one conversion).
 //
 // Loads are never predicated: a tile's 64 rows always exist inside its block, so rows past the agent's
 // length are read and then ignored (their score is forced to "minus infinity", their p*s to zero; codes
 // are nibbles and cannot produce a NaN, scale/bias of such rows are replaced by zero after the load).
-template <int DK, int DV, int NREP>
+template <int DK, int DV, int NREP, bool BF>
 __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attention_kernel(DecodeParams p)
 {
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
@@ -516,13 +517,13 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         float ks[GK], kb[GK], vs[GV], vb[GV];
 #pragma unroll
         for (int g = 0; g < GK; ++g) {
-            ks[g] = group_value<GK>(ks_bits, g) * kCodeScaleA;
-            kb[g] = group_value<GK>(kb_bits, g);
+            ks[g] = group_value<GK, BF>(ks_bits, g) * kCodeScaleA;
+            kb[g] = group_value<GK, BF>(kb_bits, g);
         }
 #pragma unroll
         for (int g = 0; g < GV; ++g) {
-            vs[g] = group_value<GV>(vs_bits, g);
-            vb[g] = group_value<GV>(vb_bits, g);
+            vs[g] = group_value<GV, BF>(vs_bits, g);
+            vb[g] = group_value<GV, BF>(vb_bits, g);
         }
         load_params(row0_next);
         float alpha[NREP];
@@ -708,7 +709,10 @@ hipError_t launch_decode_t(const AttentionArgs &a, hipStream_t stream)
     p.q_heads = a.spec.num_q_heads;
     p.max_slots = a.max_slots;
     p.score_scale = a.sm_scale * kLog2e;
-    hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
+    if (a.spec.param_format == Q4KV_PARAMS_BF16)
+        hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, true>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
+    else
+        hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, false>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -105,7 +105,9 @@ __device__ __forceinline__ float half_of(uint32_t pair, int hi)
 }
 
 // GK, GV: quantization groups of the latent row and of its value part (k_dim = 64 GK, v_dim = 64 GV <= k_dim).
-template <int GK, int GV>
+// BF: scale and bias are stored as bfloat16; they are converted to binary16 (exactly, for parameters of binary16-range
+// data above 2^-14) when a tile's parameters are re-laid in LDS, everything after that is the same.
+template <int GK, int GV, bool BF>
 __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams p)
 {
     static_assert(GV <= 8 && GV <= GK && GK <= 10, "group counts");
@@ -254,8 +256,8 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                 uint32_t s[GK], b[BTP];
 #pragma unroll
                 for (int g = 0; g < GK; ++g) {
-                    s[g] = sraw[g];
-                    b[g] = braw[g];
+                    s[g] = BF ? (uint32_t)float_to_half_bits(bf16_bits_to_float((uint16_t)sraw[g])) : sraw[g];
+                    b[g] = BF ? (uint32_t)float_to_half_bits(bf16_bits_to_float((uint16_t)braw[g])) : braw[g];
                 }
                 if (edge) { // interior tiles (nearly all) skip the selects
 #pragma unroll
@@ -498,7 +500,7 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
     __builtin_amdgcn_s_waitcnt(0x0F70); // the last tile's look-ahead transfer must land before the LDS is released
 }
 
-template <int GK, int GV>
+template <int GK, int GV, bool BF>
 hipError_t launch_mla_t(const AttentionArgs &a, hipStream_t stream)
 {
     MlaParams p;
@@ -509,7 +511,7 @@ hipError_t launch_mla_t(const AttentionArgs &a, hipStream_t stream)
     p.q_heads = a.spec.num_q_heads;
     p.max_slots = a.max_slots;
     p.score_scale = a.sm_scale * kLog2e;
-    hipLaunchKernelGGL((mla_decode_kernel<GK, GV>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((mla_decode_kernel<GK, GV, BF>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -524,7 +526,7 @@ hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t strea
 {
     hipError_t e = launch_plan(a, stream);
     if (e != hipSuccess) return e;
-    return launch_mla_t<9, 8>(a, stream);
+    return a.spec.param_format == Q4KV_PARAMS_BF16 ? launch_mla_t<9, 8, true>(a, stream) : launch_mla_t<9, 8, false>(a, stream);
 }
 
 } // namespace q4kv

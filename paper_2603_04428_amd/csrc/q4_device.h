@@ -24,6 +24,21 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float f)
     return __builtin_bit_cast(uint16_t, (half_t)f); // v_cvt_f16_f32, round to nearest even
 }
 
+// bfloat16 (the upper half of a binary32): the other type scale and bias may be stored in (Sec. 3.1, Sec. 3.2).
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) // finite f, round to nearest even
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+// a stored scale or bias as binary32; BF: the bits are bfloat16, else binary16
+template <bool BF>
+__device__ __forceinline__ float param_bits_to_float(uint16_t b)
+{
+    if constexpr (BF) return bf16_bits_to_float(b);
+    else return half_bits_to_float(b);
+}
+
 // Eight 4-bit codes of one word as four packed binary16 pairs.  A code c placed in the low
 // mantissa bits of a binary16 with zero exponent is the subnormal c * 2^-24 (bits 0..3) or
 // c * 2^-20 (bits 4..7), so no integer-to-float conversion is needed:

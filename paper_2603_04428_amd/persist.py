@@ -8,7 +8,8 @@ parses the header around it.  No arithmetic happens here.
 File = 8-byte little-endian header length, a JSON header padded with spaces to a multiple of 8 bytes, the image.
 Tensor names follow the appendix: L{l}_B{b}_K_weights / _K_scales / _K_biases / _V_weights / _V_scales / _V_biases,
 b counting the agent's blocks in token order.  Shapes are the device layout's, token-major: weights uint32
-(kv_heads, 256, dim/8), scales and biases float16 (kv_heads, 256, dim/64).  (The shapes printed in the appendix
+(kv_heads, 256, dim/8), scales and biases float16 or, when the cache shape says param_format 1, bfloat16
+(kv_heads, 256, dim/64): the appendix names bfloat16 for one model family and float16 for another.  (The shapes printed in the appendix
 disagree with each other about the grouped axis and are not reproduced.)  The header's __metadata__ carries the
 cache shape, the block count and the token count as strings.
 """
@@ -18,11 +19,16 @@ import struct
 import numpy as np
 
 FORMAT = "q4kv-block-image-1"
-SPEC_FIELDS = ("num_layers", "num_q_heads", "num_kv_heads", "k_dim", "v_dim", "v_aliases_k", "block_tokens", "group_size")
+SPEC_FIELDS = ("num_layers", "num_q_heads", "num_kv_heads", "k_dim", "v_dim", "v_aliases_k", "block_tokens", "group_size",
+               "param_format")
+PARAM_DTYPES = {0: "F16", 1: "BF16"}   # safetensors dtype of scales and biases by q4kv_param_format
 
 
 def spec_dict(spec):
-    return {f: int(getattr(spec, f)) for f in SPEC_FIELDS}
+    d = {f: int(getattr(spec, f, 0)) for f in SPEC_FIELDS}
+    if d["param_format"] not in PARAM_DTYPES:
+        raise ValueError(f"unknown param_format {d['param_format']}")
+    return d
 
 
 def tensor_table(spec, num_blocks):
@@ -30,12 +36,13 @@ def tensor_table(spec, num_blocks):
     sd = spec if isinstance(spec, dict) else spec_dict(spec)
     H, T = sd["num_kv_heads"], sd["block_tokens"]
     arrays = [("K", sd["k_dim"])] + ([] if sd["v_aliases_k"] else [("V", sd["v_dim"])])
+    pdt = PARAM_DTYPES[sd.get("param_format", 0)]
     out, off = [], 0
     for l in range(sd["num_layers"]):
         for b in range(num_blocks):
             for tag, dim in arrays:
-                for kind, dtype, last, width in (("weights", "U32", dim // 8, 4), ("scales", "F16", dim // 64, 2),
-                                                 ("biases", "F16", dim // 64, 2)):
+                for kind, dtype, last, width in (("weights", "U32", dim // 8, 4), ("scales", pdt, dim // 64, 2),
+                                                 ("biases", pdt, dim // 64, 2)):
                     n = H * T * last * width
                     out.append((f"L{l}_B{b}_{tag}_{kind}", dtype, [H, T, last], off, off + n))
                     off += n
@@ -96,7 +103,9 @@ def open_agent(path):
     meta = hdr.get("__metadata__") or {}
     if meta.get("format") != FORMAT:
         raise ValueError("not a q4kv agent cache file")
-    sd = {k: int(meta[k]) for k in SPEC_FIELDS}
+    sd = {k: int(meta.get(k, 0)) for k in SPEC_FIELDS}      # files written before param_format existed hold binary16
+    if sd["param_format"] not in PARAM_DTYPES:
+        raise ValueError("unknown param_format in the header")
     num_blocks = int(meta["num_blocks"])
     table = tensor_table(sd, num_blocks)
     if len(hdr) - 1 != len(table):

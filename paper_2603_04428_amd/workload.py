@@ -6,11 +6,12 @@ import torch
 from . import binding as b
 
 
-def build_device_cache(w, device="cuda", poison=True, extra_blocks=1, tokens=None):
+def build_device_cache(w, device="cuda", poison=True, extra_blocks=1, tokens=None, param_format=b.PARAMS_F16):
     """Returns (spec, kpool, vpool, table (host int32 [A][max_blocks], -1 = unused), table on the device).
     Every agent's tokens 0..len-1 are generated on the device layer by layer and appended into freshly
     allocated blocks whose physical ids are shuffled over the pool."""
-    spec = b.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k)
+    spec = b.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k,
+                       param_format=param_format)
     table, nb = w.block_table()
     nb += extra_blocks
     kpool = b.Pool(spec, w.k_dim, nb, device, poison)

@@ -11,17 +11,20 @@ from paper_2603_04428_amd.workload import build_device_cache
 DEV = "cuda"
 
 
-def gpu_cache(w, poison=True, extra_blocks=1, tokens=None):
-    """Device pools of workload w filled with tokens 0..final_len-1 of every agent via q4kv_append."""
-    return build_device_cache(w, DEV, poison, extra_blocks, tokens)
+def gpu_cache(w, poison=True, extra_blocks=1, tokens=None, param_format=0):
+    """Device pools of workload w filled with tokens 0..final_len-1 of every agent via q4kv_append.
+    param_format: 0 binary16, 1 bfloat16 scale / bias (the same numbers on both sides of the boundary)."""
+    return build_device_cache(w, DEV, poison, extra_blocks, tokens, param_format)
 
 
-def host_cache(w, tokens=None):
+def host_cache(w, tokens=None, param_format=0):
     """The same logical cache on the host, quantized by the oracle."""
-    spec = oracle.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k)
+    spec = oracle.make_spec(w.num_layers, w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k,
+                            param_format=param_format)
     table, nb = w.block_table()
-    kpool = oracle.Pool(spec, w.k_dim, nb, fill=0x7E00)
-    vpool = None if w.v_aliases_k else oracle.Pool(spec, w.v_dim, nb, fill=0x7E00)
+    nan_bits = 0x7FC0 if param_format else 0x7E00
+    kpool = oracle.Pool(spec, w.k_dim, nb, fill=nan_bits)
+    vpool = None if w.v_aliases_k else oracle.Pool(spec, w.v_dim, nb, fill=nan_bits)
     table = np.where(table < 0, 0, table).astype(np.int32)
     lens = w.final_lens() if tokens is None else tokens
     for a, n in enumerate(lens):
@@ -33,12 +36,12 @@ def host_cache(w, tokens=None):
     return spec, kpool, vpool, table
 
 
-def oracle_unit(w, layer, agent, kvh, n, sm_scale=None, window=0, q=None, q_len=1):
+def oracle_unit(w, layer, agent, kvh, n, sm_scale=None, window=0, q=None, q_len=1, param_format=0):
     """Oracle attention of one (layer, agent, kv head) of a big workload, rebuilt alone on the host:
     returns float16 [q_len][n_rep][v_dim]."""
     R = w.n_rep
     alias = w.v_aliases_k
-    spec = oracle.make_spec(1, R, 1, w.k_dim, w.v_dim, alias)
+    spec = oracle.make_spec(1, R, 1, w.k_dim, w.v_dim, alias, param_format=param_format)
     nb = (n + 255) // 256
     kpool = oracle.Pool(spec, w.k_dim, max(nb, 1))
     vpool = None if alias else oracle.Pool(spec, w.v_dim, max(nb, 1))

@@ -51,6 +51,19 @@ def test_codec_argument_errors():
     assert l.q4kv_dequantize(None, None, None, 0, 128, None, None) == 0
 
 
+def test_parameter_format_argument_errors():
+    l = b.lib()
+    assert l.q4kv_quantize_fmt(None, 5, 64, 2, None, None, None, None) == -1 and "param_format" in _err()
+    assert l.q4kv_dequantize_fmt(None, None, None, 5, 64, -1, None, None) == -1 and "param_format" in _err()
+    assert l.q4kv_quantize_fmt(None, 0, 64, b.PARAMS_BF16, None, None, None, None) == 0
+    assert l.q4kv_quantize_fmt(None, 5, 100, b.PARAMS_BF16, None, None, None, None) == -2
+    bad = b.make_spec(2, 4, 2, 128, param_format=7)
+    assert b.lib().q4kv_cache_bytes(C.byref(bad), 10) == -1 and "param_format" in _err()
+    assert b.lib().q4kv_block_image_bytes(C.byref(bad), 1) == 0
+    good = b.make_spec(48, 16, 8, 256, param_format=b.PARAMS_BF16)
+    assert b.q4kv_cache_bytes(good, 4096) == 432 * 2 ** 20        # both parameter types are 16 bits wide
+
+
 def _pool(nb=4):
     return b._CPool(0x1000, 0x2000, 0x3000, nb)
 

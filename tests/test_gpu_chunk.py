@@ -19,9 +19,9 @@ def assert_close(got, want, what=""):
     assert not np.isnan(got.astype(np.float32)).any()
 
 
-def append_chunk_and_attend(w, window=0):
+def append_chunk_and_attend(w, window=0, param_format=0):
     """Cache of seq_lens tokens, then the library appends the chunk and attends; returns (gpu out, pools, table)."""
-    spec, kpool, vpool, table, table_d = gpu_cache(w, tokens=w.seq_lens)       # blocks for cache + chunk are reserved
+    spec, kpool, vpool, table, table_d = gpu_cache(w, tokens=w.seq_lens, param_format=param_format)   # blocks for cache + chunk are reserved
     C = w.q_len
     before = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
     for l in range(w.num_layers):
@@ -60,6 +60,20 @@ def test_chunk_matches_oracle_small(shape):
     ospec, okp, ovp, otable = host_cache(w)                  # cache + chunk, quantized by the oracle
     want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, w.final_lens(), w.sm_scale)
     assert_close(got, want, f"{shape}")
+
+
+@pytest.mark.parametrize("seed", [44, 45, 46, 47, 48, 49])
+def test_chunk_tolerance_does_not_depend_on_the_draw(seed):
+    """Short contexts with the generator's large key channels make a softmax that a few keys dominate: the case in
+    which a score error reaches the output undamped.  (Key rows rounded to binary16 before the product fail this for
+    about every second seed, by up to twice the tolerance.)"""
+    for shape in ((2, 4, 2, 128, (300, 0, 70), 70), (1, 8, 1, 64, (1000, 40), 33), (1, 2, 2, 256, (90, 5), 40)):
+        L, Hq, Hkv, D, lens, C = shape
+        w = synth.small(seed, L, Hq, Hkv, D, D, False, lens, q_len=C)
+        got, _ = append_chunk_and_attend(w)
+        ospec, okp, ovp, otable = host_cache(w)
+        want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, w.final_lens(), w.sm_scale)
+        assert_close(got, want, f"seed {seed} {shape}")
 
 
 def test_chunk_rows_equal_decode_steps_and_window():

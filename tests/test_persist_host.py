@@ -13,9 +13,10 @@ from paper_2603_04428_amd import persist
 
 
 class _Spec:
-    def __init__(self, L, Hq, Hkv, dk, dv, alias=0):
+    def __init__(self, L, Hq, Hkv, dk, dv, alias=0, param_format=0):
         self.num_layers, self.num_q_heads, self.num_kv_heads = L, Hq, Hkv
         self.k_dim, self.v_dim, self.v_aliases_k, self.block_tokens, self.group_size = dk, dv, alias, 256, 64
+        self.param_format = param_format
 
 
 def _random_image(spec, nb, seed=0):
@@ -46,6 +47,33 @@ def test_file_is_a_safetensors_file_with_the_appendix_names(tmp_path, shape):
     assert meta["seq_len"] == 600 and meta["num_blocks"] == nb and meta["agent_id"] == "a7"
     assert meta["spec"] == persist.spec_dict(spec)
     assert np.array_equal(np.asarray(image), img)
+
+
+def test_bfloat16_parameters_are_declared_as_such(tmp_path):
+    """Appendix "safetensors Q4 Format": scales and biases of one model family are bfloat16 tensors.  The format's own
+    torch reader must hand them back as bfloat16 with the image's bits."""
+    import torch
+    from safetensors.torch import load_file
+    spec = _Spec(2, 4, 2, 128, 64, 0, param_format=1)
+    nb = 2
+    img = _random_image(spec, nb, seed=3)
+    path = os.path.join(tmp_path, "agent_bf16.safetensors")
+    persist.save_agent(path, spec, img, nb, 300)
+    tensors = load_file(path)
+    for name, dtype, shp, b, e in persist.tensor_table(spec, nb):
+        t = tensors[name]
+        assert list(t.shape) == shp
+        if name.endswith("weights"):
+            assert dtype == "U32"
+            continue
+        assert dtype == "BF16" and t.dtype == torch.bfloat16
+        assert np.array_equal(t.view(torch.int16).numpy().reshape(-1).view(np.uint8), img[b:e]), name
+    meta, image = persist.open_agent(path)
+    assert meta["spec"]["param_format"] == 1 and np.array_equal(np.asarray(image), img)
+    # same sizes as the binary16 form
+    assert persist.image_bytes(spec, nb) == persist.image_bytes(_Spec(2, 4, 2, 128, 64), nb)
+    with pytest.raises(ValueError):
+        persist.image_bytes(_Spec(2, 4, 2, 128, 64, 0, param_format=3), nb)
 
 
 def test_image_size_is_the_papers_byte_count():
