@@ -139,8 +139,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
 
 // Paged form (Sec. 3.4 update_and_fetch, first half): source rows [layer in call][agent][chunk token][kv head],
 // destination the agent's blocks.  Layer and agent come from the launch grid, so that a lane's index arithmetic is
-// two 32-bit divisions (by the groups per row and by the heads) instead of a chain of 64-bit ones; a token outside
-// the table or a block id outside the pool is skipped.
+// two 32-bit divisions (by the groups per row and by the chunk length) instead of a chain of 64-bit ones; a token
+// outside the table or a block id outside the pool is skipped.
 struct AppendParams {
     const int32_t *block_table;
     const int32_t *seq_len_before;
@@ -163,11 +163,14 @@ __global__ __launch_bounds__(kThreads) void append_kernel(const uint16_t *__rest
     const int generation = linear / max(1u, gridDim.x * gridDim.y * gridDim.z / Q4KV_CODEC_WG_PER_CU);
     for (uint32_t gi = blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); gi < per_unit; gi += gridDim.x * (kThreads / 8)) {
         rotate_wave_priority(generation);
-        const uint4 raw = *reinterpret_cast<const uint4 *>(x + (src0 + gi) * kGroup + sub * 8);
+        // groups are walked in the order of the pool (head, then chunk token, then group): consecutive lanes then
+        // write consecutive rows of one head's plane of a block, and read whole 2 dim-byte source rows
+        const uint32_t row = gi / (uint32_t)p.groups_per_row, g = gi - row * p.groups_per_row;
+        const uint32_t h = row / (uint32_t)p.chunk_len, c = row - h * p.chunk_len;
+        const uint32_t src = (c * p.heads + h) * p.groups_per_row + g;
+        const uint4 raw = *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8);
         uint16_t sb, bb;
         const uint32_t word = quantize_octet<BF>(raw, sub, &sb, &bb);
-        const uint32_t row = gi / (uint32_t)p.groups_per_row, g = gi - row * p.groups_per_row;
-        const uint32_t c = row / (uint32_t)p.heads, h = row - c * p.heads;
         const int t = n0 + (int)c;
         const int bi = t / kBlockTokens;
         if (t < 0 || bi >= p.max_blocks) continue;
@@ -256,9 +259,10 @@ hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &pool, int dim, 
     if (layers <= 0 || num_agents <= 0 || per_unit == 0) return hipSuccess;
     if (per_unit > 0x7fffffffLL || num_agents > 65535 || layers > 65535) return hipErrorInvalidValue;
     AppendParams p{block_table, seq_len_before, max_blocks, chunk_len, spec.num_kv_heads, layer_begin, pool.num_blocks, G};
-    // workgroups per (layer, agent): enough for the chunk, and about 8 per compute unit over the whole launch
+    // workgroups per (layer, agent): enough for the chunk, and at most 8 per compute unit over the whole launch
+    // (rounded down: a launch of 1.2 rounds takes as long as one of 2)
     int64_t gx = (per_unit + kThreads / 8 - 1) / (kThreads / 8);
-    const int64_t cap = (256LL * Q4KV_CODEC_WG_PER_CU + (int64_t)layers * num_agents - 1) / ((int64_t)layers * num_agents);
+    const int64_t cap = 256LL * Q4KV_CODEC_WG_PER_CU / ((int64_t)layers * num_agents);
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
     const dim3 grid((unsigned)gx, (unsigned)num_agents, (unsigned)layers);
