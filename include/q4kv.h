@@ -50,7 +50,8 @@ typedef enum {
     Q4KV_ESHAPE = -2,     /* unsupported dims: dim % 64, q_heads % kv_heads, head widths, group/block size */
     Q4KV_ERANGE = -3,     /* max_seq_len exceeds what the block table can address */
     Q4KV_EWORKSPACE = -4, /* workspace too small or missing */
-    Q4KV_EHIP = -5        /* the HIP runtime refused a launch */
+    Q4KV_EHIP = -5,       /* the HIP runtime refused a launch */
+    Q4KV_ENOSPACE = -6    /* the block pool has too few free blocks (nothing was changed) */
 } q4kv_status;
 
 /* Type of the stored scale and bias values (both 16 bits wide, so layouts and byte counts do not change). */
@@ -193,6 +194,36 @@ int q4kv_export_blocks(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_poo
                        int32_t num_blocks, void *image, size_t image_bytes, void *hip_stream);
 int q4kv_import_blocks(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const int32_t *block_ids,
                        int32_t num_blocks, const void *image, size_t image_bytes, void *hip_stream);
+
+/* Sec. 3.1 "Block Pool with Per-Agent Isolation", host side: which 256-token block of the device pools belongs to
+ * which agent.  Pure bookkeeping in HOST memory (no device call): a block id is either free or in exactly one agent's
+ * list, so two agents can never share or overwrite a block (the paper's namespace isolation); the list order is the
+ * token order, i.e. a row of the block table the attention calls read.  Eviction is the caller's sequence
+ * lru_victim -> q4kv_export_blocks -> (file) -> release; a restore is reserve -> q4kv_import_blocks into whatever blocks
+ * were free.  Agent ids are caller-chosen non-negative numbers.  Every call locks the pool (thread-safe).
+ *   create        a pool over block ids 0 .. num_blocks-1, all free; NULL on a bad argument or out of memory
+ *   reserve       make the agent own ceil(tokens/256) blocks: blocks it has stay (in place and order), missing ones
+ *                 come from the free list, lowest id first; an unknown agent is created; the agent becomes the most
+ *                 recently used.  Never shrinks.  Returns the number of blocks owned, Q4KV_ENOSPACE when the free
+ *                 list is too short (nothing changed), Q4KV_EINVAL on a negative id or token count
+ *   release       free all blocks of the agent and forget it; returns the number freed, Q4KV_EINVAL if unknown
+ *   blocks        copy the agent's block ids in token order into ids[0 .. cap) (host); returns how many it owns
+ *   table_row     the same as a block-table row: ids, then `fill` up to max_blocks; Q4KV_ERANGE if it owns more
+ *   touch         mark the agent most recently used;  pin(1): never a victim while it is in a running batch
+ *   lru_victim    the unpinned agent with at least one block that was used least recently, or -1
+ *   free_blocks   length of the free list;  owner: the agent id that owns a block, or -1 */
+typedef struct q4kv_block_pool q4kv_block_pool;
+q4kv_block_pool *q4kv_block_pool_create(int32_t num_blocks);
+void q4kv_block_pool_destroy(q4kv_block_pool *pool);
+int32_t q4kv_block_pool_reserve(q4kv_block_pool *pool, int64_t agent_id, int64_t tokens);
+int32_t q4kv_block_pool_release(q4kv_block_pool *pool, int64_t agent_id);
+int32_t q4kv_block_pool_blocks(q4kv_block_pool *pool, int64_t agent_id, int32_t *ids, int32_t cap);
+int32_t q4kv_block_pool_table_row(q4kv_block_pool *pool, int64_t agent_id, int32_t *row, int32_t max_blocks, int32_t fill);
+int32_t q4kv_block_pool_touch(q4kv_block_pool *pool, int64_t agent_id);
+int32_t q4kv_block_pool_pin(q4kv_block_pool *pool, int64_t agent_id, int32_t pinned);
+int64_t q4kv_block_pool_lru_victim(q4kv_block_pool *pool);
+int32_t q4kv_block_pool_free_blocks(q4kv_block_pool *pool);
+int64_t q4kv_block_pool_owner(q4kv_block_pool *pool, int32_t block_id);
 
 /* Measurement helper, no part of the method: a kernel that only reads.  Reads the first
  * floor(bytes / 16384) * 16384 bytes of the device buffer `src` (16-byte aligned) exactly once, in the launch

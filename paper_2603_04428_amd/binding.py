@@ -14,6 +14,9 @@ LIB_PATH = os.path.join(HERE, "libq4kv.so")
 
 EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_quantize_fmt", "q4kv_dequantize_fmt", "q4kv_append", "q4kv_batched_attention",
            "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_block_image_bytes", "q4kv_export_blocks", "q4kv_import_blocks", "q4kv_read_probe",
+           "q4kv_block_pool_create", "q4kv_block_pool_destroy", "q4kv_block_pool_reserve", "q4kv_block_pool_release",
+           "q4kv_block_pool_blocks", "q4kv_block_pool_table_row", "q4kv_block_pool_touch", "q4kv_block_pool_pin",
+           "q4kv_block_pool_lru_victim", "q4kv_block_pool_free_blocks", "q4kv_block_pool_owner",
            "q4kv_last_error",
            "q4kv_version"]
 
@@ -73,6 +76,21 @@ def lib():
         l.q4kv_block_image_bytes.argtypes = [C.POINTER(Spec), i32]
         for f in (l.q4kv_export_blocks, l.q4kv_import_blocks):
             f.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, i32, vp, C.c_size_t, vp]
+        l.q4kv_block_pool_create.restype = vp
+        l.q4kv_block_pool_create.argtypes = [i32]
+        l.q4kv_block_pool_destroy.restype = None
+        l.q4kv_block_pool_destroy.argtypes = [vp]
+        l.q4kv_block_pool_reserve.argtypes = [vp, i64, i64]
+        l.q4kv_block_pool_release.argtypes = [vp, i64]
+        l.q4kv_block_pool_blocks.argtypes = [vp, i64, C.POINTER(i32), i32]
+        l.q4kv_block_pool_table_row.argtypes = [vp, i64, C.POINTER(i32), i32, i32]
+        l.q4kv_block_pool_touch.argtypes = [vp, i64]
+        l.q4kv_block_pool_pin.argtypes = [vp, i64, i32]
+        l.q4kv_block_pool_lru_victim.restype = i64
+        l.q4kv_block_pool_lru_victim.argtypes = [vp]
+        l.q4kv_block_pool_free_blocks.argtypes = [vp]
+        l.q4kv_block_pool_owner.restype = i64
+        l.q4kv_block_pool_owner.argtypes = [vp, i32]
         l.q4kv_last_error.restype = C.c_char_p
         l.q4kv_version.restype = C.c_int
         _lib = l
@@ -120,6 +138,63 @@ class Pool:
 
     def c(self):
         return _CPool(self.codes.data_ptr(), self.scale.data_ptr(), self.bias.data_ptr(), self.num_blocks)
+
+
+class BlockPool:
+    """q4kv_block_pool: host-side bookkeeping of block ownership (Sec. 3.1).  Marshalling only."""
+    ENOSPACE = -6
+
+    def __init__(self, num_blocks):
+        self._h = lib().q4kv_block_pool_create(num_blocks)
+        if not self._h:
+            raise ValueError("q4kv_block_pool_create failed")
+
+    def close(self):
+        if self._h:
+            lib().q4kv_block_pool_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    @staticmethod
+    def _ok(rc):
+        if rc < 0:
+            raise Q4KVError(rc, "block pool: " + {-1: "bad argument or unknown agent", -3: "more blocks than the row holds",
+                                                  -6: "not enough free blocks"}.get(rc, "error"))
+        return rc
+
+    def reserve(self, agent_id, tokens):
+        return self._ok(lib().q4kv_block_pool_reserve(self._h, agent_id, tokens))
+
+    def release(self, agent_id):
+        return self._ok(lib().q4kv_block_pool_release(self._h, agent_id))
+
+    def blocks(self, agent_id):
+        n = self._ok(lib().q4kv_block_pool_blocks(self._h, agent_id, None, 0))
+        ids = (C.c_int32 * max(n, 1))()
+        self._ok(lib().q4kv_block_pool_blocks(self._h, agent_id, ids, n))
+        return list(ids[:n])
+
+    def table_row(self, agent_id, max_blocks, fill=-1):
+        row = (C.c_int32 * max_blocks)()
+        self._ok(lib().q4kv_block_pool_table_row(self._h, agent_id, row, max_blocks, fill))
+        return list(row)
+
+    def touch(self, agent_id):
+        self._ok(lib().q4kv_block_pool_touch(self._h, agent_id))
+
+    def pin(self, agent_id, pinned=True):
+        self._ok(lib().q4kv_block_pool_pin(self._h, agent_id, 1 if pinned else 0))
+
+    def lru_victim(self):
+        return lib().q4kv_block_pool_lru_victim(self._h)
+
+    def free_blocks(self):
+        return lib().q4kv_block_pool_free_blocks(self._h)
+
+    def owner(self, block_id):
+        return lib().q4kv_block_pool_owner(self._h, block_id)
 
 
 def q4kv_version():

@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libq4kv.so")
-SOURCES = ["api.hip", "codec.hip", "decode_attention.hip", "chunk_attention.hip", "mla_decode.hip", "read_probe.hip", "persist.hip"]
+SOURCES = ["api.hip", "codec.hip", "decode_attention.hip", "chunk_attention.hip", "mla_decode.hip", "read_probe.hip", "persist.hip", "block_pool.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # No fast-math anywhere: the quantizer needs IEEE binary32 division and rounding.

@@ -96,3 +96,86 @@ def test_export_into_pinned_host_memory_and_skipped_ids():
     with pytest.raises(b.Q4KVError):
         b.q4kv_export_blocks(spec, kpool, vpool, ids, dev_image[:-16])          # image too small
     assert b.q4kv_export_blocks(spec, kpool, vpool, ids[:0]).numel() == 0         # nothing to do
+
+
+def test_agents_paged_through_a_small_pool(tmp_path):
+    """Sec. 3.1 / Sec. 1 (caches paged between memory and disk): five agents take turns on a device pool that holds
+    three of them.  The block pool names the least recently used agent, its blocks leave through a file and come back
+    into whatever blocks are free; every agent's decode output keeps the bits it had when all of its cache was first
+    resident."""
+    L, Hq, Hkv, D = 2, 4, 2, 64
+    lens = (600, 300, 520, 257, 700)                       # 3, 2, 3, 2, 3 blocks
+    w = synth.small(63, L, Hq, Hkv, D, D, False, lens)
+    NB, MB = 8, 3
+    spec = b.make_spec(L, Hq, Hkv, D)
+    kpool, vpool = b.Pool(spec, D, NB, DEV, True), b.Pool(spec, D, NB, DEV, True)
+    book = b.BlockPool(NB)
+    on_disk = {}
+
+    def make_room(agent, tokens):
+        while True:
+            try:
+                return book.reserve(agent, tokens)
+            except b.Q4KVError as e:
+                assert e.code == b.BlockPool.ENOSPACE
+            victim = book.lru_victim()
+            assert victim >= 0 and victim != agent
+            ids = torch.tensor(book.blocks(victim), dtype=torch.int32, device=DEV)
+            image = b.q4kv_export_blocks(spec, kpool, vpool, ids)
+            torch.cuda.synchronize()
+            path = os.path.join(tmp_path, f"agent{victim}.safetensors")
+            persist.save_agent(path, spec, image.cpu(), ids.numel(), lens[victim])
+            on_disk[victim] = path
+            # what the victim leaves behind must not matter to anyone: poison it
+            for pool in (kpool, vpool):
+                pool.codes[:, ids.long()] = -1
+                pool.scale[:, ids.long()] = 0x7E00
+                pool.bias[:, ids.long()] = 0x7E00
+            book.release(victim)
+
+    def decode(agent):
+        row = torch.tensor([book.table_row(agent, MB, fill=0)], dtype=torch.int32, device=DEV)
+        sl = torch.tensor([lens[agent]], dtype=torch.int32, device=DEV)
+        q = w.q_all(DEV)[:, agent:agent + 1].contiguous()
+        out = b.q4kv_batched_attention(spec, kpool, vpool, q, row, sl, lens[agent], w.sm_scale)
+        torch.cuda.synchronize()
+        return out.cpu().numpy().view(np.uint16)
+
+    first = {}
+    order = [0, 1, 2, 3, 0, 4, 1, 2, 0, 3, 4]
+    evictions = 0
+    for agent in order:
+        if agent in first and agent not in on_disk:
+            book.touch(agent)                                # still resident
+        elif agent in on_disk:                               # restore into whatever blocks are free now
+            meta, img = persist.open_agent(on_disk.pop(agent))
+            make_room(agent, meta["seq_len"])
+            evictions += 1
+            pinned = torch.empty(img.size, dtype=torch.uint8, pin_memory=True)
+            persist.load_agent_into(os.path.join(tmp_path, f"agent{agent}.safetensors"), pinned)
+            ids = torch.tensor(book.blocks(agent), dtype=torch.int32, device=DEV)
+            b.q4kv_import_blocks(spec, kpool, vpool, ids, pinned)
+        else:                                                # first arrival: prefill its cache through q4kv_append
+            make_room(agent, lens[agent])
+            row = torch.tensor([book.table_row(agent, MB, fill=0)], dtype=torch.int32, device=DEV)
+            zero = torch.zeros(1, dtype=torch.int32, device=DEV)
+            for l in range(L):
+                b.q4kv_append(spec, kpool, vpool, w.k_rows(l, agent, 0, lens[agent], DEV)[None, None].contiguous(),
+                              w.v_rows(l, agent, 0, lens[agent], DEV)[None, None].contiguous(), row, zero, l, l + 1)
+        got = decode(agent)
+        if agent in first:
+            assert np.array_equal(got, first[agent]), f"agent {agent} changed after paging"
+        else:
+            first[agent] = got
+        # isolation: every block has at most one owner and the resident agents' lists are disjoint
+        owners = [book.owner(i) for i in range(NB)]
+        for a in set(o for o in owners if o >= 0):
+            assert sorted(i for i, o in enumerate(owners) if o == a) == sorted(book.blocks(a))
+    assert evictions >= 3 and len(first) == 5
+    # and the first results are the oracle's
+    ospec, okp, ovp, otable = host_cache(w)
+    want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, list(lens), w.sm_scale)
+    for agent in range(5):
+        ok = np.abs(first[agent].view(np.float16).astype(np.float64)[:, 0] - want[:, agent].astype(np.float64)) <= \
+            2e-3 + 2e-3 * np.abs(want[:, agent].astype(np.float64))
+        assert ok.all()
