@@ -9,11 +9,13 @@
 //  * A workgroup (4 waves) owns 128 query rows of one (layer, agent, KV head): 128/n_rep consecutive chunk
 //    positions times the n_rep query heads of the group.  Each wave owns 32 rows.
 //  * KV tiles of 64 tokens are fetched as Q4 (codes + scale/bias, coalesced 16-byte loads, prefetched one
-//    tile ahead into registers), unpacked ONCE per workgroup into LDS as binary16 and reused by all 128
-//    rows, both row-major with the dims inside a word in the order the nibble masks deliver them
-//    (0,4,1,5,2,6,3,7): the query operand uses the same order for K, the output store undoes it for V_hat.
-//  * K stays factored, S^T = sum_g s[t,g] (C_g Q_g^T) + b Qsum^T: the K rows in LDS are the bare codes (binary16
-//    subnormals c 2^-24, odd nibbles 16 c 2^-24 against q/16), the matrix core multiplies them exactly, and the
+//    tile ahead into registers) and staged ONCE per workgroup in LDS for all 128 rows, row-major: V_hat
+//    dequantized to binary16, K as the packed code words themselves (a quarter of the LDS traffic of binary16
+//    keys; a lane's A operand of a matrix instruction is exactly one word).  The dims inside a word appear in the
+//    order the nibble masks deliver them (0,4,1,5,2,6,3,7): the query operand uses the same order for K, the
+//    output store undoes it for V_hat.
+//  * K stays factored, S^T = sum_g s[t,g] (C_g Q_g^T) + b Qsum^T: a code word masked in place is eight binary16
+//    subnormals (c 2^-24, odd nibbles 16 c 2^-24 against q/16), the matrix core multiplies them exactly, and the
 //    per-(token, group) scale meets the binary32 result of each group; the bias term is one more matrix
 //    instruction per 16 tokens whose contraction runs over the groups (group sums of q split into a binary16 high
 //    and low part).  A K row dequantized to binary16 would carry an absolute rounding error of 2^-11 |K_hat|,
@@ -119,9 +121,10 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     constexpr int kWaves = kRowsWG / kRowsWave;
     constexpr int kThreads = kWaves * kWave;
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
-    // halves per row of the unpacked tiles in LDS.  K rows (codes) are read 16 bytes per lane by 16 rows at a time
-    // (pitch = 16 bytes mod 256), V_hat rows 8 bytes per lane by 4 rows x 32 bytes at a time (pitch = 32 mod 256)
-    constexpr int KPITCH = DK + 8;
+    // row pitches of the tiles in LDS.  K rows (32-bit code words) are read one word per lane by 16 rows x 4 words at
+    // a time: a pitch of 4 x odd words spreads those over all 64 banks.  V_hat rows (halves) are read 8 bytes per
+    // lane by 4 rows x 32 bytes at a time (pitch = 32 bytes mod 256).
+    constexpr int KPITCH = DK / 8 + 4;
     constexpr int VPITCH = DV + 16;
     constexpr int QPOS = kRowsWG / NREP; // chunk positions per workgroup
     constexpr int KSTEPS = DK / 32;    // k-steps of the QK contraction
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     typedef Stage<DV, kThreads> SV;    // ... and of its V rows
 
     // two tiles each: while the waves multiply against one, they unpack the next into the other
-    __shared__ __attribute__((aligned(16))) half_t k_lds[2][kTile * KPITCH]; // codes (c or 16 c) * 2^-24
+    __shared__ __attribute__((aligned(16))) uint32_t k_lds[2][kTile * KPITCH]; // K code words as they are in the pool
     __shared__ __attribute__((aligned(16))) half_t v_lds[2][kTile * VPITCH]; // V_hat
     __shared__ __attribute__((aligned(16))) half_t ks_lds[2][GK * kTile];    // K scale [group][token]
     // K bias [token][8]: groups 0..3 (zero padded) twice, against the high and the low parts of the group sums of q
@@ -306,9 +309,23 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     // K rows keep their codes: the nibbles masked in place are binary16 subnormals c 2^-24 (dims 0, 4, 2, 6 of a
     // word) and 16 c 2^-24 (dims 1, 5, 3, 7); the row's scale and bias go to LDS beside them, written by the thread
     // that holds the first word of the group
-    auto store_codes = [&](half_t *dst, uint32_t raw, bool ok) {
-        const uint32_t word = ok ? raw : 0u, w8 = word >> 8;
-        *reinterpret_cast<uint4 *>(dst) = make_uint4(word & 0x000F000Fu, word & 0x00F000F0u, w8 & 0x000F000Fu, w8 & 0x00F000F0u);
+    // the staged K words of this thread go to LDS as they are, 16 (or 8) bytes per store: 16 consecutive lanes
+    // are 16 consecutive tokens, whose rows start 4 x odd banks apart
+    auto store_codes = [&](uint32_t *dst, const uint32_t (&raw)[SK::WPT], bool ok) {
+        if constexpr (SK::WPT % 4 == 0) {
+#pragma unroll
+            for (int w = 0; w < SK::WPT; w += 4)
+                *reinterpret_cast<uint4 *>(dst + w) =
+                    ok ? make_uint4(raw[w], raw[w + 1], raw[w + 2], raw[w + 3]) : make_uint4(0u, 0u, 0u, 0u);
+        } else {
+            *reinterpret_cast<uint2 *>(dst) = ok ? make_uint2(raw[0], raw[1]) : make_uint2(0u, 0u);
+        }
+    };
+    // a code word as the A operand of a matrix instruction: the nibbles masked in place are binary16 subnormals
+    // c 2^-24 (dims 0, 4, 2, 6 of the word) and 16 c 2^-24 (dims 1, 5, 3, 7)
+    auto code_operand = [&](uint32_t w) {
+        const uint32_t w8 = w >> 8;
+        return __builtin_bit_cast(half8_t, make_uint4(w & 0x000F000Fu, w & 0x00F000F0u, w8 & 0x000F000Fu, w8 & 0x00F000F0u));
     };
     const bool k_params_writer = k_on && (k_w0 * 8) % kGroup == 0;
     auto store_k_params = [&](int b, const RowDequant &r) {
@@ -323,7 +340,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     // rows of an unreachable block and rows at or past t_end (never visible, possibly never written) become zeros,
     // so that no stale bit pattern can reach an accumulator
     auto row_ok = [&](int t0, int tok, bool ok_tile) { return ok_tile && (t0 + tok < t_end); };
-    const int k_dst = k_tok * KPITCH + k_w0 * 8, v_dst = v_tok * VPITCH + v_w0 * 8;
+    const int k_dst = k_tok * KPITCH + k_w0, v_dst = v_tok * VPITCH + v_w0 * 8;
 
     // transposing read of V_hat: this lane's address inside a tile for (16-dim tile 0, 32-token block 0, first
     // half): token 4 kb + (lane % 16) / 4, dims 4 (lane % 4) ..
@@ -338,10 +355,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         load_tile(t_begin, ok_next);
         const RowDequant kr = row_params(ksb, row_ok(t_begin, k_tok, ok_next));
         const RowDequant vr = row_params(vsb, row_ok(t_begin, v_tok, ok_next));
-        if (k_on) {
-#pragma unroll
-            for (int w = 0; w < SK::WPT; ++w) store_codes(k_lds[0] + k_dst + 8 * w, kraw[w], kr.ok);
-        }
+        if (k_on) store_codes(k_lds[0] + k_dst, kraw, kr.ok);
         if (k_params_writer) store_k_params(0, kr);
         if (v_on) {
 #pragma unroll
@@ -352,7 +366,8 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
     }
     __syncthreads();
     for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
-        const half_t *k_cur = k_lds[buf], *v_cur = v_lds[buf];
+        const uint32_t *k_cur = k_lds[buf];
+        const half_t *v_cur = v_lds[buf];
 
         // ---- S^T = sum_g s_g (C_g Q_g^T) + b Qsum^T : [64 tokens][16 QT query rows] per wave, binary32, in units of
         // 2^-24.  An item is one (group, 16-token tile): two matrix instructions per query tile over the group's 64
@@ -379,9 +394,9 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
         constexpr int TPI = 1;
         constexpr int kItemsPerGroup = kTile / 16 / TPI;
         constexpr int kItems = GK * kItemsPerGroup;
-        constexpr int kAhead = TPI == 2 ? 1 : 2; // items the operand reads run ahead (the ring must fit the registers)
+        constexpr int kAhead = 1; // items the operand reads run ahead (1: 757, 2: 750, 3: 750 TFLOP/s at D = 256)
         struct ItemIn {
-            half8_t a0[TPI], a1[TPI]; // codes of token 16 tt + qn, dims 64 g + 8 kb .. and 64 g + 32 + 8 kb ..
+            uint32_t a0[TPI], a1[TPI]; // code words of token 16 tt + qn: dims 64 g + 8 kb .. and 64 g + 32 + 8 kb ..
             uint2 s4[TPI];            // scales of tokens 16 tt + 4 kb .. + 3, group g
         };
         auto load_item = [&](int it) {
@@ -389,9 +404,9 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
             ItemIn in;
 #pragma unroll
             for (int j = 0; j < TPI; ++j) {
-                const half_t *row = k_cur + ((tt0 + j) * 16 + qn) * KPITCH + 64 * g + 8 * kb;
-                in.a0[j] = *reinterpret_cast<const half8_t *>(row);
-                in.a1[j] = *reinterpret_cast<const half8_t *>(row + 32);
+                const uint32_t *row = k_cur + ((tt0 + j) * 16 + qn) * KPITCH + 8 * g + kb;
+                in.a0[j] = row[0];
+                in.a1[j] = row[4];
                 in.s4[j] = *reinterpret_cast<const uint2 *>(ks_cur + g * kTile + (tt0 + j) * 16 + 4 * kb);
             }
             return in;
@@ -411,13 +426,13 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
                 for (int j = 0; j < TPI; ++j)
 #pragma unroll
                     for (int qi = 0; qi < QT; ++qi)
-                        dq[it & 1][j][qi] = __builtin_amdgcn_mfma_f32_16x16x32_f16(in.a0[j], qop[qi][2 * g], zero4, 0, 0, 0);
+                        dq[it & 1][j][qi] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(in.a0[j]), qop[qi][2 * g], zero4, 0, 0, 0);
 #pragma unroll
                 for (int j = 0; j < TPI; ++j)
 #pragma unroll
                     for (int qi = 0; qi < QT; ++qi)
                         dq[it & 1][j][qi] =
-                            __builtin_amdgcn_mfma_f32_16x16x32_f16(in.a1[j], qop[qi][2 * g + 1], dq[it & 1][j][qi], 0, 0, 0);
+                            __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(in.a1[j]), qop[qi][2 * g + 1], dq[it & 1][j][qi], 0, 0, 0);
             }
             if (it > 0) { // the item before: scores += scale * product
                 const int g = (it - 1) / kItemsPerGroup, tt0 = ((it - 1) % kItemsPerGroup) * TPI;
@@ -441,10 +456,7 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attentio
 #pragma unroll
                 for (int j = 0; j < TPI; ++j) s_prev[j] = item[it % (kAhead + 1)].s4[j];
             }
-            // words of the K row spread evenly over the items
-#pragma unroll
-            for (int w = 0; w < SK::WPT; ++w)
-                if (w * kItems / SK::WPT == it && k_on) store_codes(k_lds[buf ^ 1] + k_dst + 8 * w, kraw[w], kr.ok);
+            if (it == 0 && k_on) store_codes(k_lds[buf ^ 1] + k_dst, kraw, kr.ok); // the next tile's K words
             if (it == 1 && k_params_writer) store_k_params(buf ^ 1, kr);
             __builtin_amdgcn_sched_barrier(0);
         }
