@@ -25,9 +25,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes per launch of each workload's dominant kernel, read + written, from the rocprofv3 --pmc runs whose
 # summaries are under profiles/ (FETCH_SIZE and WRITE_SIZE scaled by what a plain copy of known size reads)
 MEASURED_TRAFFIC = {
-    "decode": 4756695040 + 12307456,
+    "decode": 4754976768 + 12307456,
     "dsv2lite_mla_latent_5agents_27layers_32k_decode": 1444208640 + 53625856,
-    "dsv2lite_mla_per_head_5agents_27layers_8k_decode": 3187363840,   # reads only (no WRITE_SIZE run)
+    "dsv2lite_mla_per_head_5agents_27layers_8k_decode": 3187380224,   # reads only (no WRITE_SIZE run)
 }
 
 
@@ -187,13 +187,13 @@ def bench_latent(args, torch, b, synth, build_device_cache):
     """Decode over the shared-latent cache (DeepSeek-V2-Lite-shaped: 5 agents x 32,768 tokens x 27 layers, one
     576-wide Q4 row per token read by 16 heads), all layers in one call; reported as HBM GB/s."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.config(3),
-                             "mla_decode_kernel<9,8> (+ combine_kernel in the same call)")
+                             "mla_decode_kernel<9,8,false> (+ combine_kernel in the same call)")
 
 
 def bench_per_head(args, torch, b, synth, build_device_cache):
     """Decode over the decompressed per-head form of the same model's cache (keys 192, values 128, 16 KV heads)."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.per_head_mla_config(),
-                             "decode_attention_kernel<192,128,1> (+ combine_kernel in the same call)")
+                             "decode_attention_kernel<192,128,1,false> (+ combine_kernel in the same call)")
 
 
 def bench_restore(args, torch, b, synth, build_device_cache):
@@ -598,7 +598,7 @@ def main():
                      "traffic": MEASURED_TRAFFIC["decode"] if args.layer_windows == "global" and not args.split_tokens
                      else None,
                      "traffic_source": "profiles/decode_attention_gemma10_ragged.md (FETCH_SIZE + WRITE_SIZE, scaled)",
-                     "kernel": "decode_attention_kernel<256,256,2> (+ combine_kernel in the same call)"},
+                     "kernel": "decode_attention_kernel<256,256,2,false> (+ combine_kernel in the same call)"},
     }
     if not args.skip_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, [0, w.num_layers // 3, 2 * w.num_layers // 3, w.num_layers - 1])
