@@ -31,12 +31,29 @@ MEASURED_TRAFFIC = {
 }
 
 
+PARAM_FORMAT = 0      # q4kv_param_format of the run (--param-format): 0 binary16, 1 bfloat16 scale / bias
+
+
+def emit(res):
+    """Print the result line; a bfloat16-parameter run says so in dtype, config and kernel name."""
+    if PARAM_FORMAT == 1:
+        res["dtype"] = res["dtype"].replace("f16 scale/bias", "bf16 scale/bias")
+        res["config"]["param_format"] = "bf16"
+        roof = res.get("roofline") or {}
+        if "kernel" in roof:
+            roof["kernel"] = roof["kernel"].replace(",false>", ",true>")
+        if roof.get("traffic") is not None:
+            roof["traffic"] = None          # the counter runs under profiles/ were made with binary16 parameters
+    print(json.dumps(res))
+
+
 def cpu_baseline(w, layers):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: all agents and heads of a few
     layers.  Returns the JSON object; GB/s counts the same algorithmic Q4 bytes as the GPU figure."""
     import numpy as np
     import oracle
-    spec = oracle.make_spec(len(layers), w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k)
+    spec = oracle.make_spec(len(layers), w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k,
+                            param_format=PARAM_FORMAT)
     table, nb = w.block_table()
     table = np.where(table < 0, 0, table).astype(np.int32)
     kpool = oracle.Pool(spec, w.k_dim, nb)
@@ -121,7 +138,7 @@ def bench_append(args, torch, b, synth, build_device_cache):
                      "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
                      "kernel": "chunk_attention_kernel<256,256,2,1,false>"},
     }
-    print(json.dumps(res))
+    emit(res)
 
 
 def percentile(xs, q):
@@ -300,7 +317,7 @@ def bench_restore(args, torch, b, synth, build_device_cache):
                      "frac": copy_gbps / HBM_PEAK_GBPS, "traffic": None,
                      "kernel": "image_copy_kernel<true> (pool -> device image; bytes read + written)"},
     }
-    print(json.dumps(res))
+    emit(res)
 
 
 def bench_mixed_step(args, torch, b, synth, build_device_cache):
@@ -389,7 +406,7 @@ def bench_mixed_step(args, torch, b, synth, build_device_cache):
         "decode_steps_per_chunk": n, "serial_ms_for_the_same_work": serial_ms,
         "roofline": None,
     }
-    print(json.dumps(res))
+    emit(res)
 
 
 def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
@@ -444,7 +461,7 @@ def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
                      "traffic_source": "profiles/ (FETCH_SIZE + WRITE_SIZE of the kernel, scaled)",
                      "kernel": kernel_name},
     }
-    print(json.dumps(res))
+    emit(res)
 
 
 def main():
@@ -468,6 +485,9 @@ def main():
                     help="decode workload: also time the same step issued as one call per layer, recorded into a graph "
                          "and replayed (adds 'per_layer_graph_ms'; leave it out of profiler runs, whose per-kernel "
                          "averages it would mix with the single-launch figures)")
+    ap.add_argument("--param-format", choices=["f16", "bf16"], default="f16",
+                    help="type of the stored scale and bias (decode, append, latent, per-head workloads); f16 is what "
+                         "every benchmark configuration specifies")
     ap.add_argument("--layer-windows", choices=["global", "mixed"], default="global",
                     help="decode workload only.  global (default, the headline configuration): every layer attends "
                          "to the whole cache; mixed: five layers with a 1,024-token sliding window, then one global "
@@ -482,6 +502,11 @@ def main():
     from paper_2603_04428_amd import synth
     from paper_2603_04428_amd.workload import build_device_cache
 
+    global PARAM_FORMAT
+    if args.param_format == "bf16":
+        import functools
+        PARAM_FORMAT = b.PARAMS_BF16
+        build_device_cache = functools.partial(build_device_cache, param_format=b.PARAMS_BF16)
     dev = "cuda"
     if args.workload == "append":
         return bench_append(args, torch, b, synth, build_device_cache)
@@ -506,7 +531,7 @@ def main():
     # one fresh 4,096-token fp16 agent cache [layers][K,V][tokens][kv_heads][dim] and its Q4 form
     fresh = torch.stack([torch.stack([w.k_rows(l, 0, 100000, 104096, dev), w.v_rows(l, 0, 100000, 104096, dev)])
                          for l in range(w.num_layers)])
-    codes, scale, bias = b.q4kv_quantize(fresh)
+    codes, scale, bias = b.q4kv_quantize(fresh, param_format=PARAM_FORMAT)
     restored = torch.empty_like(fresh)
     quant_bytes = fresh.numel() * 2 + codes.numel() * 4 + scale.numel() * 4
     if args.layer_windows == "mixed":
@@ -524,10 +549,10 @@ def main():
     def step(ev=None):
         if ev:
             ev[0].record()
-        b.q4kv_dequantize(codes, scale, bias, restored)
+        b.q4kv_dequantize(codes, scale, bias, restored, param_format=PARAM_FORMAT)
         if ev:
             ev[1].record()
-        b.q4kv_quantize(fresh, codes, scale, bias)
+        b.q4kv_quantize(fresh, codes, scale, bias, param_format=PARAM_FORMAT)
         if ev:
             ev[2].record()
         b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, seq, max_len, w.sm_scale, window, split, 0, None,
@@ -602,7 +627,7 @@ def main():
     }
     if not args.skip_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, [0, w.num_layers // 3, 2 * w.num_layers // 3, w.num_layers - 1])
-    print(json.dumps(res))
+    emit(res)
 
 
 if __name__ == "__main__":
