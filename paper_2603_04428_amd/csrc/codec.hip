@@ -207,7 +207,10 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
             const float hi = (float)((word >> (8 * i + 4)) & 0xfu) * s + b;
             o[i] = (uint32_t)float_to_half_bits(lo) | ((uint32_t)float_to_half_bits(hi) << 16);
         }
-        *reinterpret_cast<uint4 *>(x + w * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+        // a store that says the line will not be read again: +4 % (4.85 -> 5.05 TB/s); the same hint on the loads
+        // changes nothing, and on either side of the quantize kernel it costs 6-9 %
+        typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+        __builtin_nontemporal_store(u4_t{o[0], o[1], o[2], o[3]}, reinterpret_cast<u4_t *>(x + w * 8));
     }
 }
 

@@ -48,10 +48,12 @@ __global__ __launch_bounds__(kCopyThreads) void image_copy_kernel(ImageParams p)
 #pragma unroll
         for (int k = 1; k < kPieces; ++k)
             if (k < p.pieces && off >= p.piece_off[k]) piece = k;
-        uint4 *pool = reinterpret_cast<uint4 *>(p.pool[piece] + ((long long)l * p.pool_blocks + blk) * p.piece_bytes[piece] +
-                                                (off - p.piece_off[piece]));
-        uint4 *img = reinterpret_cast<uint4 *>(p.image + rec * p.record_bytes + off);
-        if (TO_IMAGE) *img = *pool; else *pool = *img;
+        typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+        u4_t *pool = reinterpret_cast<u4_t *>(p.pool[piece] + ((long long)l * p.pool_blocks + blk) * p.piece_bytes[piece] +
+                                              (off - p.piece_off[piece]));
+        u4_t *img = reinterpret_cast<u4_t *>(p.image + rec * p.record_bytes + off);
+        // the stores say that the line will not be read again soon (as in the dequantize kernel)
+        if (TO_IMAGE) __builtin_nontemporal_store(*pool, img); else __builtin_nontemporal_store(*img, pool);
     }
 }
 
