@@ -25,9 +25,9 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes per launch of each workload's dominant kernel, read + written, from the rocprofv3 --pmc runs whose
 # summaries are under profiles/ (FETCH_SIZE and WRITE_SIZE scaled by what a plain copy of known size reads)
 MEASURED_TRAFFIC = {
-    "decode": 4754976768 + 12307456,
+    "decode": 4789188608 + 12313600,
     "dsv2lite_mla_latent_5agents_27layers_32k_decode": 1444208640 + 53625856,
-    "dsv2lite_mla_per_head_5agents_27layers_8k_decode": 3187380224,   # reads only (no WRITE_SIZE run)
+    "dsv2lite_mla_per_head_5agents_27layers_8k_decode": 3188256768,   # reads only (no WRITE_SIZE run)
 }
 
 

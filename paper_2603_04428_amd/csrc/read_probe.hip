@@ -11,6 +11,18 @@ namespace {
 constexpr int kProbeThreads = 256;
 constexpr int kProbeTile = 16384; // bytes a wave reads per step: two halves of eight 16-byte loads per lane
 
+// the decode kernel's load: 16 bytes, marked non-temporal (the data is read once)
+__device__ __forceinline__ uint4 probe_load(const uint4 *p)
+{
+#ifdef Q4KV_PROBE_PLAIN
+    return *p;
+#else
+    typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
+    const u4_t t = __builtin_nontemporal_load(reinterpret_cast<const u4_t *>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+#endif
+}
+
 __global__ __launch_bounds__(kProbeThreads, 2) void read_probe_kernel(const uint4 *__restrict__ src, long long tiles,
                                                                       uint32_t *__restrict__ sink)
 {
@@ -26,12 +38,12 @@ __global__ __launch_bounds__(kProbeThreads, 2) void read_probe_kernel(const uint
     auto load_a = [&](long long t) {
         const uint4 *p = src + t * (kProbeTile / 16) + lane;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) a[i] = p[i * kWave];
+        for (int i = 0; i < 8; ++i) a[i] = probe_load(p + i * kWave);
     };
     auto load_b = [&](long long t) {
         const uint4 *p = src + t * (kProbeTile / 16) + 8 * kWave + lane;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) b[i] = p[i * kWave];
+        for (int i = 0; i < 8; ++i) b[i] = probe_load(p + i * kWave);
     };
     load_a(t0);
     load_b(t0);
