@@ -207,6 +207,13 @@ def bench_latent(args, torch, b, synth, build_device_cache):
                              "mla_decode_kernel<9,8,false> (+ combine_kernel in the same call)")
 
 
+def bench_llama(args, torch, b, synth, build_device_cache):
+    """Decode over the Llama-3.1-8B-shaped cache of configuration 1 (5 agents x 4,096 tokens x 32 layers, 32 query /
+    8 KV heads, 128 wide): a short call (0.15 ms), so plan and combine weigh in it."""
+    return bench_decode_only(args, torch, b, build_device_cache, synth.config(1),
+                             "decode_attention_kernel<128,128,4,false> (+ combine_kernel in the same call)")
+
+
 def bench_per_head(args, torch, b, synth, build_device_cache):
     """Decode over the decompressed per-head form of the same model's cache (keys 192, values 128, 16 KV heads)."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.per_head_mla_config(),
@@ -474,7 +481,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (a known-size reference for scaling "
                          "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head", "restore", "mixed-step"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head", "llama", "restore", "mixed-step"], default="decode",
                     help="decode (default): the headline configuration; append: the chunked-append configuration "
                          "(10 agents, 4,096..32,768 cached tokens, 512-token chunk), reported as TFLOP/s; latent: "
                          "decode over the shared-latent (MLA-shaped) cache, 5 agents x 32,768 tokens x 27 layers; per-head: "
@@ -514,6 +521,8 @@ def main():
         return bench_latent(args, torch, b, synth, build_device_cache)
     if args.workload == "per-head":
         return bench_per_head(args, torch, b, synth, build_device_cache)
+    if args.workload == "llama":
+        return bench_llama(args, torch, b, synth, build_device_cache)
     if args.workload == "restore":
         return bench_restore(args, torch, b, synth, build_device_cache)
     if args.workload == "mixed-step":
