@@ -114,8 +114,9 @@ struct Stage {
 // a wave within 256 registers also at D = 256, so that two waves share a SIMD and one wave's dequantization and
 // softmax run under the other's matrix instructions.  The workgroup always owns 128 rows: 128 / (16 QT) waves.
 // BF: scale and bias are stored as bfloat16 (converted to binary16 when a row is staged).
+// (Two tiles at 192-wide keys need more than 256 registers: one wave per SIMD there, no scratch.)
 template <int DK, int DV, int NREP, int QT, bool BF>
-__global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, 2) void chunk_attention_kernel(ChunkParams p)
+__global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, (QT == 2 && DK > 128) ? 1 : 2) void chunk_attention_kernel(ChunkParams p)
 {
     constexpr int kRowsWave = 16 * QT;
     constexpr int kWaves = kRowsWG / kRowsWave;
