@@ -179,3 +179,42 @@ def test_agents_paged_through_a_small_pool(tmp_path):
         ok = np.abs(first[agent].view(np.float16).astype(np.float64)[:, 0] - want[:, agent].astype(np.float64)) <= \
             2e-3 + 2e-3 * np.abs(want[:, agent].astype(np.float64))
         assert ok.all()
+
+
+def test_bfloat16_cache_file_round_trip(tmp_path):
+    """A pool with bfloat16 scale / bias (appendix "safetensors Q4 Format") saved and read back with the format's own
+    torch reader: the scale and bias tensors are bfloat16 tensors holding the oracle-side cache's bits."""
+    from safetensors.torch import load_file
+    BF = b.PARAMS_BF16
+    w = synth.small(64, 2, 4, 2, 128, 128, False, (520, 90))
+    spec, kpool, vpool, table, table_d = gpu_cache(w, param_format=BF)
+    ospec, okp, ovp, otable = host_cache(w, param_format=BF)
+    agent, nb = 0, 3
+    ids = table_d[agent, :nb].contiguous()
+    image = b.q4kv_export_blocks(spec, kpool, vpool, ids)
+    path = os.path.join(tmp_path, "agent0_bf16.safetensors")
+    persist.save_agent(path, spec, image.cpu(), nb, 520)
+    tensors = load_file(path)
+    for l in range(2):
+        for i in range(nb):
+            blk = otable[agent, i]
+            for tag, pool in (("K", okp), ("V", ovp)):
+                assert np.array_equal(tensors[f"L{l}_B{i}_{tag}_weights"].numpy().view(np.uint32), pool.codes[l, blk])
+                for kind, arr in (("scales", pool.scale), ("biases", pool.bias)):
+                    t = tensors[f"L{l}_B{i}_{tag}_{kind}"]
+                    assert t.dtype == torch.bfloat16
+                    assert np.array_equal(t.view(torch.int16).numpy().view(np.uint16), arr[l, blk])
+    meta, img = persist.open_agent(path)
+    assert meta["spec"]["param_format"] == BF
+    # back into other blocks of a fresh pool: attention over the restored agent is bit-identical
+    k2, v2 = b.Pool(spec, 128, 6, DEV, True), b.Pool(spec, 128, 6, DEV, True)
+    new_ids = torch.tensor([5, 0, 3], dtype=torch.int32, device=DEV)
+    b.q4kv_import_blocks(spec, k2, v2, new_ids, torch.from_numpy(np.asarray(img).copy()).to(DEV))
+    sl = torch.tensor([520], dtype=torch.int32, device=DEV)
+    q = w.q_all(DEV)[:, :1].contiguous()
+    row_old = table_d[:1, :3].contiguous()
+    row_new = new_ids[None].contiguous()
+    a = b.q4kv_batched_attention(spec, kpool, vpool, q, row_old, sl, 520, w.sm_scale)
+    c = b.q4kv_batched_attention(spec, k2, v2, q, row_new, sl, 520, w.sm_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(a, c)
