@@ -425,7 +425,11 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                     }
             }
 
-            // ---- values: per 32-token half, B = p * s (binary16) of tokens 32 h2 + 4 e + qk, e = 0..7
+            // ---- values: per 32-token half, B = p * s of tokens 32 h2 + 4 e + qk, e = 0..7, in two binary16 terms.
+            // The product of two binary16 numbers minus its rounded value is a binary16 number again (barring
+            // underflow), so hi + lo carries p s to about 22 bits.  With hi alone an agent of a handful of tokens,
+            // where one or two rounding errors of p s make up the whole error of an output, can leave the tolerance
+            // when the latent holds channels of several times the usual magnitude.
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
                 half2_t p16[4];
@@ -443,10 +447,18 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                     const GroupIn in = grp_in[step % kRing];
                     if (step + kRing < 2 * GV) grp_in[step % kRing] = load_group(step + kRing);
                     __builtin_amdgcn_sched_barrier(0);
-                    const half8_t ps = words_to_half8(half2_to_bits(p16[0] * bits_to_half2(in.s8.x)),
-                                                      half2_to_bits(p16[1] * bits_to_half2(in.s8.y)),
-                                                      half2_to_bits(p16[2] * bits_to_half2(in.s8.z)),
-                                                      half2_to_bits(p16[3] * bits_to_half2(in.s8.w)));
+                    const half2_t s2[4] = {bits_to_half2(in.s8.x), bits_to_half2(in.s8.y), bits_to_half2(in.s8.z),
+                                           bits_to_half2(in.s8.w)};
+                    half2_t hi[4], lo[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        hi[i] = p16[i] * s2[i];
+                        lo[i] = __builtin_elementwise_fma(p16[i], s2[i], -hi[i]);
+                    }
+                    const half8_t ps_hi = words_to_half8(half2_to_bits(hi[0]), half2_to_bits(hi[1]), half2_to_bits(hi[2]),
+                                                         half2_to_bits(hi[3]));
+                    const half8_t ps_lo = words_to_half8(half2_to_bits(lo[0]), half2_to_bits(lo[1]), half2_to_bits(lo[2]),
+                                                         half2_to_bits(lo[3]));
                     uint32_t wm[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) wm[e] = in.w[e] & nibble_mask;
@@ -456,7 +468,8 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
                         const half8_t cop =
                             words_to_half8(__builtin_amdgcn_perm(wm[1], wm[0], sel), __builtin_amdgcn_perm(wm[3], wm[2], sel),
                                            __builtin_amdgcn_perm(wm[5], wm[4], sel), __builtin_amdgcn_perm(wm[7], wm[6], sel));
-                        acc[g][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cop, ps, acc[g][m], 0, 0, 0);
+                        acc[g][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cop, ps_hi, acc[g][m], 0, 0, 0);
+                        acc[g][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(cop, ps_lo, acc[g][m], 0, 0, 0);
                     }
                     if (g == GV - 1) // bias sums of this half: rows = groups
                         pbacc = __builtin_amdgcn_mfma_f32_16x16x32_f16(words_to_half8(braw4.x, braw4.y, braw4.z, braw4.w), pop,

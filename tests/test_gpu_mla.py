@@ -79,6 +79,20 @@ def test_latent_edge_cases_zero_length_poison_window_layer_range_and_bad_blocks(
     assert_close(got_bad[:, :3], want[:, :3], "agents beside the masked block")
 
 
+@pytest.mark.parametrize("param_format", [0, 1])
+def test_latent_tolerance_does_not_depend_on_the_draw(param_format):
+    """Agents of a handful of tokens, twenty draws: here one or two products p * s make up an output, and their
+    rounding decides the margin (the kernel carries p * s in two binary16 terms for this case)."""
+    lens = (5, 3, 9, 20)
+    for seed in range(100, 120):
+        w = mla(seed, 1, lens)
+        spec, kpool, vpool, table, table_d = gpu_cache(w, param_format=param_format)
+        ospec, okp, ovp, otable = host_cache(w, param_format=param_format)
+        got = run_gpu(w, spec, kpool, vpool, table_d, list(lens))
+        want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, list(lens), w.sm_scale)
+        assert_close(got, want, f"seed {seed} format {param_format}")
+
+
 def test_latent_per_layer_windows_match_oracle():
     w = mla(44, 4, (700, 90, 0, 1300))
     spec, kpool, vpool, table, table_d = gpu_cache(w)
