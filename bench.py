@@ -214,6 +214,13 @@ def bench_llama(args, torch, b, synth, build_device_cache):
                              "decode_attention_kernel<128,128,4,false> (+ combine_kernel in the same call)")
 
 
+def bench_tiny(args, torch, b, synth, build_device_cache):
+    """Configuration 0 (1 agent x 1,024 tokens x 1 layer, Llama-shaped): 1.2 MB of cache that stays in the caches of
+    the chip, so the figure of interest is the latency of one call (plan + attention + combine), `decode_us`."""
+    return bench_decode_only(args, torch, b, build_device_cache, synth.config(0),
+                             "decode_attention_kernel<128,128,4,false> (+ plan_kernel and combine_kernel in the same call)")
+
+
 def bench_per_head(args, torch, b, synth, build_device_cache):
     """Decode over the decompressed per-head form of the same model's cache (keys 192, values 128, 16 KV heads)."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.per_head_mla_config(),
@@ -459,7 +466,7 @@ def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
                    "split_tokens": split, "launch": "all layers in one q4kv_batched_attention call"},
         "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "agent_tokens_per_s": w.num_agents / (dec_ms * 1e-3),
-        "decode_ms": dec_ms, "decode_ms_p10": percentile(dec, 10), "decode_ms_p90": percentile(dec, 90),
+        "decode_ms": dec_ms, "decode_us": dec_ms * 1e3, "decode_ms_p10": percentile(dec, 10), "decode_ms_p90": percentile(dec, 90),
         "decode_ms_min": min(dec), "decode_bytes": decode_bytes,
         "matrix_TFLOPs": flops / (dec_ms * 1e-3) / 1e12,
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -481,11 +488,12 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (a known-size reference for scaling "
                          "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head", "llama", "restore", "mixed-step"], default="decode",
+    ap.add_argument("--workload", choices=["decode", "append", "latent", "per-head", "llama", "tiny", "restore", "mixed-step"], default="decode",
                     help="decode (default): the headline configuration; append: the chunked-append configuration "
                          "(10 agents, 4,096..32,768 cached tokens, 512-token chunk), reported as TFLOP/s; latent: "
                          "decode over the shared-latent (MLA-shaped) cache, 5 agents x 32,768 tokens x 27 layers; per-head: "
-                         "decode over the decompressed form of that cache (keys 192, values 128, 16 KV heads); restore: save "
+                         "decode over the decompressed form of that cache (keys 192, values 128, 16 KV heads); llama: decode over the "
+                         "Llama-shaped cache of configuration 1; tiny: the latency of one call on configuration 0; restore: save "
                          "and restore of one 32,768-token agent through a block image, also while other agents decode; mixed-step: "
                          "one agent's 512-token append on a second stream beside the decode steps of ten others")
     ap.add_argument("--per-layer-graph", action="store_true",
@@ -523,6 +531,8 @@ def main():
         return bench_per_head(args, torch, b, synth, build_device_cache)
     if args.workload == "llama":
         return bench_llama(args, torch, b, synth, build_device_cache)
+    if args.workload == "tiny":
+        return bench_tiny(args, torch, b, synth, build_device_cache)
     if args.workload == "restore":
         return bench_restore(args, torch, b, synth, build_device_cache)
     if args.workload == "mixed-step":
@@ -619,7 +629,7 @@ def main():
                    "split_tokens": split, "launch": "all layers in one q4kv_batched_attention call"},
         "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
         "agent_tokens_per_s": w.num_agents / (dec_ms * 1e-3),
-        "decode_ms": dec_ms, "decode_ms_p10": percentile(dec, 10), "decode_ms_p90": percentile(dec, 90),
+        "decode_ms": dec_ms, "decode_us": dec_ms * 1e3, "decode_ms_p10": percentile(dec, 10), "decode_ms_p90": percentile(dec, 90),
         "decode_ms_min": min(dec), "decode_ms_mean": sum(dec) / len(dec), "decode_bytes": decode_bytes,
         "read_probe_GBps": probe_gbps, "pct_of_read_probe": 100.0 * gbps / probe_gbps,
         "per_layer_graph_ms": per_layer_ms, "seed": w.seed,
