@@ -7,7 +7,7 @@ import torch
 import oracle
 from paper_2603_04428_amd import binding as b
 from paper_2603_04428_amd import synth
-from tests.gpu_util import DEV, gpu_cache, host_cache, oracle_unit
+from tests.gpu_util import DEV, bits, gpu_cache, host_cache, oracle_unit
 from tests.util import within_tol
 
 pytestmark = pytest.mark.gpu
@@ -142,3 +142,43 @@ def test_config4_one_layer_sampled_rows():
             q = w.q_rows(0, a).numpy()[r:r + 1]
             want = oracle_unit(w, 0, a, h, vis, q=q)
             assert_close(got[0, a, r, h * R:(h + 1) * R], want[0], f"agent {a} kv head {h} chunk row {r}")
+
+
+def test_config4_full_size_sampled_rows():
+    """The same at full size with the benchmark's launches: one q4kv_append and one attention call for all 48 layers
+    (21 GB of Q4 cache, 1 GB of new K and of new V, 2 GB of output).  Sampled appended rows are compared bit for bit
+    and sampled (layer, agent, kv head, chunk row) outputs within the tolerance with the oracle, which rebuilds each
+    of them from the generator alone."""
+    w = synth.config(4)
+    spec, kpool, vpool, table, table_d = gpu_cache(w, tokens=w.seq_lens)
+    C = w.q_len
+    before = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    k_new = torch.empty((w.num_layers, w.num_agents, C, w.num_kv_heads, w.k_dim), dtype=torch.float16, device=DEV)
+    v_new = torch.empty((w.num_layers, w.num_agents, C, w.num_kv_heads, w.v_dim), dtype=torch.float16, device=DEV)
+    for l in range(w.num_layers):
+        for a, n in enumerate(w.seq_lens):
+            k_new[l, a] = w.k_rows(l, a, n, n + C, DEV)
+            v_new[l, a] = w.v_rows(l, a, n, n + C, DEV)
+    b.q4kv_append(spec, kpool, vpool, k_new, v_new, table_d, before, 0, w.num_layers)
+    after = torch.tensor(w.final_lens(), dtype=torch.int32, device=DEV)
+    got = b.q4kv_batched_attention(spec, kpool, vpool, w.q_all(DEV), table_d, after, max(w.final_lens()), w.sm_scale, 0)
+    torch.cuda.synchronize()
+    assert not torch.isnan(got).any()
+    shortest, longest = int(np.argmin(w.seq_lens)), int(np.argmax(w.seq_lens))
+    R = w.n_rep
+    for (l, a, h) in [(0, shortest, 0), (w.num_layers - 1, longest, 7), (20, 3, 4)]:
+        n0, n = w.seq_lens[a], w.final_lens()[a]
+        for c in (0, 255, 511):          # appended rows, bit for bit
+            t = n0 + c
+            blk, slot = int(table[a, t // 256]), t % 256
+            for pool, rows in ((kpool, w.k_rows(l, a, t, t + 1, h0=h, h1=h + 1)), (vpool, w.v_rows(l, a, t, t + 1, h0=h, h1=h + 1))):
+                codes, scale, bias = oracle.quantize(rows.numpy().reshape(1, -1))
+                assert np.array_equal(bits(pool.codes[l, blk, h, slot]), codes[0]), f"codes of layer {l} agent {a} token {t}"
+                assert np.array_equal(bits(pool.scale[l, blk, h, slot]), scale[0])
+                assert np.array_equal(bits(pool.bias[l, blk, h, slot]), bias[0])
+        for r in (0, 255, 511):
+            vis = n - (w.q_len - 1 - r)
+            q = w.q_rows(l, a).numpy()[r:r + 1]
+            want = oracle_unit(w, l, a, h, vis, q=q)
+            assert_close(got[l, a, r, h * R:(h + 1) * R].cpu().numpy(), want[0],
+                         f"layer {l} agent {a} kv head {h} chunk row {r}")
