@@ -1,5 +1,6 @@
 // The C ABI of libq4kv (include/q4kv.h): argument validation on the host, launch planning
 // (split-K schedule), and nothing else -- every step of the path runs in the kernels.
+#include <atomic>
 #include <hip/hip_runtime.h>
 
 #include <cstdarg>
@@ -52,15 +53,15 @@ int check_pool(const q4kv_pool *p, const char *name)
 // Compute units of the current device (cached per device); the attention launch is two workgroups per unit.
 int compute_units()
 {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64]; // zero-initialised; threads that race here store the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 // Workgroups of a decode launch: the shared-latent kernel fills a compute unit's LDS with one workgroup,

@@ -273,3 +273,47 @@ def test_decode_call_replays_from_a_graph():
     call()
     torch.cuda.synchronize()
     assert torch.equal(out, replayed)
+
+
+def test_host_threads_on_their_own_streams():
+    """Calls that overlap in time from several host threads, each on a stream of its own with its own output and
+    workspace, give bit for bit what the same calls give one after the other (the boundary promises this)."""
+    import threading
+    w = synth.small(51, 2, 8, 2, 128, 128, False, (700, 90, 1300, 5))
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    lens = list(w.seq_lens)
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    q = w.q_all(DEV)
+    x = torch.randn((4096, 128), generator=torch.Generator().manual_seed(5)).to(torch.float16).to(DEV)
+    variants = [dict(window=0, split_tokens=0), dict(window=100, split_tokens=256), dict(window=0, split_tokens=512),
+                dict(window=[0, 64], split_tokens=0)]
+
+    def work(i):
+        out = b.q4kv_batched_attention(spec, kpool, vpool, q, table_d, sl, max(lens), w.sm_scale, **variants[i % 4])
+        codes, scale, bias = b.q4kv_quantize(x[i * 512:(i + 2) * 512])
+        return out, codes, scale, bias
+
+    serial = [work(i) for i in range(6)]
+    torch.cuda.synchronize()
+    results, errors = [None] * 6, []
+
+    def worker(i):
+        try:
+            st = torch.cuda.Stream()
+            with torch.cuda.stream(st):
+                for _ in range(20):
+                    r = work(i)
+                st.synchronize()
+            results[i] = r
+        except Exception as e:      # noqa: BLE001 - reported below
+            errors.append((i, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(6)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for i in range(6):
+        for got, want in zip(results[i], serial[i]):
+            assert torch.equal(got, want), f"thread {i}"
