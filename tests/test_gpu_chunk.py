@@ -182,3 +182,56 @@ def test_config4_full_size_sampled_rows():
             want = oracle_unit(w, l, a, h, vis, q=q)
             assert_close(got[l, a, r, h * R:(h + 1) * R].cpu().numpy(), want[0],
                          f"layer {l} agent {a} kv head {h} chunk row {r}")
+
+
+def test_append_and_chunk_attention_replay_from_a_graph():
+    """One step of a prefill loop (append a chunk, attend over cache + chunk) recorded into a graph once and replayed
+    for the following chunks: lengths, the new rows and the queries live in device buffers that the host refills
+    between replays.  Every replay must equal the same step issued eagerly on a second copy of the cache."""
+    C = 64
+    w = synth.small(52, 2, 8, 4, 128, 128, False, (300, 10, 700), q_len=4 * C)   # blocks for four chunks are reserved
+    spec, kpool, vpool, table, table_d = gpu_cache(w, tokens=w.seq_lens)
+    spec2, kpool2, vpool2, _, table2_d = gpu_cache(w, tokens=w.seq_lens)
+    A, L = w.num_agents, w.num_layers
+    before = torch.tensor(w.seq_lens, dtype=torch.int32, device=DEV)
+    after = before + C
+    k_new = torch.empty((L, A, C, w.num_kv_heads, w.k_dim), dtype=torch.float16, device=DEV)
+    v_new = torch.empty_like(k_new)
+    q = torch.empty((L, A, C, w.num_q_heads, w.k_dim), dtype=torch.float16, device=DEV)
+    out = torch.empty((L, A, C, w.num_q_heads, w.v_dim), dtype=torch.float16, device=DEV)
+    msl = max(w.seq_lens) + 4 * C
+
+    def fill(step):
+        for l in range(L):
+            for a, n in enumerate(w.seq_lens):
+                k_new[l, a] = w.k_rows(l, a, n + step * C, n + (step + 1) * C, DEV)
+                v_new[l, a] = w.v_rows(l, a, n + step * C, n + (step + 1) * C, DEV)
+        q.copy_(torch.randn(q.shape, generator=torch.Generator().manual_seed(100 + step)).to(torch.float16))
+        before.copy_(torch.tensor([n + step * C for n in w.seq_lens], dtype=torch.int32))
+        after.copy_(before + C)
+
+    def step_on(kp, vp, tab, dst):
+        b.q4kv_append(spec, kp, vp, k_new, v_new, tab, before, 0, L)
+        b.q4kv_batched_attention(spec, kp, vp, q, tab, after, msl, w.sm_scale, 0, 0, 0, None, dst)
+
+    fill(0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step_on(kpool, vpool, table_d, out)            # warm-up on the capture stream (writes chunk 0, rewritten below)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step_on(kpool, vpool, table_d, out)
+    for step in range(4):
+        fill(step)
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = torch.empty_like(out)
+        step_on(kpool2, vpool2, table2_d, want)
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {step}"
+    assert torch.equal(kpool.codes, kpool2.codes) and torch.equal(vpool.scale, vpool2.scale)
