@@ -68,15 +68,19 @@ int compute_units()
 // the GQA kernel runs two per compute unit.
 int attention_workgroups(const q4kv_spec &s) { return (q4kv::mla_decode_supported(s) ? 1 : 2) * compute_units(); }
 
-// Smallest token range a wave takes when the caller leaves the choice to the library: about half of an even
-// share of the largest possible job, between one block and 4,096 tokens.
+// Smallest token range a wave takes when the caller leaves the choice to the library.  The floor matters for small
+// jobs only (a wave's partial record and its share of the combine step cost about one tile's time, so shares
+// below a few tiles do not pay); a large job gives every wave an even share whatever the floor is.  Since only the
+// device knows how much of max_seq_len the agents and the sliding windows leave visible, the floor stays small:
+// half of an even share of the largest possible job, between one block and 1,024 tokens.  (A floor of 4,096
+// tokens left a quarter of the waves without work on a 10-agent step whose windows hid two thirds of the cache.)
 int pick_split_tokens(const q4kv_spec &s, int num_agents, int max_seq_len, int layers)
 {
     const long long tiles = (long long)layers * s.num_kv_heads * num_agents * ((max_seq_len + 63) / 64);
     const long long waves = (long long)attention_workgroups(s) * q4kv::decode_waves_per_workgroup();
     long long blocks = tiles / waves / 2 / 4; // in 256-token blocks
     if (blocks < 1) blocks = 1;
-    if (blocks > 16) blocks = 16;
+    if (blocks > 4) blocks = 4;
     return (int)blocks * 256;
 }
 
