@@ -161,7 +161,8 @@ def test_workspace_and_split_queries():
     gemma = b.make_spec(48, 16, 8, 256)
     st = b.q4kv_default_split_tokens(gemma, 10, 1, 8192, 48)
     assert st % 256 == 0 and 256 <= st <= 1024
-    assert b.q4kv_default_split_tokens(gemma, 10, 1, 8192, 1) == 256            # small job: finest share
+    assert b.q4kv_default_split_tokens(gemma, 10, 1, 8192, 1) == 512            # one layer's call: twice an even share
+    assert b.q4kv_default_split_tokens(gemma, 1, 1, 1024, 1) == 256             # small job: finest share
     n = b.q4kv_attention_workspace_bytes(gemma, 10, 1, 8192, 1024, 48)
     slots = (8192 // 64 + 15) // 16 + 1            # a unit of 128 tiles can meet at most 9 shares of >= 16 tiles
     A, L = 10, 48                                  # plan: header, per-layer prefix and class, L class blocks, lengths
