@@ -572,12 +572,17 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         wave_lds_sync();
 
         // ---- V side: acc[head][e] += (p s)[t] * c[t][e], four tokens per matrix instruction
+        // One wave-uniform test for all heads: a branch per head made the compiler copy the accumulators round
+        // every one of them.  The running maxima settle after a unit's first tiles, so this is rarely taken.
+        float alpha_min = alpha[0];
 #pragma unroll
-        for (int r = 0; r < NREP; ++r)
-            if (alpha[r] != 1.0f) { // wave-uniform
+        for (int r = 1; r < NREP; ++r) alpha_min = fminf(alpha_min, alpha[r]);
+        if (__builtin_bit_cast(float, uniform(__builtin_bit_cast(int, alpha_min))) != 1.0f) {
+#pragma unroll
+            for (int r = 0; r < NREP; ++r)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[r / 4][e][r % 4] *= alpha[r];
-            }
+        }
 #pragma unroll
         for (int i = 0; i < VSTEPS; i += 4) {
             half4_t pq[VHQ];
