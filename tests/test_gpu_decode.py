@@ -40,6 +40,10 @@ SMALL = [
     (1, 4, 4, 256, (90,)),
     (1, 8, 2, 64, (1000,)),
     (1, 4, 1, 128, (1500, 20)),
+    # eight query heads per KV head: two passes of four heads on the value side
+    (1, 8, 1, 64, (200, 70)),
+    (1, 16, 2, 128, (300, 5)),
+    (1, 8, 1, 256, (150, 65)),
 ]
 
 
@@ -49,6 +53,7 @@ PER_HEAD_MLA = [
     (2, 16, 16, (192, 128), (37, 300, 1, 64)),
     (1, 4, 4, (192, 128), (700, 257)),
     (1, 8, 4, (192, 128), (513,)),
+    (1, 8, 1, (192, 128), (130, 3)),
 ]
 
 
