@@ -72,18 +72,19 @@ int attention_workgroups(const q4kv_spec &s) { return (q4kv::mla_decode_supporte
 // jobs only (a wave's partial record and its share of the combine step cost about one tile's time, so shares
 // of very few tiles do not pay); a large job gives every wave an even share whatever the floor is.  Since only the
 // device knows how much of max_seq_len the agents and the sliding windows leave visible, the floor stays small:
-// twice an even share of the largest possible job, between one block and 1,024 tokens.  Measured on one layer's
+// twice an even share of the largest possible job, between one block and 512 tokens.  Measured on one layer's
 // call: 10 agents of 1K-8K tokens, 256-wide heads (even share 2.7 tiles) 51.6 / 47.8 / 52.6 / 59.9 us at 256 /
 // 512 / 768 / 1,024 tokens; 5 agents of 4K tokens, 128-wide heads (1.25 tiles) 32.6 / 34.2 / 43.6 / 46.7 us.
-// (A floor of 4,096 tokens left a quarter of the waves without work on a 10-agent, 48-layer step whose windows
-// hid two thirds of the cache.)
+// A larger floor leaves waves without work whenever the visible cache is a fraction of the largest job: at
+// 4,096 tokens a quarter of the waves on a 10-agent, 48-layer step whose windows hid two thirds of the cache; at
+// 1,024 tokens four in ten on ten 300-token agents (0.115 ms against 0.090 ms at 512).
 int pick_split_tokens(const q4kv_spec &s, int num_agents, int max_seq_len, int layers)
 {
     const long long tiles = (long long)layers * s.num_kv_heads * num_agents * ((max_seq_len + 63) / 64);
     const long long waves = (long long)attention_workgroups(s) * q4kv::decode_waves_per_workgroup();
     long long blocks = tiles / waves / 2; // 2 * (tiles / waves) tiles, in 256-token blocks of 4 tiles
     if (blocks < 1) blocks = 1;
-    if (blocks > 4) blocks = 4;
+    if (blocks > 2) blocks = 2;
     return (int)blocks * 256;
 }
 
