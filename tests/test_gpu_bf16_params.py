@@ -9,6 +9,7 @@ import oracle
 from paper_2603_04428_amd import binding as b
 from paper_2603_04428_amd import synth
 from tests.gpu_util import DEV, bits, gpu_cache, host_cache, oracle_unit
+from tests.util import tie_adjacent_rows_bf16
 from tests.test_gpu_chunk import append_chunk_and_attend
 from tests.test_gpu_decode import assert_close, run_gpu
 
@@ -76,22 +77,7 @@ def test_quantize_special_groups_bit_exact():
 def test_quantize_quotients_next_to_rounding_ties_bit_exact():
     """Quotients (x - bias_stored) / scale_stored on, just below and just above k + 0.5 for bfloat16-representable
     scales and biases: an approximate division flips some of these codes."""
-    rng = np.random.default_rng(8)
-    rows = []
-    for _ in range(400):
-        s = oracle.bf2f(oracle.f2bf(rng.uniform(0.01, 4.0)))
-        base = oracle.bf2f(oracle.f2bf(rng.uniform(-3, 3)))
-        g = np.empty(64)
-        g[0], g[1] = base, base + 15 * s
-        g[2:] = base + (rng.integers(0, 15, 62) + 0.5) * s
-        x16 = g.astype(F16)
-        nb = x16.copy().view(np.uint16).astype(np.int32)
-        step = rng.integers(-2, 3, 64)
-        step[:2] = 0
-        rows.append(x16)
-        rows.append((nb + step).clip(0, 0xFBFF).astype(np.uint16).view(F16))
-    x = np.stack(rows)
-    check_quantize(x[np.isfinite(x.astype(np.float32)).all(axis=1)])
+    check_quantize(tie_adjacent_rows_bf16(8))
 
 
 def test_dequantize_arbitrary_codes_bit_exact():

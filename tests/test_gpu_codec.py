@@ -7,6 +7,7 @@ import oracle
 from paper_2603_04428_amd import binding as b
 from paper_2603_04428_amd import synth
 from tests.gpu_util import DEV, bits
+from tests.util import tie_adjacent_rows
 
 pytestmark = pytest.mark.gpu
 F16 = np.float16
@@ -65,29 +66,7 @@ def test_quantize_quotients_next_to_rounding_ties_bit_exact():
     """Groups whose quotients (x - min) / scale sit on, just below and just above k + 0.5 for every code k and many
     scales (normal and subnormal binary16): a quotient approximated in any cheaper way than the correctly rounded
     binary32 division flips some of these codes."""
-    rng = np.random.default_rng(7)
-    rows = []
-    scales = np.concatenate([rng.uniform(0.01, 4.0, 300), 2.0 ** rng.integers(-20, 3, 60).astype(np.float64),
-                             rng.uniform(1, 60, 60) * 2.0 ** -24])
-    for sc in scales:
-        s16 = float(F16(sc))
-        if s16 == 0.0:
-            continue
-        base = float(F16(rng.uniform(-3, 3))) if sc > 1e-4 else 0.0
-        g = np.empty(64)
-        g[0], g[1] = base, base + 15 * s16
-        k = rng.integers(0, 15, 62) + 0.5
-        g[2:] = base + k * s16
-        x16 = g.astype(F16)
-        # neighbours in binary16 of the tie points, in both directions
-        nb = x16.copy().view(np.uint16)
-        step = rng.integers(-2, 3, 64).astype(np.int32)
-        step[:2] = 0
-        nb = (nb.astype(np.int32) + step).clip(0, 0xFBFF).astype(np.uint16)
-        rows.append(x16)
-        rows.append(nb.view(F16))
-    x = np.stack(rows)
-    x = x[np.isfinite(x.astype(np.float32)).all(axis=1)]
+    x = tie_adjacent_rows(7)
     check_quantize(x)
     # the same rows tiled into wide rows (several groups per row, ragged row count)
     check_quantize(np.ascontiguousarray(x[: (len(x) // 4) * 4].reshape(-1, 256)))
