@@ -33,9 +33,14 @@
 //  * V side: the contraction runs over tokens while a word holds 8 dims of one token, so the big matrix
 //    tiles do not fit (their K-index would have to be 8 tokens of one dim).  It runs on the 16-block
 //    4x4x4 form instead (v_mfma_f32_4x4x4_16B_f16): each block of 4 lanes multiplies the 4x4 matrix
-//    (query head) x (4 tokens) of binary16 p*s -- one quantization group per block, so the per-group
+//    (operand row) x (4 tokens) of binary16 p*s -- one quantization group per block, so the per-group
 //    scale can live in it -- with (4 tokens) x (4 dims) of codes.  The lane owning a word pairs the
 //    codes of two tokens with v_perm and masks nibbles in place, two tokens per register.
+//    p*s travels as two binary16 terms, hi = fl16(p*s) and lo = fl16(p*s - hi), in two operand rows per
+//    query head: one term alone errs by 2^-12 of p*s*c, which is relative to a group's range (c*s up to
+//    15 s) and not to the value, and would leave the output tolerance on caches with wide value groups.
+//    With one or two query heads per KV head the second term sits in operand rows that were repeats (no
+//    further matrix instruction); with four or eight it is a second instruction into the same accumulator.
 #include "q4_device.h"
 #include "q4kv_internal.h"
 #include "stream_k.h"
@@ -333,13 +338,15 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     constexpr int VLPT = DV / 8;
     constexpr int VTPS = kWave / VLPT;
     constexpr int VSTEPS = kWave / VTPS;
+    constexpr int VROWS = 2 * NREP;                // rows of p*s: row t*NREP + r = term t (0: hi, 1: lo) of head r
+    constexpr bool kTermRows = NREP <= 2;          // both terms fit the 4 operand rows of one instruction
     constexpr int VHQ = NREP > 4 ? NREP / 4 : 1;   // passes over the query heads, 4 rows each
     static_assert(VLPT % 8 == 0 && VLPT <= kWave && VSTEPS % 4 == 0, "V layout");
-    // per wave: q.c per token, group and head [64][GK][NREP] (binary32) and p*scale [NREP][GV][64] (binary16,
+    // per wave: q.c per token, group and head [64][GK][NREP] (binary32) and p*scale [VROWS][GV][64] (binary16,
     // the tokens of four consecutive V load steps of a slot side by side, 8 bytes); the same
     // region serves the end-of-unit reduction [VTPS][NREP][DV] + bias sums [NREP][GV]
     constexpr int kPartFloats = kWave * GK * NREP;
-    constexpr int kPsFloats = NREP * GV * kWave / 2;
+    constexpr int kPsFloats = VROWS * GV * kWave / 2;
     constexpr int kFinalFloats = VTPS * NREP * DV + NREP * GV;
     constexpr int kWaveFloats = (kPartFloats + kPsFloats > kFinalFloats ? kPartFloats + kPsFloats : kFinalFloats) + NREP * GK;
     __shared__ float lds[kWaves * kWaveFloats];
@@ -357,7 +364,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 
     float *region = lds + wave * kWaveFloats;
     float *part = region;                                                  // [64][GK][NREP]
-    uint16_t *ps_h = reinterpret_cast<uint16_t *>(region + kPartFloats);   // [NREP][GV][64] binary16
+    uint16_t *ps_h = reinterpret_cast<uint16_t *>(region + kPartFloats);   // [VROWS][GV][64] binary16
     const uint2 *ps_q = reinterpret_cast<const uint2 *>(ps_h);            // the same as token quads
     float *qsum_lds = region + (kWaveFloats - NREP * GK);                  // [NREP][GK]
 
@@ -367,7 +374,8 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / 8;
     // where the token owned by this lane (local index `lane` = step*VTPS + slot) goes in ps_h
     const int ps_slot = 4 * VTPS * ((lane / VTPS) / 4) + 4 * (lane % VTPS) + ((lane / VTPS) & 3);
-    const int v_row = NREP >= 4 ? (lane & 3) : (lane & 3) % NREP; // query head (within a pass) of this lane's operand row
+    // row of p*s (within a pass and term) that this lane supplies to the matrix instruction
+    const int v_row = kTermRows ? (lane & 3) % VROWS : (lane & 3);
 
     Words<KWPL> kc[KSETS][KCHUNKS];
     uint32_t vc[VSTEPS];
@@ -401,8 +409,8 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 
     half8_t qop[KCHUNKS][KWPL];
     float qsum[NREP][GK];
-    float4_t acc[VHQ][8]; // [pass][dim of this lane's word][head in pass]; odd dims carry an extra factor 16 until
-                          // the end (their codes sit 4 bits higher)
+    float4_t acc[VHQ][8]; // [pass][dim of this lane's word][operand row in pass]; odd dims carry an extra factor 16
+                          // until the end (their codes sit 4 bits higher)
     float m_run[NREP], l_run[NREP], pb[NREP][GV]; // l_run, pb: this lane's tokens only
 
     const int64_t row0 = cur.row;
@@ -565,7 +573,12 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
             l_run[r] = fmaf(l_run[r], alpha[r], pr);
 #pragma unroll
             for (int g = 0; g < GV; ++g) {
-                ps_h[(r * GV + g) * kWave + ps_slot] = float_to_half_bits(tok_valid ? pr * vs[g] : 0.0f);
+                const float prs = tok_valid ? pr * vs[g] : 0.0f;
+                const half_t hi = (half_t)prs;
+                // what hi rounded away (a masked row's scale may hold anything, a NaN included)
+                const half_t lo = tok_valid ? (half_t)fmaf(pr, vs[g], -(float)hi) : (half_t)0.0f;
+                ps_h[(r * GV + g) * kWave + ps_slot] = __builtin_bit_cast(uint16_t, hi);
+                ps_h[((NREP + r) * GV + g) * kWave + ps_slot] = __builtin_bit_cast(uint16_t, lo);
                 pb[r][g] = fmaf(pb[r][g], alpha[r], tok_valid ? pr * vb[g] : 0.0f);
             }
         }
@@ -579,18 +592,21 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         for (int r = 1; r < NREP; ++r) alpha_min = fminf(alpha_min, alpha[r]);
         if (__builtin_bit_cast(float, uniform(__builtin_bit_cast(int, alpha_min))) != 1.0f) {
 #pragma unroll
-            for (int r = 0; r < NREP; ++r)
+            for (int row = 0; row < (kTermRows ? VROWS : NREP); ++row)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc[r / 4][e][r % 4] *= alpha[r];
+                for (int e = 0; e < 8; ++e) acc[row / 4][e][row % 4] *= alpha[row % NREP];
         }
 #pragma unroll
         for (int i = 0; i < VSTEPS; i += 4) {
-            half4_t pq[VHQ];
+            constexpr int kTerms = kTermRows ? 1 : 2; // matrix instructions per accumulator and step
+            half4_t pq[kTerms][VHQ];
 #pragma unroll
-            for (int h = 0; h < VHQ; ++h) {
-                const uint2 raw = ps_q[((h * 4 + v_row) * GV + vg) * (kWave / 4) + VTPS * (i / 4) + vo];
-                pq[h] = __builtin_bit_cast(half4_t, raw);
-            }
+            for (int t = 0; t < kTerms; ++t)
+#pragma unroll
+                for (int h = 0; h < VHQ; ++h) {
+                    const uint2 raw = ps_q[((t * NREP + h * 4 + v_row) * GV + vg) * (kWave / 4) + VTPS * (i / 4) + vo];
+                    pq[t][h] = __builtin_bit_cast(half4_t, raw);
+                }
 #pragma unroll
             for (int by = 0; by < 4; ++by) {
                 // byte `by` of the four tokens' words: codes 2*by (low nibble) and 2*by+1 (high nibble)
@@ -600,10 +616,12 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                 const half4_t lo = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x000F000Fu, p23 & 0x000F000Fu));
                 const half4_t hi = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x00F000F0u, p23 & 0x00F000F0u));
 #pragma unroll
-                for (int h = 0; h < VHQ; ++h) {
-                    acc[h][2 * by] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[h], lo, acc[h][2 * by], 0, 0, 0);
-                    acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[h], hi, acc[h][2 * by + 1], 0, 0, 0);
-                }
+                for (int t = 0; t < kTerms; ++t)
+#pragma unroll
+                    for (int h = 0; h < VHQ; ++h) {
+                        acc[h][2 * by] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[t][h], lo, acc[h][2 * by], 0, 0, 0);
+                        acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[t][h], hi, acc[h][2 * by + 1], 0, 0, 0);
+                    }
             }
             load_v_quad(i, row0_next);
         }
@@ -619,7 +637,9 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
             for (int r = 0; r < NREP; ++r) {
                 float *dst = fin_acc + (vo * NREP + r) * DV + vj * 8;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dst[e] = acc[r / 4][e][r % 4] * ((e & 1) ? kCodeScaleB : kCodeScaleA);
+                for (int e = 0; e < 8; ++e)
+                    dst[e] = (kTermRows ? acc[0][e][r] + acc[0][e][NREP + r] : acc[r / 4][e][r % 4]) *
+                             ((e & 1) ? kCodeScaleB : kCodeScaleA);
                 lsum[r] = wave_sum(l_run[r]);
 #pragma unroll
                 for (int g = 0; g < GV; ++g) {

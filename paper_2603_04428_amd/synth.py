@@ -116,9 +116,9 @@ def draw(seed: int, tensor: int, layer: int, agent: int, t0: int, t1: int, heads
     return x.to(torch.float16)
 
 
-def outlier_channels(seed: int, layers: int, kv_heads: int, dim: int, n: int = 4) -> np.ndarray:
-    """4 distinct K channels per (layer, kv head), fixed across tokens and agents: int64 [layers][kv_heads][n]."""
-    rng = np.random.default_rng([seed, 0xC0FFEE])
+def outlier_channels(seed: int, layers: int, kv_heads: int, dim: int, n: int = 4, tag: int = 0xC0FFEE) -> np.ndarray:
+    """4 distinct channels per (layer, kv head), fixed across tokens and agents: int64 [layers][kv_heads][n]."""
+    rng = np.random.default_rng([seed, tag])
     out = np.empty((layers, kv_heads, n), np.int64)
     for l in range(layers):
         for h in range(kv_heads):
@@ -141,10 +141,15 @@ class Workload:
     q_len: int = 1               # 1 = decode, >1 = appended chunk length
     block_tokens: int = BLOCK_TOKENS
     outliers: np.ndarray = field(default=None, repr=False)
+    wide_v: bool = False         # test shapes only: a quarter of the V channels is multiplied by 8 (group ranges of 20 to 45)
+    v_outliers: np.ndarray = field(default=None, repr=False)
 
     def __post_init__(self):
         if self.outliers is None:
             self.outliers = outlier_channels(self.seed, self.num_layers, self.num_kv_heads, self.k_dim)
+        if self.wide_v and self.v_outliers is None:
+            self.v_outliers = outlier_channels(self.seed, self.num_layers, self.num_kv_heads, self.v_dim, n=self.v_dim // 4,
+                                               tag=0xFACADE)
 
     @property
     def num_agents(self):
@@ -168,7 +173,8 @@ class Workload:
                     self.outliers[layer], h0, h1)
 
     def v_rows(self, layer, agent, t0, t1, device="cpu", h0=0, h1=None):
-        return draw(self.seed, TENSOR_V, layer, agent, t0, t1, self.num_kv_heads, self.v_dim, device, None, h0, h1)
+        return draw(self.seed, TENSOR_V, layer, agent, t0, t1, self.num_kv_heads, self.v_dim, device,
+                    self.v_outliers[layer] if self.wide_v else None, h0, h1)
 
     def q_rows(self, layer, agent, device="cpu"):
         """[q_len][q_heads][k_dim]"""
@@ -233,6 +239,6 @@ def per_head_mla_config() -> Workload:
 
 
 def small(seed, num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, seq_lens=(300,),
-          q_len=1, name="small") -> Workload:
+          q_len=1, name="small", wide_v=False) -> Workload:
     return Workload(name, seed, num_layers, num_q_heads, num_kv_heads, k_dim, k_dim if v_dim is None else v_dim,
-                    v_aliases_k, list(seq_lens), q_len)
+                    v_aliases_k, list(seq_lens), q_len, wide_v=wide_v)

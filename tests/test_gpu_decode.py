@@ -322,3 +322,38 @@ def test_host_threads_on_their_own_streams():
     for i in range(6):
         for got, want in zip(results[i], serial[i]):
             assert torch.equal(got, want), f"thread {i}"
+
+
+WIDE_V = [
+    # Hq, Hkv, (Dk, Dv): every kernel template (64 / 128 / 256 / 192-128 wide) x 1, 2, 4, 8 query heads per KV head
+    (1, 1, 64), (4, 2, 64), (4, 1, 64), (8, 1, 64),
+    (2, 2, 128), (4, 2, 128), (8, 2, 128), (8, 1, 128),
+    (1, 1, 256), (4, 2, 256), (4, 1, 256), (8, 1, 256),
+    (2, 2, (192, 128)), (2, 1, (192, 128)), (4, 1, (192, 128)), (8, 1, (192, 128)),
+]
+
+
+@pytest.mark.parametrize("param_format", [0, 1], ids=["f16_params", "bf16_params"])
+@pytest.mark.parametrize("shape", WIDE_V)
+def test_decode_tolerance_with_wide_value_groups(shape, param_format):
+    """Value groups spanning 20 to 45 (a quarter of the V channels multiplied by 8) and contexts of 3 to 20 tokens,
+    twenty draws: an output is then a handful of products p * s * c with c * s up to the group's range, and nothing
+    averages their rounding out.  With p * s in one binary16 term the error reaches 2^-12 of the range (1e-2 here);
+    the kernel carries it in two terms."""
+    Hq, Hkv, D = shape
+    Dk, Dv = D if isinstance(D, tuple) else (D, D)
+    lens = (5, 3, 9, 20)
+    for seed in range(200, 220):
+        w = synth.small(seed, 1, Hq, Hkv, Dk, Dv, False, lens, wide_v=True)
+        spec, kpool, vpool, table, table_d = gpu_cache(w, param_format=param_format)
+        ospec, okp, ovp, otable = host_cache(w, param_format=param_format)
+        got = run_gpu(w, spec, kpool, vpool, table_d, list(lens))
+        want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, list(lens), w.sm_scale)
+        assert_close(got, want, f"{shape} seed {seed} format {param_format}")
+    # and a longer context with the same values (several tiles, two waves meeting in a unit)
+    w = synth.small(221, 1, Hq, Hkv, Dk, Dv, False, (700, 130), wide_v=True)
+    spec, kpool, vpool, table, table_d = gpu_cache(w, param_format=param_format)
+    ospec, okp, ovp, otable = host_cache(w, param_format=param_format)
+    got = run_gpu(w, spec, kpool, vpool, table_d, list(w.seq_lens), split_tokens=256)
+    want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, list(w.seq_lens), w.sm_scale)
+    assert_close(got, want, f"{shape} long format {param_format}")
