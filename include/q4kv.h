@@ -161,7 +161,30 @@ int q4kv_batched_attention_windows(const q4kv_spec *spec, const q4kv_pool *k, co
                                    int32_t layer_begin, int32_t layer_end, void *workspace, size_t workspace_bytes,
                                    void *hip_stream);
 
-/* Bytes of workspace q4kv_batched_attention needs for these arguments (0 on bad arguments). */
+/* For callers that cannot allocate device memory or have none to hand over -- code recording a HIP graph, tight
+ * serving loops that call once per layer, harnesses that forbid hipMalloc: q4kv_batched_attention with the decode
+ * path's workspace (tile plan and partial results) taken from a fixed array of Q4KV_STATIC_SCRATCH_BYTES bytes that
+ * the library's code object holds on every GPU it is loaded on, from the first use of the library on that GPU until
+ * the process ends.  No workspace arguments; everything else, q and out (caller-owned device memory) included, is as
+ * for q4kv_batched_attention, and the results are bit-identical to that call with the same split_tokens.
+ *   - The call allocates nothing and frees nothing, on the device or through any library.  The first call on a
+ *     device looks the array's address up once (with that device current, as for every call); make that first call
+ *     outside a graph capture.
+ *   - q4kv_attention_workspace_bytes(...) > Q4KV_STATIC_SCRATCH_BYTES -> Q4KV_EWORKSPACE, nothing is launched: pass
+ *     fewer layers per call (one layer of every benchmark configuration fits: at most 11 MB) or a larger split_tokens.
+ *   - Every call on a GPU shares that GPU's one array, which keeps the last call's contents (nothing in it has to
+ *     start at zero that the call's own first kernel does not write): calls that overlap in time on one GPU, on
+ *     different streams or from different threads, race on it and are not allowed.  Calls on one stream are ordered
+ *     by the stream. */
+#define Q4KV_STATIC_SCRATCH_BYTES (16u << 20)
+int q4kv_batched_attention_static(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                                  uint16_t *out, const int32_t *block_table, int32_t max_blocks,
+                                  const int32_t *seq_len, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                  float sm_scale, int32_t window, int32_t split_tokens, int32_t layer_begin,
+                                  int32_t layer_end, void *hip_stream);
+
+/* Bytes of workspace q4kv_batched_attention needs for these arguments.  0 on bad arguments (q4kv_last_error() then
+ * holds a message) and for q_len > 1, where the chunk kernel keeps everything on chip and needs no workspace. */
 size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
                                       int32_t split_tokens, int32_t num_layers_in_call);
 

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libq4kv.so")
 
 EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_quantize_fmt", "q4kv_dequantize_fmt", "q4kv_append", "q4kv_batched_attention",
-           "q4kv_batched_attention_windows", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_block_image_bytes", "q4kv_export_blocks", "q4kv_import_blocks", "q4kv_read_probe",
+           "q4kv_batched_attention_windows", "q4kv_batched_attention_static", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_block_image_bytes", "q4kv_export_blocks", "q4kv_import_blocks", "q4kv_read_probe",
            "q4kv_block_pool_create", "q4kv_block_pool_destroy", "q4kv_block_pool_reserve", "q4kv_block_pool_release",
            "q4kv_block_pool_blocks", "q4kv_block_pool_table_row", "q4kv_block_pool_touch", "q4kv_block_pool_pin",
            "q4kv_block_pool_lru_victim", "q4kv_block_pool_free_blocks", "q4kv_block_pool_owner",
@@ -65,6 +65,8 @@ def lib():
         l.q4kv_batched_attention_windows.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp,
                                                      i32, vp, i32, i32, i32, C.c_float, C.POINTER(i32), i32, i32, i32,
                                                      vp, C.c_size_t, vp]
+        l.q4kv_batched_attention_static.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32,
+                                                    vp, i32, i32, i32, C.c_float, i32, i32, i32, i32, vp]
         l.q4kv_attention_workspace_bytes.restype = C.c_size_t
         l.q4kv_attention_workspace_bytes.argtypes = [C.POINTER(Spec), i32, i32, i32, i32, i32]
         l.q4kv_default_split_tokens.restype = i32
@@ -321,4 +323,22 @@ def q4kv_batched_attention(spec, kpool, vpool, q, block_table, seq_len, max_seq_
         _check(lib().q4kv_batched_attention_windows(*common, windows, *tail))
     else:
         _check(lib().q4kv_batched_attention(*common, int(window), *tail))
+    return out
+
+
+STATIC_SCRATCH_BYTES = 16 << 20   # Q4KV_STATIC_SCRATCH_BYTES
+
+
+def q4kv_batched_attention_static(spec, kpool, vpool, q, out, block_table, seq_len, max_seq_len, sm_scale, window=0,
+                                  split_tokens=0, layer_begin=0, layer_end=None):
+    """q4kv_batched_attention_static: the decode path's workspace comes from the library's fixed per-GPU array.
+    Allocates no tensor: `out` (fp16 [layers_in_call][A][q_len][q_heads][v_dim]) is the caller's."""
+    layer_end = spec.num_layers if layer_end is None else layer_end
+    kp = kpool.c()
+    vp = None if spec.v_aliases_k else vpool.c()
+    _check(lib().q4kv_batched_attention_static(
+        C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp), _dev(q, torch.float16, "q"),
+        _dev(out, torch.float16, "out"), _dev(block_table, torch.int32, "block_table"), block_table.shape[1],
+        _dev(seq_len, torch.int32, "seq_len"), q.shape[1], q.shape[2], max_seq_len, float(sm_scale), int(window),
+        int(split_tokens), layer_begin, layer_end, _stream()))
     return out

@@ -9,6 +9,11 @@
 
 #include "q4kv_internal.h"
 
+// Workspace of q4kv_batched_attention_static: one copy per GPU inside the loaded code object, never allocated or
+// freed.  In host code this name is only a handle for hipGetSymbolAddress; the device address it yields (one per
+// device) is what kernels and host calls are given.
+static __device__ __align__(256) unsigned char scratch[Q4KV_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_error[256] = "";
@@ -317,6 +322,52 @@ int q4kv_batched_attention_windows(const q4kv_spec *spec, const q4kv_pool *k, co
         return fail(Q4KV_EINVAL, "at most %d layers per call with per-layer windows", q4kv::max_window_layers());
     return attention_common(spec, k, v, q, out, block_table, max_blocks, seq_len, num_agents, q_len, max_seq_len, sm_scale,
                             0, window_per_layer, split_tokens, layer_begin, layer_end, workspace, workspace_bytes,
+                            hip_stream);
+}
+
+// Device address of `scratch` on the current device, looked up once per device (threads that race here store the
+// same value).  nullptr with the error message set when the runtime cannot resolve it.
+static void *static_scratch()
+{
+    static std::atomic<void *> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        fail(Q4KV_EHIP, "no current device (or a device index above 63)");
+        return nullptr;
+    }
+    void *ptr = cached[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            fail(Q4KV_EHIP, "address of the static scratch array on device %d: %s", dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        cached[dev].store(ptr, std::memory_order_release);
+    }
+    return ptr;
+}
+
+int q4kv_batched_attention_static(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                                  uint16_t *out, const int32_t *block_table, int32_t max_blocks,
+                                  const int32_t *seq_len, int32_t num_agents, int32_t q_len, int32_t max_seq_len,
+                                  float sm_scale, int32_t window, int32_t split_tokens, int32_t layer_begin,
+                                  int32_t layer_end, void *hip_stream)
+{
+    // the size first, from host arithmetic alone: a call that does not fit launches nothing and touches no device state
+    if (spec && num_agents > 0 && q_len == 1 && max_seq_len >= 0 && layer_end > layer_begin && split_tokens >= 0 &&
+        split_tokens % 256 == 0 && check_spec(spec) == Q4KV_OK) {
+        const size_t need =
+            q4kv_attention_workspace_bytes(spec, num_agents, q_len, max_seq_len, split_tokens, layer_end - layer_begin);
+        if (need > (size_t)Q4KV_STATIC_SCRATCH_BYTES)
+            return fail(Q4KV_EWORKSPACE,
+                        "the call needs %zu bytes of workspace, the static scratch array holds %u: pass fewer layers "
+                        "per call or a larger split_tokens, or use q4kv_batched_attention with a workspace",
+                        need, (unsigned)Q4KV_STATIC_SCRATCH_BYTES);
+    }
+    void *ptr = static_scratch();
+    if (!ptr) return Q4KV_EHIP;
+    return attention_common(spec, k, v, q, out, block_table, max_blocks, seq_len, num_agents, q_len, max_seq_len, sm_scale,
+                            window, nullptr, split_tokens, layer_begin, layer_end, ptr, (size_t)Q4KV_STATIC_SCRATCH_BYTES,
                             hip_stream);
 }
 
