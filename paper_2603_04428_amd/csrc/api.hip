@@ -104,6 +104,12 @@ size_t plan_bytes(int num_agents, int layers)
     return (q4kv::decode_plan_ints(num_agents, layers) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
+// arrival counters, one per (layer, KV head, agent)
+size_t arrival_bytes(const q4kv_spec &s, int num_agents, int layers)
+{
+    return ((size_t)layers * s.num_kv_heads * num_agents * sizeof(int32_t) + 255) / 256 * 256;
+}
+
 } // namespace
 
 extern "C" {
@@ -220,7 +226,8 @@ size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents,
     const int st = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
     const int64_t slots = slots_per_unit(max_seq_len, st);
     const int64_t units = (int64_t)num_layers_in_call * num_agents * q_len * spec->num_q_heads;
-    return plan_bytes(num_agents, num_layers_in_call) + (size_t)(units * slots * (spec->v_dim + 2) * (int64_t)sizeof(float));
+    return plan_bytes(num_agents, num_layers_in_call) + arrival_bytes(*spec, num_agents, num_layers_in_call) +
+           (size_t)(units * slots * (spec->v_dim + 2) * (int64_t)sizeof(float));
 }
 
 static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
@@ -292,11 +299,12 @@ static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4k
         return fail(Q4KV_EWORKSPACE, "workspace needs %zu bytes (16-byte aligned), got %zu", need, workspace_bytes);
     const int64_t units = (int64_t)layers * num_agents * q_len * spec->num_q_heads;
     a.plan = static_cast<int32_t *>(workspace);
-    a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents, layers));
+    a.arrivals = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + plan_bytes(num_agents, layers));
+    a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents, layers) +
+                                           arrival_bytes(*spec, num_agents, layers));
     a.part_ml = a.part_acc + units * a.max_slots * spec->v_dim;
 
     hipError_t e = mla ? q4kv::launch_mla_decode_attention(a, st) : q4kv::launch_decode_attention(a, st);
-    if (e == hipSuccess) e = q4kv::launch_combine(a, st);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));
 }
 

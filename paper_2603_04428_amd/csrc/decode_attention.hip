@@ -67,8 +67,8 @@ struct DecodeParams {
     const uint16_t *k_scale, *k_bias, *v_scale, *v_bias;
     const uint16_t *q;
     StreamParams stream;
-    float *part_acc, *part_ml;
-    int q_heads, max_slots;
+    MergeParams merge;
+    int q_heads;
     float score_scale;             // sm_scale * log2(e): scores are kept in log2 units
 };
 
@@ -81,12 +81,18 @@ struct LayerWindows {
     int w[kMaxWindowLayers];
 };
 
-// One workgroup.  total_waves = waves of the attention launch.  Writes the plan described in stream_k.h.
+// total_waves = waves of the attention launch.  Workgroup 0 writes the plan described in stream_k.h; all workgroups
+// of the launch share the clearing of the arrival counters (one per (layer, KV head, agent) unit).
 __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restrict__ seq_len, int num_agents,
                                                         int max_seq_len, const LayerWindows lw, int layers,
                                                         int kv_heads, int total_waves, int min_tiles_per_wave,
-                                                        int32_t *__restrict__ plan)
+                                                        int32_t *__restrict__ plan, int32_t *__restrict__ arrivals)
 {
+    {
+        const int counters = layers * kv_heads * num_agents; // the host keeps this below 2^31
+        for (int i = blockIdx.x * kThreads + threadIdx.x; i < counters; i += gridDim.x * kThreads) arrivals[i] = 0;
+        if (blockIdx.x != 0) return;
+    }
     __shared__ int s_wave_sum[kWaves];
     __shared__ int s_cls[kMaxWindowLayers], s_win[kMaxWindowLayers], s_tt[kMaxWindowLayers], s_classes;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -142,7 +148,35 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
         const int first = (window > 0 && n > window) ? n - window : 0;
         return first & ~(kWave - 1);
     };
-    for (int a = a0; a < a1; ++a) nlen[a] = length(a);
+    int empties = 0;
+    for (int a = a0; a < a1; ++a) {
+        const int n = length(a);
+        nlen[a] = n;
+        empties += n == 0 ? 1 : 0;
+    }
+    { // ---- agents without a visible token, in index order
+        int incl = empties;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
+        }
+        if (lane == kWave - 1) s_wave_sum[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const int t = s_wave_sum[w];
+            if (w < wave) before += t;
+            total += t;
+        }
+        __syncthreads(); // s_wave_sum is free again
+        if (tid == 0) plan[4] = total;
+        int at = before + incl - empties;
+        int32_t *empty = plan + pv.empty_off();
+        for (int a = a0; a < a1; ++a)
+            if (length(a) == 0) empty[at++] = a;
+    }
     // ---- per class: first visible tile and tile count of every agent, prefix sum over the agents
     for (int c = 0; c < C; ++c) {
         const int cb = pv.class_off(c);
@@ -356,6 +390,7 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     const int gw = blockIdx.x * kWaves + wave; // this wave's index in the launch
 
     const TileStream ts_(p.stream);
+    zero_empty_units<DV>(ts_.pv, p.merge.out, p.q_heads, gw, gridDim.x * kWaves, lane);
     const int per = ts_.per, N = ts_.N;
     const long long x_begin = (long long)gw * per;
     if (x_begin >= N) return;
@@ -629,7 +664,8 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 
         if (unit_ends) {
             // ---- this wave's share of the unit is complete: fold token slots and lanes through LDS (fixed
-            // order) and write one partial per query head into the slot this wave has in the unit
+            // order).  A unit that no other wave shares is normalised and written out; otherwise one partial per
+            // query head goes into the slot this wave has in the unit, and the wave that arrives last merges them
             float *fin_acc = region;                      // [VTPS][NREP][DV]
             float *fin_pb = region + VTPS * NREP * DV;    // [NREP][GV]
             float lsum[NREP];
@@ -648,100 +684,42 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                 }
             }
             wave_lds_sync();
-            const int slot = ts_.slot_of(cur, gw);
+            int slot, slots;
+            ts_.slot_of(cur, gw, slot, slots);
+            const bool alone = slots == 1;
 #pragma unroll
             for (int r = 0; r < NREP; ++r) {
-                const int64_t rec = (unit0 + r) * p.max_slots + slot;
+                const int64_t rec = (unit0 + r) * p.merge.max_slots + slot;
+                const float inv = lsum[r] > 0.0f ? 1.0f / lsum[r] : 0.0f;
 #pragma unroll
                 for (int e0 = 0; e0 < DV; e0 += kWave) {
                     const int e = e0 + lane;
                     float o = fin_pb[r * GV + e / kGroup];
 #pragma unroll
                     for (int sl = 0; sl < VTPS; ++sl) o += fin_acc[(sl * NREP + r) * DV + e];
-                    p.part_acc[rec * DV + e] = o;
+                    if (alone) p.merge.out[(unit0 + r) * DV + e] = float_to_half_bits(o * inv);
+                    else record_store(p.merge.part_acc + rec * DV + e, o);
                 }
-                if (lane == 0) {
-                    p.part_ml[rec * 2] = m_run[r];
-                    p.part_ml[rec * 2 + 1] = lsum[r];
+                if (!alone && lane == 0) {
+                    record_store(p.merge.part_ml + rec * 2, m_run[r]);
+                    record_store(p.merge.part_ml + rec * 2 + 1, lsum[r]);
                 }
             }
             wave_lds_sync();
+            if (!alone) {
+                int32_t *counter = p.merge.arrivals + ((int64_t)cur.li * p.stream.kv_heads + cur.kvh) * p.stream.num_agents + cur.agent;
+                if (arrive_last(counter, slots, lane)) {
+                    for (int r = 0; r < NREP; ++r) {
+                        const int64_t rec0 = (unit0 + r) * p.merge.max_slots;
+                        merge_head<DV>(p.merge.part_acc + rec0 * DV, p.merge.part_ml + rec0 * 2, slots,
+                                       p.merge.out + (unit0 + r) * DV, lane);
+                    }
+                }
+            }
         }
         unit_begins = unit_ends;
         cur = nxt;
     }
-}
-
-// Merge the partials of every (layer, agent, query head) in slot order: binary32, output binary16.  A thread owns
-// four consecutive output elements of one head (16-byte loads); v_dim / 4 threads share a head.
-__global__ __launch_bounds__(kThreads) void combine_kernel(const float *__restrict__ part_acc,
-                                                           const float *__restrict__ part_ml,
-                                                           const int32_t *__restrict__ plan, uint16_t *__restrict__ out,
-                                                           int q_heads, int kv_heads, int num_agents, int v_dim,
-                                                           int max_slots, int layers, long long units)
-{
-    const int threads_per_unit = v_dim / 4;
-    const long long unit = (long long)blockIdx.x * (kThreads / threads_per_unit) + threadIdx.x / threads_per_unit;
-    if (unit >= units) return; // (layer in call, agent, query head)
-    const int e = (threadIdx.x % threads_per_unit) * 4;
-    const int qh = (int)(unit % q_heads);
-    const int agent = (int)((unit / q_heads) % num_agents);
-    const int li = (int)(unit / ((long long)q_heads * num_agents));
-    const int kvh = qh / (q_heads / kv_heads);
-    PlanView pv;
-    pv.plan = plan;
-    pv.A = num_agents;
-    pv.L = layers;
-    const int per = plan[1];
-    const int cb = pv.layer_class_off(li);
-    const int32_t *tpre = pv.tpre(cb);
-    const int tiles = tpre[agent + 1] - tpre[agent];
-    int slots = 0;
-    if (tiles > 0) {
-        const long long u0 = (long long)plan[pv.lt_off() + li] + (long long)kvh * pv.tiles_per_head(cb) + tpre[agent];
-        slots = (int)((u0 + tiles - 1) / per - u0 / per) + 1;
-    }
-    const float *ml = part_ml + unit * max_slots * 2;
-    const float *acc = part_acc + unit * max_slots * v_dim + e;
-    // Four slots at a time: every load of a group is issued before anything is computed, so a unit costs one
-    // memory round trip per group instead of two dependent ones per slot.  The running reference moves group by
-    // group (with at most four slots: exactly the maximum over all slots, then one weighted sum in slot order).
-    float m = kNegBig, denom = 0.0f;
-    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    for (int s0 = 0; s0 < slots; s0 += 4) {
-        float mm[4], ll[4];
-        float4 a[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const bool in = s0 + k < slots;
-            const float2 t = in ? *reinterpret_cast<const float2 *>(ml + 2 * (s0 + k)) : make_float2(kNegBig, 0.0f);
-            mm[k] = t.x;
-            ll[k] = t.y;
-            a[k] = in ? *reinterpret_cast<const float4 *>(acc + (long long)(s0 + k) * v_dim) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        }
-        float m_new = m;
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (ll[k] > 0.0f) m_new = fmaxf(m_new, mm[k]);
-        const float keep = __builtin_amdgcn_exp2f(m - m_new); // 1 when the reference stays, 0 while nothing was added yet
-        denom *= keep;
-        o.x *= keep; o.y *= keep; o.z *= keep; o.w *= keep;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (!(ll[k] > 0.0f)) continue;
-            const float wgt = __builtin_amdgcn_exp2f(mm[k] - m_new);
-            denom = fmaf(wgt, ll[k], denom);
-            o.x = fmaf(wgt, a[k].x, o.x);
-            o.y = fmaf(wgt, a[k].y, o.y);
-            o.z = fmaf(wgt, a[k].z, o.z);
-            o.w = fmaf(wgt, a[k].w, o.w);
-        }
-        m = m_new;
-    }
-    const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
-    const uint32_t lo = (uint32_t)float_to_half_bits(o.x * inv) | ((uint32_t)float_to_half_bits(o.y * inv) << 16);
-    const uint32_t hi = (uint32_t)float_to_half_bits(o.z * inv) | ((uint32_t)float_to_half_bits(o.w * inv) << 16);
-    *reinterpret_cast<uint2 *>(out + unit * v_dim + e) = make_uint2(lo, hi);
 }
 
 template <int DK, int DV, int NREP>
@@ -752,9 +730,8 @@ hipError_t launch_decode_t(const AttentionArgs &a, hipStream_t stream)
     p.v_codes = a.v.codes; p.v_scale = a.v.scale; p.v_bias = a.v.bias;
     p.q = a.q;
     p.stream = stream_params(a);
-    p.part_acc = a.part_acc; p.part_ml = a.part_ml;
+    p.merge = merge_params(a);
     p.q_heads = a.spec.num_q_heads;
-    p.max_slots = a.max_slots;
     p.score_scale = a.sm_scale * kLog2e;
     if (a.spec.param_format == Q4KV_PARAMS_BF16)
         hipLaunchKernelGGL((decode_attention_kernel<DK, DV, NREP, true>), dim3(a.grid_workgroups), dim3(kThreads), 0, stream, p);
@@ -791,14 +768,29 @@ StreamParams stream_params(const AttentionArgs &a)
     return s;
 }
 
+MergeParams merge_params(const AttentionArgs &a)
+{
+    MergeParams m;
+    m.part_acc = a.part_acc;
+    m.part_ml = a.part_ml;
+    m.arrivals = a.arrivals;
+    m.out = a.out;
+    m.max_slots = a.max_slots;
+    return m;
+}
+
 hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream)
 {
     LayerWindows lw;
     lw.uniform = a.layer_window == nullptr;
     lw.window = a.window;
     for (int i = 0; i < kMaxWindowLayers; ++i) lw.w[i] = (!lw.uniform && i < a.layers_in_call) ? a.layer_window[i] : 0;
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len, lw,
-                       a.layers_in_call, a.spec.num_kv_heads, a.grid_workgroups * kWaves, a.split_tokens / kWave, a.plan);
+    // workgroup 0 plans; one more per 8,192 arrival counters (at most 256) helps clearing them
+    const int64_t counters = (int64_t)a.layers_in_call * a.spec.num_kv_heads * a.num_agents;
+    const int helpers = (int)(counters / 8192 < 256 ? counters / 8192 : 256);
+    hipLaunchKernelGGL(plan_kernel, dim3(1 + helpers), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len,
+                       lw, a.layers_in_call, a.spec.num_kv_heads, a.grid_workgroups * kWaves, a.split_tokens / kWave,
+                       a.plan, a.arrivals);
     return hipGetLastError();
 }
 
@@ -829,18 +821,6 @@ hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
     case 256: return launch_decode_d<256, 256>(a, n_rep, stream);
     default: return hipErrorInvalidValue;
     }
-}
-
-hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream)
-{
-    const int64_t units = (int64_t)a.layers_in_call * a.num_agents * a.q_len * a.spec.num_q_heads;
-    if (units == 0) return hipSuccess;
-    const int units_per_block = kThreads / (a.spec.v_dim / 4); // v_dim is a multiple of 64 and at most 1,024 here
-    const int64_t blocks = (units + units_per_block - 1) / units_per_block;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, a.part_acc, a.part_ml, a.plan,
-                       a.out, a.spec.num_q_heads, a.spec.num_kv_heads, a.num_agents, a.spec.v_dim, a.max_slots,
-                       a.layers_in_call, (long long)units);
-    return hipGetLastError();
 }
 
 } // namespace q4kv

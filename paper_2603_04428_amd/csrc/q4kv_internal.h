@@ -34,10 +34,13 @@ struct AttentionArgs {
     int32_t *plan;              // workspace: tile plan written by the plan kernel
     float *part_acc;            // workspace: [units][max_slots][v_dim]
     float *part_ml;             // workspace: [units][max_slots][2]  (running max in log2 units, denominator)
+    int32_t *arrivals;          // workspace: [layers_in_call][kv_heads][num_agents] waves that have left a unit
 };
 
 struct StreamParams;
+struct MergeParams;
 StreamParams stream_params(const AttentionArgs &a);
+MergeParams merge_params(const AttentionArgs &a);
 hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream);   // needs grid_workgroups, split_tokens, plan
 
 // true when a decode (q_len == 1) kernel exists for these head shapes
@@ -46,10 +49,8 @@ int decode_waves_per_workgroup();
 size_t decode_plan_ints(int num_agents, int layers);
 int max_window_layers();   // layers per call when every layer brings its own window
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);
-hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream);
 
-// shared-latent decode (V is a prefix of K, 16 query heads per latent head): plan + attention; the partials are
-// merged by launch_combine like the GQA ones
+// shared-latent decode (V is a prefix of K, 16 query heads per latent head): plan + attention
 bool mla_decode_supported(const q4kv_spec &spec);
 hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t stream);
 

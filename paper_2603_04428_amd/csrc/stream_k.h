@@ -3,8 +3,10 @@
 // All (layer in call, KV head, agent) units are cut into 64-token tiles and numbered consecutively (layer-major,
 // then KV head, then agent); a fixed launch of waves owns equal contiguous tile ranges.  plan_kernel turns
 // seq_len[] into per-agent tile prefix sums on the device; a Cursor walks a wave's range with scalar arithmetic,
-// touching memory only where a unit or a 256-token block begins; combine_kernel merges the partial results
-// that the waves meeting in one unit leave behind.
+// touching memory only where a unit or a 256-token block begins.  A unit that lies inside one wave's range is
+// finished by that wave.  Waves that meet in a unit each leave a partial result (un-normalised sums, running
+// maximum, denominator) in the unit's slot for them and count themselves in on the unit's arrival counter; the
+// one that arrives last merges all slots, in slot order whoever it is, so results do not depend on timing.
 #pragma once
 #include "q4_device.h"
 
@@ -18,7 +20,9 @@ namespace q4kv {
 //   C_max = L class blocks of 2A + 2 ints:  window (0 = global), tpre[A + 1] (tile prefix sum over agents, tpre[A] =
 //                tiles of one (layer, KV head) of the class), tstart[A] (first visible token rounded down to a tile)
 //   nlen[A]      seq_len clamped to [0, max_seq_len]
-constexpr int kPlanHeader = 4;
+//   [4] E = agents without a visible token; empty[A]: their indices (first E entries) -- no wave visits their
+//                units, their output rows are zeroed by the attention launch before anything else
+constexpr int kPlanHeader = 5;
 constexpr int kMaxWindowLayers = 128; // layers per call when every layer brings its own window
 
 struct PlanView {
@@ -26,13 +30,14 @@ struct PlanView {
     int A, L;
     __device__ __host__ __forceinline__ static size_t ints(int A, int L)
     {
-        return (size_t)kPlanHeader + 2 * (size_t)L + 1 + (size_t)L * (2 * (size_t)A + 2) + (size_t)A;
+        return (size_t)kPlanHeader + 2 * (size_t)L + 1 + (size_t)L * (2 * (size_t)A + 2) + 2 * (size_t)A;
     }
     __device__ __forceinline__ int class_stride() const { return 2 * A + 2; }
     __device__ __forceinline__ int lt_off() const { return kPlanHeader; }
     __device__ __forceinline__ int cls_off() const { return kPlanHeader + L + 1; }
     __device__ __forceinline__ int class_off(int c) const { return kPlanHeader + 2 * L + 1 + c * class_stride(); }
     __device__ __forceinline__ int nlen_off() const { return class_off(L); }
+    __device__ __forceinline__ int empty_off() const { return nlen_off() + A; }
     __device__ __forceinline__ int layer_class_off(int li) const { return class_off(plan[cls_off() + li]); }
     // inside a class block
     __device__ __forceinline__ int window(int cb) const { return plan[cb]; }
@@ -178,14 +183,126 @@ struct TileStream {
         return c;
     }
 
-    // index of the partial record that wave `gw` writes for the unit the cursor is in
+    // index of the partial record that wave `gw` writes for the unit the cursor is in, and how many waves meet in
+    // that unit (= records to merge)
     template <typename C>
-    __device__ __forceinline__ int slot_of(const C &c, int gw) const
+    __device__ __forceinline__ void slot_of(const C &c, int gw, int &slot, int &slots) const
     {
         const int unit_first_tile =
             pv.plan[pv.lt_off() + c.li] + c.kvh * pv.tiles_per_head(c.cb) + pv.tpre(c.cb)[c.agent];
-        return gw - unit_first_tile / per;
+        const int first_wave = unit_first_tile / per;
+        slot = gw - first_wave;
+        slots = (unit_first_tile + c.tiles - 1) / per - first_wave + 1;
     }
 };
+
+// ---------------------------------------------------------------------------------------------- merging a unit
+
+constexpr float kMergeNegBig = -1.0e30f;
+
+struct MergeParams {
+    float *part_acc;    // [query-head unit][max_slots][DV] un-normalised sums
+    float *part_ml;     // [query-head unit][max_slots][2]  running maximum (log2 units), denominator
+    int32_t *arrivals;  // [layer in call][kv head][agent], zeroed by the plan kernel
+    uint16_t *out;      // [query-head unit][DV] binary16
+    int max_slots;
+};
+
+// Rows of agents that have no visible token: zeros.  Every wave of the launch takes its share before it looks
+// for tiles (waves without tiles included); a call without such agents pays one scalar load.
+template <int DV>
+__device__ __forceinline__ void zero_empty_units(const PlanView &pv, uint16_t *out, int q_heads, int gw, int total_waves,
+                                                 int lane)
+{
+    const int E = pv.plan[4];
+    if (E == 0) return;
+    const int32_t *empty = pv.plan + pv.empty_off();
+    const int rows = pv.L * E * q_heads;
+    for (int i = gw; i < rows; i += total_waves) {
+        const int h = i % q_heads, ea = (i / q_heads) % E, li = i / (q_heads * E);
+        uint16_t *row = out + (((int64_t)li * pv.A + empty[ea]) * q_heads + h) * DV;
+        for (int e = 2 * lane; e < DV; e += 2 * kWave) *reinterpret_cast<uint32_t *>(row + e) = 0u;
+    }
+}
+
+// Partial records are exchanged between waves on different compute dies, whose second-level caches are not kept
+// coherent with each other inside a kernel.  A device-wide release / acquire fence pair would do (write the whole
+// cache back, drop it on the other side), but costs tens of microseconds per fence on this chip (measured: the
+// 48-layer decode call went from 0.76 to 0.93 ms).  Instead every access to a record is itself a device-scope access:
+// such a store goes through to memory, such a load does not take a cached copy, and nothing else has to move.
+__device__ __forceinline__ void record_store(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float record_load(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Counts this wave in on a unit whose partial record it has just written with record_store; true for the wave that
+// arrives last, which may then read every record of the unit with record_load.  Lane 0 counts only after the
+// record stores of all lanes have been acknowledged (they are issued by the same wave, in order, before the wait).
+__device__ __forceinline__ bool arrive_last(int32_t *counter, int slots, int lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); // the compiler keeps the record stores above this point
+    __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): they have reached memory
+    int old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront"); // and the record loads below it
+    return old == slots - 1;
+}
+
+// Merge the `slots` partial records of one query head and write its output row: binary32, slot order, output
+// binary16.  A lane owns elements lane, lane + 64, ...  Records whose denominator is zero (every token of the
+// wave's share was masked) are skipped; a head with nothing at all yields zeros.
+// A record load is a trip to memory, so loads are issued in batches of 32 / (DV / 64) records (32 loads in flight
+// per lane) together with the batch's maxima and denominators, and only then used: a unit of up to that many
+// records costs one round trip per head.  The reference maximum moves from batch to batch like a running maximum.
+template <int DV>
+__device__ __forceinline__ void merge_head(const float *acc, const float *ml, int slots, uint16_t *out_row, int lane)
+{
+    constexpr int CH = DV / kWave; // 1, 2, 4 or 8 elements per lane
+    static_assert(CH == 1 || CH == 2 || CH == 4 || CH == 8, "row width");
+    constexpr int B = 32 / CH;     // records per batch
+    float o[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) o[i] = 0.0f;
+    float m_ref = kMergeNegBig, denom = 0.0f;
+    for (int s0 = 0; s0 < slots; s0 += B) {
+        const int count = slots - s0 < B ? slots - s0 : B;
+        const int s = s0 + (lane < count ? lane : count - 1);
+        const float m_s = record_load(ml + 2 * s);
+        const float l_s = lane < count ? record_load(ml + 2 * s + 1) : 0.0f;
+        float v[B][CH];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const int k = j < count ? j : count - 1; // repeats of the batch's last record carry weight zero
+            const float *row = acc + (int64_t)(s0 + k) * DV + lane;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) v[j][c] = record_load(row + c * kWave);
+        }
+        const float m_new = fmaxf(m_ref, wave_max(l_s > 0.0f ? m_s : kMergeNegBig));
+        const float keep = __builtin_amdgcn_exp2f(m_ref - m_new); // 1 when the reference stays; 0 * 0 while nothing was added
+        m_ref = m_new;
+        denom *= keep;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) o[c] *= keep;
+        const float w = l_s > 0.0f ? __builtin_amdgcn_exp2f(m_s - m_ref) : 0.0f;
+        const float wl = w * l_s;
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            if (j < count) { // wave-uniform
+                const float wk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), j));
+                denom += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), j));
+#pragma unroll
+                for (int c = 0; c < CH; ++c) o[c] = fmaf(wk, v[j][c], o[c]);
+            }
+        }
+    }
+    const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) out_row[c * kWave + lane] = float_to_half_bits(o[c] * inv);
+}
 
 } // namespace q4kv
