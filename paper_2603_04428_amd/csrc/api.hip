@@ -86,17 +86,30 @@ int attention_workgroups(const q4kv_spec &s) { return (q4kv::mla_decode_supporte
 int pick_split_tokens(const q4kv_spec &s, int num_agents, int max_seq_len, int layers)
 {
     const long long tiles = (long long)layers * s.num_kv_heads * num_agents * ((max_seq_len + 63) / 64);
-    const long long waves = (long long)attention_workgroups(s) * q4kv::decode_waves_per_workgroup();
-    long long blocks = tiles / waves / 2; // 2 * (tiles / waves) tiles, in 256-token blocks of 4 tiles
+    // the workers that share the tiles out: workgroups, or single waves for the shared-latent kernel
+    const long long workers =
+        (long long)attention_workgroups(s) * (q4kv::mla_decode_supported(s) ? q4kv::decode_waves_per_workgroup() : 1);
+    long long blocks = tiles / workers / 2; // 2 * (tiles / workers) tiles, in 256-token blocks of 4 tiles
     if (blocks < 1) blocks = 1;
     if (blocks > 2) blocks = 2;
     return (int)blocks * 256;
 }
 
-int slots_per_unit(int max_seq_len, int split_tokens)
+// Partial records reserved per (layer, agent, query head): the most workers that can meet in one unit.  A worker's
+// range is at least split_tokens long.  The GQA kernel's workers are workgroups, except that from a certain range
+// length on (decode_solo_quarter_tiles() * 4) every wave takes a quarter of its workgroup's range and writes a record
+// of its own.
+int slots_per_unit(const q4kv_spec &s, int max_seq_len, int split_tokens)
 {
-    const int tiles = (max_seq_len + 63) / 64, min_per_wave = split_tokens / 64;
-    return (tiles + min_per_wave - 1) / min_per_wave + 1;
+    const int tiles = (max_seq_len + 63) / 64, min_per = split_tokens / 64;
+    int slots = (tiles + min_per - 1) / min_per + 1;
+    if (!q4kv::mla_decode_supported(s)) {
+        int quarter = min_per / 4;
+        if (quarter < q4kv::decode_solo_quarter_tiles()) quarter = q4kv::decode_solo_quarter_tiles();
+        const int solo = (tiles + quarter - 1) / quarter + 1;
+        if (solo > slots) slots = solo;
+    }
+    return slots;
 }
 
 size_t plan_bytes(int num_agents, int layers)
@@ -224,7 +237,7 @@ size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents,
     }
     if (q_len > 1) return 0; // the chunk kernel keeps everything on chip
     const int st = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
-    const int64_t slots = slots_per_unit(max_seq_len, st);
+    const int64_t slots = slots_per_unit(*spec, max_seq_len, st);
     const int64_t units = (int64_t)num_layers_in_call * num_agents * q_len * spec->num_q_heads;
     return plan_bytes(num_agents, num_layers_in_call) + arrival_bytes(*spec, num_agents, num_layers_in_call) +
            (size_t)(units * slots * (spec->v_dim + 2) * (int64_t)sizeof(float));
@@ -275,7 +288,7 @@ static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4k
     a.window = window;
     a.layer_window = layer_window;
     a.split_tokens = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, layers);
-    a.max_slots = slots_per_unit(max_seq_len, a.split_tokens);
+    a.max_slots = slots_per_unit(*spec, max_seq_len, a.split_tokens);
     a.grid_workgroups = attention_workgroups(*spec);
     a.layer_begin = layer_begin;
     a.layers_in_call = layers;

@@ -7,16 +7,23 @@
 // query heads of the group.  The design follows from keeping everything else under that stream:
 //
 //  * Work decomposition ("stream-K" over tokens).  All (layer, KV head, agent) units are cut into
-//    64-token tiles and numbered consecutively; the launch is a fixed set of waves (two workgroups
-//    per compute unit) and wave g owns the contiguous tile range [g*per, (g+1)*per).  Ragged context
-//    lengths therefore balance to within one tile, a wave's range usually lies inside one or two
-//    units, and every (unit, wave) intersection emits one un-normalised partial (acc[DV], running
-//    max m, denominator l) per query head.  A small plan kernel turns seq_len[] into the tile
-//    prefix sums first; a combine kernel merges each unit's partials in a fixed order afterwards, so
-//    results are run-to-run identical.
-//  * Waves never synchronise with each other: each walks its tiles with private online-softmax state
-//    and private LDS, and the next tile's loads (also across a unit boundary) are issued while the
-//    current tile is processed, so loads are always in flight.
+//    64-token tiles and numbered consecutively; the launch is a fixed set of workgroups (two per compute
+//    unit) and workgroup w owns the contiguous tile range [w*per, (w+1)*per), whose tiles its four waves
+//    take in turn (wave i: the range's tiles i, i+4, ...: inside a unit the four waves read one 256-token
+//    block together).  Ragged context lengths therefore balance to within a few tiles.  A small plan
+//    kernel turns seq_len[] into the tile prefix sums first.
+//  * Waves walk their tiles with private online-softmax state and private LDS, and the next tile's loads
+//    (also across a unit boundary) are issued while the current tile is processed, so loads are always
+//    in flight.  They meet only where a unit (or the workgroup's part of it) ends: each folds its state
+//    into one (sums, running maximum, denominator) per query head in LDS, and the four are merged there.
+//    A unit that lies inside one workgroup's range is normalised and written out at that point; a unit
+//    shared by several workgroups gets one un-normalised record per workgroup in the workspace, and the
+//    workgroup that arrives last (a counter per unit) merges the records, in record order whoever it is,
+//    so results are run-to-run identical.  A short call (one layer) thus keeps every wave busy with two
+//    or three tiles while a unit still has only a dozen records to merge.
+//  * A long call (a workgroup's range spans several units) gains nothing from that and would pay for the
+//    meetings: there every wave takes a contiguous quarter of the workgroup's range for itself, as if it
+//    were a workgroup of one -- the same segments, records and arrival counters, no barrier.
 //  * Codes never become integers or binary32: a nibble masked in place is a binary16 subnormal
 //    (c*2^-24 or c*2^-20) and goes straight into a matrix-core operand.
 //  * The affine part of the dequantization is factored out of the inner loops:
@@ -48,15 +55,11 @@
 namespace q4kv {
 namespace {
 
-#ifndef Q4KV_DEC_WAVES_PER_EU
-#define Q4KV_DEC_WAVES_PER_EU 2 // resident waves per SIMD the register budget is sized for
-#endif
-#ifndef Q4KV_DEC_PRIO_SHIFT
-#define Q4KV_DEC_PRIO_SHIFT 12 // log2 of the priority time slice in 10 ns ticks (0: waves keep the default priority)
-#endif
-#ifndef Q4KV_DEC_PRIO_LEVEL
-#define Q4KV_DEC_PRIO_LEVEL 2
-#endif
+constexpr int kWavesPerSimd = 2; // resident waves per SIMD the register budget is sized for
+constexpr int kPrioShift = 12;   // log2 of the priority time slice in 10 ns ticks (41 us)
+constexpr int kPrioLevel = 2;
+constexpr int kPrioMinTiles = 128; // tiles per workgroup from which the priority turns are taken
+constexpr int kCoopMaxTiles = 64;  // tiles per workgroup below which its four waves share every unit (else: a quarter each)
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr float kNegBig = -1.0e30f; // "minus infinity" that survives subtraction
@@ -81,12 +84,13 @@ struct LayerWindows {
     int w[kMaxWindowLayers];
 };
 
-// total_waves = waves of the attention launch.  Workgroup 0 writes the plan described in stream_k.h; all workgroups
+// total_waves = workers of the attention launch (workgroups, or waves for the shared-latent kernel).  Workgroup 0 writes the plan described in stream_k.h; all workgroups
 // of the launch share the clearing of the arrival counters (one per (layer, KV head, agent) unit).
 __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restrict__ seq_len, int num_agents,
                                                         int max_seq_len, const LayerWindows lw, int layers,
                                                         int kv_heads, int total_waves, int min_tiles_per_wave,
-                                                        int32_t *__restrict__ plan, int32_t *__restrict__ arrivals)
+                                                        int per_multiple, int32_t *__restrict__ plan,
+                                                        int32_t *__restrict__ arrivals)
 {
     {
         const int counters = layers * kv_heads * num_agents; // the host keeps this below 2^31
@@ -242,6 +246,7 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
             plan[pv.lt_off() + layers] = total;
             int per = (int)(((long long)total + total_waves - 1) / total_waves);
             if (per < min_tiles_per_wave) per = min_tiles_per_wave;
+            per = (per + per_multiple - 1) / per_multiple * per_multiple;
             plan[0] = total;
             plan[1] = per;
             plan[2] = C;
@@ -256,6 +261,7 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
         plan[pv.lt_off() + layers] = total;
         int per = (int)(((long long)total + total_waves - 1) / total_waves);
         if (per < min_tiles_per_wave) per = min_tiles_per_wave;
+        per = (per + per_multiple - 1) / per_multiple * per_multiple;
         plan[0] = total;
         plan[1] = per;
         plan[2] = C;
@@ -357,7 +363,7 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 // length are read and then ignored (their score is forced to "minus infinity", their p*s to zero; codes
 // are nibbles and cannot produce a NaN, scale/bias of such rows are replaced by zero after the load).
 template <int DK, int DV, int NREP, bool BF>
-__global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attention_kernel(DecodeParams p)
+__global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kernel(DecodeParams p)
 {
     constexpr int GK = DK / kGroup, GV = DV / kGroup;
     // K side (matrix core): lane = (token j = lane % 16 of a 16-token set, k-block kb = lane / 16)
@@ -378,12 +384,19 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     static_assert(VLPT % 8 == 0 && VLPT <= kWave && VSTEPS % 4 == 0, "V layout");
     // per wave: q.c per token, group and head [64][GK][NREP] (binary32) and p*scale [VROWS][GV][64] (binary16,
     // the tokens of four consecutive V load steps of a slot side by side, 8 bytes); the same
-    // region serves the end-of-unit reduction [VTPS][NREP][DV] + bias sums [NREP][GV]
+    // region serves the end-of-unit reduction [VTPS][NREP][DV] + bias sums [NREP][GV]; behind it the group sums of
+    // q [NREP][GK]
     constexpr int kPartFloats = kWave * GK * NREP;
     constexpr int kPsFloats = VROWS * GV * kWave / 2;
     constexpr int kFinalFloats = VTPS * NREP * DV + NREP * GV;
     constexpr int kWaveFloats = (kPartFloats + kPsFloats > kFinalFloats ? kPartFloats + kPsFloats : kFinalFloats) + NREP * GK;
     __shared__ float lds[kWaves * kWaveFloats];
+    // what a wave leaves behind when it is done with a segment: sums [NREP][DV], then (maximum, denominator)
+    // [NREP][2]; kSegBufs segments can be pending before a wave has to wait for the others
+    constexpr int kSegFloats = NREP * DV + 2 * NREP;
+    constexpr int kSegBufs = (NREP >= 8 || NREP * DV >= 2048) ? 1 : 2; // LDS: two workgroups per compute unit
+    __shared__ float seg_lds[kSegBufs * kWaves * kSegFloats];
+    __shared__ int s_last;
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = uniform(tid / kWave);
@@ -391,11 +404,18 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
 
     const TileStream ts_(p.stream);
     zero_empty_units<DV>(ts_.pv, p.merge.out, p.q_heads, gw, gridDim.x * kWaves, lane);
-    const int per = ts_.per, N = ts_.N;
-    const long long x_begin = (long long)gw * per;
-    if (x_begin >= N) return;
+    const int per = ts_.per, N = ts_.N; // per: tiles of a workgroup
+    const int wg = blockIdx.x;
+    const long long x_begin = (long long)wg * per;
+    if (x_begin >= N) return;           // the whole workgroup leaves
     const int x0 = (int)x_begin;
     const int x1 = (int)min((long long)N, x_begin + per);
+    // how the workgroup's range is shared out: tiles in turn (short ranges), or a contiguous quarter per wave
+    const bool coop = per < kCoopMaxTiles;
+    const int stride = coop ? kWaves : 1;
+    const int wx0 = coop ? x0 + wave : x0 + wave * (per / kWaves); // per is a multiple of 4
+    const int wx1 = coop ? x1 : min(x1, wx0 + per / kWaves);
+    if (!coop && wx0 >= wx1) return; // nothing to do and nobody to meet
 
     float *region = lds + wave * kWaveFloats;
     float *part = region;                                                  // [64][GK][NREP]
@@ -403,7 +423,20 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     const uint2 *ps_q = reinterpret_cast<const uint2 *>(ps_h);            // the same as token quads
     float *qsum_lds = region + (kWaveFloats - NREP * GK);                  // [NREP][GK]
 
-    Cursor cur = ts_.locate(x0);
+    // This wave's tiles are wx0, wx0 + stride, ... below wx1; a wave of a sharing workgroup whose range holds none
+    // keeps a valid cursor that it never uses.  A range (the workgroup's when its waves share, else the wave's own) is
+    // a sequence of segments (the parts of units inside it), numbered from 0: `seg` is the oldest one the four waves
+    // have not finished together yet (number k_old), `mseg` the one this wave's current tile lies in (number k_my).
+    const int r0 = coop ? x0 : wx0, r1 = coop ? x1 : wx1;
+    Cursor cur = ts_.locate(r0);
+    Segment seg, mseg;
+    seg.start(cur, r0, r1);
+    mseg = seg;
+    int k_old = 0, k_my = 0;
+    uint32_t pub_mask = 0; // bit i: this wave has left its result of segment k_old + i in seg_lds
+    int x = wx0;
+    bool active = x < wx1;
+    if (coop && active && wave > 0) ts_.advance(cur, wave);
 
     const int kj = lane % 16, kkb = lane / 16;
     const int vj = lane % VLPT, vo = lane / VLPT, vg = vj / 8;
@@ -448,20 +481,22 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
                           // until the end (their codes sit 4 bits higher)
     float m_run[NREP], l_run[NREP], pb[NREP][GV]; // l_run, pb: this lane's tokens only
 
-    const int64_t row0 = cur.row;
-    // same issue order as inside the loop (K codes first), pinned so that the wait for the K codes never
-    // covers the loads issued after them
+    if (active) {
+        const int64_t row0 = cur.row;
+        // same issue order as inside the loop (K codes first), pinned so that the wait for the K codes never
+        // covers the loads issued after them
 #pragma unroll
-    for (int tp = 0; tp < KSETS; tp += 2) {
-        load_k_pair(tp, row0);
+        for (int tp = 0; tp < KSETS; tp += 2) {
+            load_k_pair(tp, row0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        load_params(row0);
         __builtin_amdgcn_sched_barrier(0);
-    }
-    load_params(row0);
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < VSTEPS; i += 4) {
-        load_v_quad(i, row0);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < VSTEPS; i += 4) {
+            load_v_quad(i, row0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // Two workgroups share a compute unit, and at equal priority the older wave wins every arbitration, also the
@@ -470,20 +505,220 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
     // therefore take turns at a raised priority, in time slices read from the chip-wide clock.  (Which half is the
     // older one on a compute unit is a guess from the launch order; if it is wrong nothing but this balance is lost.)
     const bool second_half = blockIdx.x >= gridDim.x / 2;
-    bool unit_begins = true; // the wave's first tile, or tile 0 of a unit
-    int64_t unit0 = 0;
-    for (int x = x0; x < x1; ++x) {
-        if (Q4KV_DEC_PRIO_SHIFT > 0) {
-            const bool turn = ((wall_clock64() >> Q4KV_DEC_PRIO_SHIFT) & 1) != 0;
-            if (turn != second_half) __builtin_amdgcn_s_setprio(Q4KV_DEC_PRIO_LEVEL); else __builtin_amdgcn_s_setprio(0);
-        }
-        const bool last_of_wave = x + 1 >= x1;
-        Cursor nxt = cur;
-        if (!last_of_wave) ts_.step(nxt); // the wave's last tile re-reads itself: a valid address, the data is ignored
-        const int64_t row0_next = nxt.row;
-        const bool unit_ends = last_of_wave || nxt.j == 0;
 
-        if (unit_begins) {
+    // ---- Leaving a segment and finishing it are two steps, so that no wave waits while it still has tiles.
+    // publish: a wave that is done with its tiles of segment k folds token slots and lanes through its LDS region
+    // (fixed order) into one (sums, maximum, denominator) per query head and leaves that in buffer k % kSegBufs.
+    // close: the four waves finish the oldest segment together -- a wave that had no tile in it marks its entry
+    // empty -- and all 256 threads merge the four entries in wave order, one (head, element) at a time: into the
+    // output row when no other workgroup shares the unit, else into this workgroup's record of the unit, after
+    // which the workgroup that arrives last merges the records.  A wave closes segments only when it needs a buffer
+    // for a later one or has run out of tiles.  Barriers here wait for LDS traffic only (loads stay in flight).
+    auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+    auto publish = [&]() {
+        float *fin_acc = region;                      // [VTPS][NREP][DV]
+        float *fin_pb = region + VTPS * NREP * DV;    // [NREP][GV]
+        float *mine = seg_lds + ((k_my % kSegBufs) * kWaves + wave) * kSegFloats;
+        float lsum[NREP];
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+            float *dst = fin_acc + (vo * NREP + r) * DV + vj * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                dst[e] = (kTermRows ? acc[0][e][r] + acc[0][e][NREP + r] : acc[r / 4][e][r % 4]) *
+                         ((e & 1) ? kCodeScaleB : kCodeScaleA);
+            lsum[r] = wave_sum(l_run[r]);
+#pragma unroll
+            for (int g = 0; g < GV; ++g) {
+                const float s = wave_sum(pb[r][g]);
+                if (lane == 0) fin_pb[r * GV + g] = s;
+            }
+        }
+        wave_lds_sync();
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+#pragma unroll
+            for (int e0 = 0; e0 < DV; e0 += kWave) {
+                const int e = e0 + lane;
+                float o = fin_pb[r * GV + e / kGroup];
+#pragma unroll
+                for (int sl = 0; sl < VTPS; ++sl) o += fin_acc[(sl * NREP + r) * DV + e];
+                mine[r * DV + e] = o;
+            }
+            if (lane == 0) {
+                mine[NREP * DV + 2 * r] = m_run[r];
+                mine[NREP * DV + 2 * r + 1] = lsum[r];
+            }
+        }
+        wave_lds_sync(); // the region is free for the next tile
+        pub_mask |= 1u << (k_my - k_old);
+    };
+    auto close_oldest = [&]() {
+        const float *buf = seg_lds + (k_old % kSegBufs) * kWaves * kSegFloats;
+        if (!(pub_mask & 1u) && lane < NREP) {
+            float *mine = seg_lds + ((k_old % kSegBufs) * kWaves + wave) * kSegFloats;
+            mine[NREP * DV + 2 * lane] = kNegBig;
+            mine[NREP * DV + 2 * lane + 1] = 0.0f;
+        }
+        pub_mask >>= 1;
+        lds_barrier();
+        int slot, slots;
+        seg.slot_of(per, wg, slot, slots);
+        const bool alone = slots == 1;
+        const int64_t u0 = ((int64_t)seg.li * p.stream.num_agents + seg.agent) * p.q_heads + (int64_t)seg.kvh * NREP;
+        // thread tid takes (head, element) pairs tid, tid + 256, ...: the head is the same for a whole wave
+        for (int i = tid; i < NREP * DV; i += kThreads) {
+            const int r = i / DV, e = i % DV;
+            float mw[kWaves], lw[kWaves], m_ref = kNegBig;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                mw[w] = buf[w * kSegFloats + NREP * DV + 2 * r];
+                lw[w] = buf[w * kSegFloats + NREP * DV + 2 * r + 1];
+                if (lw[w] > 0.0f) m_ref = fmaxf(m_ref, mw[w]);
+            }
+            float o = 0.0f, l = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                if (lw[w] > 0.0f) { // a wave without tiles here left nothing to read
+                    const float wgt = __builtin_amdgcn_exp2f(mw[w] - m_ref);
+                    o = fmaf(wgt, buf[w * kSegFloats + r * DV + e], o);
+                    l = fmaf(wgt, lw[w], l);
+                }
+            }
+            if (alone) {
+                p.merge.out[(u0 + r) * DV + e] = float_to_half_bits(l > 0.0f ? o / l : 0.0f);
+            } else {
+                const int64_t rec = (u0 + r) * p.merge.max_slots + slot;
+                record_store(p.merge.part_acc + rec * DV + e, o);
+                if (e == 0) {
+                    record_store(p.merge.part_ml + rec * 2, m_ref);
+                    record_store(p.merge.part_ml + rec * 2 + 1, l);
+                }
+            }
+        }
+        if (!alone) {
+            // every wave's record stores have reached memory before thread 0 counts the workgroup in
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0)
+            lds_barrier();
+            if (tid == 0) {
+                int32_t *counter = p.merge.arrivals +
+                                   ((int64_t)seg.li * p.stream.kv_heads + seg.kvh) * p.stream.num_agents + seg.agent;
+                s_last = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == slots - 1;
+            }
+            lds_barrier();
+            const bool last = s_last != 0;
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            if (last) {
+                for (int i = tid; i < NREP * DV; i += kThreads) {
+                    const int r = i / DV, e = i % DV;
+                    const int64_t rec0 = (u0 + r) * p.merge.max_slots;
+                    const float o = merge_element<DV>(p.merge.part_acc + rec0 * DV, p.merge.part_ml + rec0 * 2, slots, e, lane);
+                    p.merge.out[(u0 + r) * DV + e] = float_to_half_bits(o);
+                }
+            }
+        } else {
+            lds_barrier(); // the buffer is free again
+        }
+        if (seg.end < x1) seg.next(ts_, x1); else seg.begin = x1;
+        ++k_old;
+    };
+
+    // ---- a wave on its own: what publish and close do together, for mseg, without the other waves
+    auto finish_alone = [&]() {
+        float *fin_acc = region;                      // [VTPS][NREP][DV]
+        float *fin_pb = region + VTPS * NREP * DV;    // [NREP][GV]
+        float lsum[NREP];
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+            float *dst = fin_acc + (vo * NREP + r) * DV + vj * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                dst[e] = (kTermRows ? acc[0][e][r] + acc[0][e][NREP + r] : acc[r / 4][e][r % 4]) *
+                         ((e & 1) ? kCodeScaleB : kCodeScaleA);
+            lsum[r] = wave_sum(l_run[r]);
+#pragma unroll
+            for (int g = 0; g < GV; ++g) {
+                const float s = wave_sum(pb[r][g]);
+                if (lane == 0) fin_pb[r * GV + g] = s;
+            }
+        }
+        wave_lds_sync();
+        int slot, slots;
+        mseg.slot_of_quarter(per, wg * kWaves + wave, slot, slots);
+        const bool alone = slots == 1;
+        const int64_t u0 = ((int64_t)mseg.li * p.stream.num_agents + mseg.agent) * p.q_heads + (int64_t)mseg.kvh * NREP;
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+            const int64_t rec = (u0 + r) * p.merge.max_slots + slot;
+            const float inv = lsum[r] > 0.0f ? 1.0f / lsum[r] : 0.0f;
+#pragma unroll
+            for (int e0 = 0; e0 < DV; e0 += kWave) {
+                const int e = e0 + lane;
+                float o = fin_pb[r * GV + e / kGroup];
+#pragma unroll
+                for (int sl = 0; sl < VTPS; ++sl) o += fin_acc[(sl * NREP + r) * DV + e];
+                if (alone) p.merge.out[(u0 + r) * DV + e] = float_to_half_bits(o * inv);
+                else record_store(p.merge.part_acc + rec * DV + e, o);
+            }
+            if (!alone && lane == 0) {
+                record_store(p.merge.part_ml + rec * 2, m_run[r]);
+                record_store(p.merge.part_ml + rec * 2 + 1, lsum[r]);
+            }
+        }
+        wave_lds_sync(); // the region is free for the next tile
+        if (!alone) {
+            int32_t *counter = p.merge.arrivals +
+                               ((int64_t)mseg.li * p.stream.kv_heads + mseg.kvh) * p.stream.num_agents + mseg.agent;
+            if (arrive_last(counter, slots, lane)) {
+                for (int r = 0; r < NREP; ++r) {
+                    const int64_t rec0 = (u0 + r) * p.merge.max_slots;
+                    for (int e0 = 0; e0 < DV; e0 += kWave) {
+                        const float o = merge_element<DV>(p.merge.part_acc + rec0 * DV, p.merge.part_ml + rec0 * 2, slots,
+                                                          e0 + lane, lane);
+                        p.merge.out[(u0 + r) * DV + e0 + lane] = float_to_half_bits(o);
+                    }
+                }
+            }
+        }
+    };
+
+    bool have = false; // this wave holds online-softmax state of mseg's unit
+    int64_t unit0 = 0;
+    for (;;) {
+        if (!active || x >= mseg.end) {
+            // this wave is done with mseg: it leaves its result behind (closing the oldest segments first when
+            // no buffer is free) and goes on, or, without a tile left, helps to close everything that remains
+            if (have) {
+                if (coop) {
+                    while (k_my - k_old >= kSegBufs) close_oldest();
+                    publish();
+                } else {
+                    finish_alone();
+                }
+                have = false;
+            }
+            if (!active) {
+                if (coop)
+                    while (seg.begin < x1) close_oldest();
+                break;
+            }
+            while (x >= mseg.end) {
+                mseg.next(ts_, r1);
+                ++k_my;
+            }
+        }
+        if (per >= kPrioMinTiles) { // a short call would spend its whole life in one slice
+            const bool turn = ((wall_clock64() >> kPrioShift) & 1) != 0;
+            if (turn != second_half) __builtin_amdgcn_s_setprio(kPrioLevel); else __builtin_amdgcn_s_setprio(0);
+        }
+        const bool more = x + stride < wx1;
+        Cursor nxt = cur;
+        if (more) ts_.advance(nxt, stride); // the wave's last tile re-reads itself: a valid address, the data is ignored
+        const int64_t row0_next = nxt.row;
+
+        if (!have) {
+            have = true;
             // first of this unit's NREP query heads
             unit0 = ((int64_t)cur.li * p.stream.num_agents + cur.agent) * p.q_heads + (int64_t)cur.kvh * NREP;
             // ---- new unit: its query heads.  Query operand of the matrix core, one per (chunk, word): row
@@ -662,63 +897,9 @@ __global__ __launch_bounds__(kThreads, Q4KV_DEC_WAVES_PER_EU) void decode_attent
         }
         wave_lds_sync(); // the next tile (or the reduction below) overwrites part / ps
 
-        if (unit_ends) {
-            // ---- this wave's share of the unit is complete: fold token slots and lanes through LDS (fixed
-            // order).  A unit that no other wave shares is normalised and written out; otherwise one partial per
-            // query head goes into the slot this wave has in the unit, and the wave that arrives last merges them
-            float *fin_acc = region;                      // [VTPS][NREP][DV]
-            float *fin_pb = region + VTPS * NREP * DV;    // [NREP][GV]
-            float lsum[NREP];
-#pragma unroll
-            for (int r = 0; r < NREP; ++r) {
-                float *dst = fin_acc + (vo * NREP + r) * DV + vj * 8;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    dst[e] = (kTermRows ? acc[0][e][r] + acc[0][e][NREP + r] : acc[r / 4][e][r % 4]) *
-                             ((e & 1) ? kCodeScaleB : kCodeScaleA);
-                lsum[r] = wave_sum(l_run[r]);
-#pragma unroll
-                for (int g = 0; g < GV; ++g) {
-                    const float s = wave_sum(pb[r][g]);
-                    if (lane == 0) fin_pb[r * GV + g] = s;
-                }
-            }
-            wave_lds_sync();
-            int slot, slots;
-            ts_.slot_of(cur, gw, slot, slots);
-            const bool alone = slots == 1;
-#pragma unroll
-            for (int r = 0; r < NREP; ++r) {
-                const int64_t rec = (unit0 + r) * p.merge.max_slots + slot;
-                const float inv = lsum[r] > 0.0f ? 1.0f / lsum[r] : 0.0f;
-#pragma unroll
-                for (int e0 = 0; e0 < DV; e0 += kWave) {
-                    const int e = e0 + lane;
-                    float o = fin_pb[r * GV + e / kGroup];
-#pragma unroll
-                    for (int sl = 0; sl < VTPS; ++sl) o += fin_acc[(sl * NREP + r) * DV + e];
-                    if (alone) p.merge.out[(unit0 + r) * DV + e] = float_to_half_bits(o * inv);
-                    else record_store(p.merge.part_acc + rec * DV + e, o);
-                }
-                if (!alone && lane == 0) {
-                    record_store(p.merge.part_ml + rec * 2, m_run[r]);
-                    record_store(p.merge.part_ml + rec * 2 + 1, lsum[r]);
-                }
-            }
-            wave_lds_sync();
-            if (!alone) {
-                int32_t *counter = p.merge.arrivals + ((int64_t)cur.li * p.stream.kv_heads + cur.kvh) * p.stream.num_agents + cur.agent;
-                if (arrive_last(counter, slots, lane)) {
-                    for (int r = 0; r < NREP; ++r) {
-                        const int64_t rec0 = (unit0 + r) * p.merge.max_slots;
-                        merge_head<DV>(p.merge.part_acc + rec0 * DV, p.merge.part_ml + rec0 * 2, slots,
-                                       p.merge.out + (unit0 + r) * DV, lane);
-                    }
-                }
-            }
-        }
-        unit_begins = unit_ends;
         cur = nxt;
+        x += stride;
+        active = more;
     }
 }
 
@@ -779,7 +960,7 @@ MergeParams merge_params(const AttentionArgs &a)
     return m;
 }
 
-hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream)
+hipError_t launch_plan(const AttentionArgs &a, int workers, int per_multiple, hipStream_t stream)
 {
     LayerWindows lw;
     lw.uniform = a.layer_window == nullptr;
@@ -789,12 +970,14 @@ hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream)
     const int64_t counters = (int64_t)a.layers_in_call * a.spec.num_kv_heads * a.num_agents;
     const int helpers = (int)(counters / 8192 < 256 ? counters / 8192 : 256);
     hipLaunchKernelGGL(plan_kernel, dim3(1 + helpers), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len,
-                       lw, a.layers_in_call, a.spec.num_kv_heads, a.grid_workgroups * kWaves, a.split_tokens / kWave,
-                       a.plan, a.arrivals);
+                       lw, a.layers_in_call, a.spec.num_kv_heads, workers, a.split_tokens / kWave, per_multiple, a.plan,
+                       a.arrivals);
     return hipGetLastError();
 }
 
 int decode_waves_per_workgroup() { return kWaves; }
+
+int decode_solo_quarter_tiles() { return kCoopMaxTiles / kWaves; }
 
 int max_window_layers() { return kMaxWindowLayers; }
 
@@ -811,7 +994,8 @@ bool decode_supported(const q4kv_spec &s)
 
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
 {
-    hipError_t e = launch_plan(a, stream);
+    // the workers of the tile stream are workgroups here, with ranges that divide among four waves
+    hipError_t e = launch_plan(a, a.grid_workgroups, kWaves, stream);
     if (e != hipSuccess) return e;
     const int n_rep = a.spec.num_q_heads / a.spec.num_kv_heads;
     switch (a.spec.k_dim) {

@@ -625,7 +625,7 @@ bool mla_decode_supported(const q4kv_spec &s)
 
 hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t stream)
 {
-    hipError_t e = launch_plan(a, stream);
+    hipError_t e = launch_plan(a, a.grid_workgroups * kWaves, 1, stream); // every wave walks a tile range of its own
     if (e != hipSuccess) return e;
     e = a.spec.param_format == Q4KV_PARAMS_BF16 ? launch_mla_t<9, 8, true>(a, stream) : launch_mla_t<9, 8, false>(a, stream);
     return e == hipSuccess ? launch_combine(a, stream) : e;

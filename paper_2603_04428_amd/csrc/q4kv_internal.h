@@ -41,11 +41,14 @@ struct StreamParams;
 struct MergeParams;
 StreamParams stream_params(const AttentionArgs &a);
 MergeParams merge_params(const AttentionArgs &a);
-hipError_t launch_plan(const AttentionArgs &a, hipStream_t stream);   // needs grid_workgroups, split_tokens, plan
+// workers: how many equal tile ranges the plan cuts the call into, each a multiple of per_multiple tiles long; needs
+// split_tokens, plan, arrivals
+hipError_t launch_plan(const AttentionArgs &a, int workers, int per_multiple, hipStream_t stream);
 
 // true when a decode (q_len == 1) kernel exists for these head shapes
 bool decode_supported(const q4kv_spec &spec);
 int decode_waves_per_workgroup();
+int decode_solo_quarter_tiles();   // smallest tile range a single wave of the GQA kernel takes for itself
 size_t decode_plan_ints(int num_agents, int layers);
 int max_window_layers();   // layers per call when every layer brings its own window
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);

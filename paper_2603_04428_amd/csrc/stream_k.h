@@ -151,6 +151,51 @@ struct TileStream {
         enter_block(c);
     }
 
+    // to the next unit of the stream that has tiles (li, kvh, agent and cb only)
+    template <typename C>
+    __device__ __forceinline__ void next_unit(C &c) const
+    {
+        const int32_t *tpre = pv.tpre(c.cb);
+        do {
+            if (++c.agent >= sp.num_agents) {
+                c.agent = 0;
+                if (++c.kvh >= sp.kv_heads) {
+                    c.kvh = 0;
+                    ++c.li;
+                    c.cb = pv.layer_class_off(c.li);
+                    tpre = pv.tpre(c.cb);
+                }
+            }
+        } while (tpre[c.agent + 1] == tpre[c.agent]);
+    }
+
+    // `stride` tiles ahead (stride <= 4, the target stays below the stream's end): the walk of one wave of a
+    // workgroup whose waves take the tiles of the workgroup's range in turn.  Inside a unit with stride 4 the target
+    // is the same slot range of the next 256-token block.
+    template <typename C>
+    __device__ __forceinline__ void advance(C &c, int stride) const
+    {
+        c.j += stride;
+        if (c.j < c.tiles) {
+            const int old_block = c.t0 / kBlockTokens;
+            c.t0 += stride * kWave;
+            if (c.t0 / kBlockTokens != old_block) next_block(c); else c.row += stride * kWave;
+            return;
+        }
+        int r = c.j - c.tiles; // tiles to go beyond the end of this unit
+        for (;;) {
+            next_unit(c);
+            const int32_t *tpre = pv.tpre(c.cb);
+            const int tiles = tpre[c.agent + 1] - tpre[c.agent];
+            if (r < tiles) break;
+            r -= tiles;
+        }
+        c.j = r;
+        c.t0 = pv.tstart(c.cb)[c.agent] + r * kWave;
+        enter_unit(c);
+        enter_block(c);
+    }
+
     // where tile x lies: layer by binary search over the layer prefix, agent by binary search over the class's
     // per-agent prefix
     template <typename C = Cursor>
@@ -193,6 +238,50 @@ struct TileStream {
         const int first_wave = unit_first_tile / per;
         slot = gw - first_wave;
         slots = (unit_first_tile + c.tiles - 1) / per - first_wave + 1;
+    }
+};
+
+// The part of one unit that lies inside a worker's tile range [x0, x1): what the waves of a workgroup finish
+// together before any of them goes on.
+struct Segment {
+    int li, kvh, agent, cb;
+    int unit_first, tiles; // stream index of the unit's first tile, tiles of the unit
+    int begin, end;        // stream indices of the segment, begin < end <= x1
+
+    // the segment that starts at the worker's first tile (c = locate(x0))
+    template <typename C>
+    __device__ __forceinline__ void start(const C &c, int x0, int x1)
+    {
+        li = c.li, kvh = c.kvh, agent = c.agent, cb = c.cb;
+        unit_first = x0 - c.j;
+        tiles = c.tiles;
+        begin = x0;
+        end = unit_first + tiles < x1 ? unit_first + tiles : x1;
+    }
+    // the next one (meaningful while end < x1)
+    __device__ __forceinline__ void next(const TileStream &ts, int x1)
+    {
+        ts.next_unit(*this);
+        const int32_t *tpre = ts.pv.tpre(cb);
+        unit_first = begin = end;
+        tiles = tpre[agent + 1] - tpre[agent];
+        end = unit_first + tiles < x1 ? unit_first + tiles : x1;
+    }
+    // the record this worker writes for the unit, and how many workers meet in it
+    __device__ __forceinline__ void slot_of(int per, int worker, int &slot, int &slots) const
+    {
+        const int first_worker = unit_first / per;
+        slot = worker - first_worker;
+        slots = (unit_first + tiles - 1) / per - first_worker + 1;
+    }
+    // the same when every worker's range of `per` tiles (a multiple of 4) is cut into four sub-ranges of per / 4
+    // tiles with a record each: sub-range i of worker w has the number 4 w + i
+    __device__ __forceinline__ void slot_of_quarter(int per, int number, int &slot, int &slots) const
+    {
+        const int q = per / 4, last_tile = unit_first + tiles - 1;
+        const int first = 4 * (unit_first / per) + (unit_first % per) / q;
+        slot = number - first;
+        slots = 4 * (last_tile / per) + (last_tile % per) / q - first + 1;
     }
 };
 
@@ -253,41 +342,32 @@ __device__ __forceinline__ bool arrive_last(int32_t *counter, int slots, int lan
     return old == slots - 1;
 }
 
-// Merge the `slots` partial records of one query head and write its output row: binary32, slot order, output
-// binary16.  A lane owns elements lane, lane + 64, ...  Records whose denominator is zero (every token of the
-// wave's share was masked) are skipped; a head with nothing at all yields zeros.
-// A record load is a trip to memory, so loads are issued in batches of 32 / (DV / 64) records (32 loads in flight
-// per lane) together with the batch's maxima and denominators, and only then used: a unit of up to that many
-// records costs one round trip per head.  The reference maximum moves from batch to batch like a running maximum.
+// One output value of one query head from the `slots` partial records of its unit: element e of every record,
+// binary32, slot order.  All lanes of the wave work on the same head (ml: its [slots][2] maxima and denominators;
+// acc: its [slots][DV] sums).  Records whose denominator is zero (every token masked) are skipped; a head with
+// nothing at all yields zero.  A record load is a trip to memory, so the loads of up to 16 records are issued
+// together with their maxima and denominators and only then used: units of up to 16 records cost one round trip.
 template <int DV>
-__device__ __forceinline__ void merge_head(const float *acc, const float *ml, int slots, uint16_t *out_row, int lane)
+__device__ __forceinline__ float merge_element(const float *acc, const float *ml, int slots, int e, int lane)
 {
-    constexpr int CH = DV / kWave; // 1, 2, 4 or 8 elements per lane
-    static_assert(CH == 1 || CH == 2 || CH == 4 || CH == 8, "row width");
-    constexpr int B = 32 / CH;     // records per batch
-    float o[CH];
-#pragma unroll
-    for (int i = 0; i < CH; ++i) o[i] = 0.0f;
-    float m_ref = kMergeNegBig, denom = 0.0f;
+    constexpr int B = 16;
+    float o = 0.0f, m_ref = kMergeNegBig, denom = 0.0f;
     for (int s0 = 0; s0 < slots; s0 += B) {
         const int count = slots - s0 < B ? slots - s0 : B;
         const int s = s0 + (lane < count ? lane : count - 1);
         const float m_s = record_load(ml + 2 * s);
         const float l_s = lane < count ? record_load(ml + 2 * s + 1) : 0.0f;
-        float v[B][CH];
+        float v[B];
 #pragma unroll
         for (int j = 0; j < B; ++j) {
-            const int k = j < count ? j : count - 1; // repeats of the batch's last record carry weight zero
-            const float *row = acc + (int64_t)(s0 + k) * DV + lane;
-#pragma unroll
-            for (int c = 0; c < CH; ++c) v[j][c] = record_load(row + c * kWave);
+            const int k = j < count ? j : count - 1; // repeats of the batch's last record are not used
+            v[j] = record_load(acc + (int64_t)(s0 + k) * DV + e);
         }
         const float m_new = fmaxf(m_ref, wave_max(l_s > 0.0f ? m_s : kMergeNegBig));
-        const float keep = __builtin_amdgcn_exp2f(m_ref - m_new); // 1 when the reference stays; 0 * 0 while nothing was added
+        const float keep = __builtin_amdgcn_exp2f(m_ref - m_new); // 1 when the reference stays
         m_ref = m_new;
         denom *= keep;
-#pragma unroll
-        for (int c = 0; c < CH; ++c) o[c] *= keep;
+        o *= keep;
         const float w = l_s > 0.0f ? __builtin_amdgcn_exp2f(m_s - m_ref) : 0.0f;
         const float wl = w * l_s;
 #pragma unroll
@@ -295,14 +375,11 @@ __device__ __forceinline__ void merge_head(const float *acc, const float *ml, in
             if (j < count) { // wave-uniform
                 const float wk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), j));
                 denom += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), j));
-#pragma unroll
-                for (int c = 0; c < CH; ++c) o[c] = fmaf(wk, v[j][c], o[c]);
+                o = fmaf(wk, v[j], o);
             }
         }
     }
-    const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) out_row[c * kWave + lane] = float_to_half_bits(o[c] * inv);
+    return denom > 0.0f ? o / denom : 0.0f;
 }
 
 } // namespace q4kv
