@@ -1,13 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the Q4 KV-cache hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip-cpu-baseline] [--skip-other-configs]
 
 Workload: the 10-agent ragged Gemma-3-12B-shaped configuration (48 layers, 16 query / 8 KV heads,
 head_dim 256, context lengths drawn uniformly from [1024, 8192]), synthetic contents.  One step is one
 pass of the whole path: a batch-10 decode-attention step over all 48 layers (one call), the quantization
 of one fresh 4,096-token fp16 agent cache, and the dequantization of one restored cache.  Everything is
-resident in HBM before the timed region.  Prints one JSON line.
+resident in HBM before the timed region.  Prints one JSON line.  The same line carries the step issued as one
+call per layer (`per_layer_graph_ms`), the CPU oracle's timing of the same rows (`cpu_baseline`) and, under
+`other_configs`, a compact measurement of the other four benchmark configurations (each with its own roofline
+and oracle sample), so that one run times every row of the path.
 """
 import argparse
 import json
@@ -23,12 +26,34 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
 
 # HBM bytes per launch of each workload's dominant kernel, read + written, from the rocprofv3 --pmc runs whose
-# summaries are under profiles/ (FETCH_SIZE and WRITE_SIZE scaled by what a plain copy of known size reads)
+# summaries are under profiles/ (FETCH_SIZE and WRITE_SIZE scaled by what a plain copy of known size reads).
+# Counters cannot be read inside this process, so the figures are constants -- each tied to the kernel sources it
+# was measured on: `sources` is kernel_sources_hash() at the time of the counter run, and traffic_for() hands a
+# figure out only while the sources are still the same (else null: measure again, `--print-sources-hash`).
 MEASURED_TRAFFIC = {
-    "decode": 4789188608 + 12313600,
-    "dsv2lite_mla_latent_5agents_27layers_32k_decode": 1444208640 + 53625856,
-    "dsv2lite_mla_per_head_5agents_27layers_8k_decode": 3188256768,   # reads only (no WRITE_SIZE run)
 }
+
+
+def kernel_sources_hash():
+    """Short hash over the library's kernel sources (what a counter run measured)."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2603_04428_amd", "csrc")
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def traffic_for(name):
+    """(bytes per launch, where it was measured) of a workload's dominant kernel, or (None, reason)."""
+    m = MEASURED_TRAFFIC.get(name)
+    if m is None:
+        return None, "no counter run for this workload"
+    if m["sources"] != kernel_sources_hash():
+        return None, f"counter run {m['file']} was taken on other kernel sources ({m['sources']})"
+    return m["read"] + m["written"], m["file"] + " (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)"
 
 
 PARAM_FORMAT = 0      # q4kv_param_format of the run (--param-format): 0 binary16, 1 bfloat16 scale / bias
@@ -47,42 +72,99 @@ def emit(res):
     print(json.dumps(res))
 
 
-def cpu_baseline(w, layers):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: all agents and heads of a few
-    layers.  Returns the JSON object; GB/s counts the same algorithmic Q4 bytes as the GPU figure."""
+def cpu_baseline(w, layers, agents=None):
+    """The CPU oracle, as it stands, on a bounded sample of the same decode workload: all heads of a few layers
+    (and, for the long-context configurations, a few agents).  Returns the JSON object; GB/s counts the same
+    algorithmic Q4 bytes as the GPU figure."""
     import numpy as np
     import oracle
+    agents = list(range(w.num_agents)) if agents is None else list(agents)
     spec = oracle.make_spec(len(layers), w.num_q_heads, w.num_kv_heads, w.k_dim, w.v_dim, w.v_aliases_k,
                             param_format=PARAM_FORMAT)
-    table, nb = w.block_table()
-    table = np.where(table < 0, 0, table).astype(np.int32)
+    lens = [w.seq_lens[a] for a in agents]
+    need = [(n + 255) // 256 for n in lens]
+    nb = max(1, sum(need))
+    table = np.zeros((len(agents), max(1, max(need))), np.int32)
+    pos = 0
+    for i, k in enumerate(need):
+        table[i, :k] = np.arange(pos, pos + k)
+        pos += k
     kpool = oracle.Pool(spec, w.k_dim, nb)
-    vpool = oracle.Pool(spec, w.v_dim, nb)
-    q = np.zeros((len(layers), w.num_agents, 1, w.num_q_heads, w.k_dim), np.float16)
+    vpool = None if w.v_aliases_k else oracle.Pool(spec, w.v_dim, nb)
+    q = np.zeros((len(layers), len(agents), 1, w.num_q_heads, w.k_dim), np.float16)
     for i, l in enumerate(layers):
-        for a, n in enumerate(w.seq_lens):
+        for j, a in enumerate(agents):
+            n = lens[j]
             k_new = w.k_rows(l, a, 0, n).numpy()[None, None]
-            v_new = w.v_rows(l, a, 0, n).numpy()[None, None]
-            oracle.append(spec, kpool, vpool, k_new, v_new, table[a:a + 1], np.zeros(1, np.int32), i, i + 1)
-            q[i, a] = w.q_rows(l, a).numpy()
+            v_new = None if w.v_aliases_k else w.v_rows(l, a, 0, n).numpy()[None, None]
+            oracle.append(spec, kpool, vpool, k_new, v_new, table[j:j + 1], np.zeros(1, np.int32), i, i + 1)
+            q[i, j] = w.q_rows(l, a).numpy()
     t0 = time.perf_counter()
-    _, threads = oracle.attention(spec, kpool, vpool, q, table, w.seq_lens, w.sm_scale, return_threads=True)
+    _, threads = oracle.attention(spec, kpool, vpool, q, table, lens, w.sm_scale, return_threads=True)
     dt = time.perf_counter() - t0
-    nbytes = sum(w.seq_lens) * len(layers) * w.q4_bytes_per_token_layer()
+    nbytes = sum(lens) * len(layers) * w.q4_bytes_per_token_layer()
+    step_bytes = sum(w.seq_lens) * w.num_layers * w.q4_bytes_per_token_layer()
+    who = f"all {w.num_agents} agents" if len(agents) == w.num_agents else f"agents {agents} of {w.num_agents}"
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "agent_tokens_per_s": w.num_agents / (dt * w.num_layers / len(layers)),
-            "sample": f"decode attention of layers {layers} of {w.num_layers}, all {w.num_agents} agents and "
+            "agent_tokens_per_s": w.num_agents / (dt * step_bytes / nbytes),
+            "sample": f"decode attention of layers {layers} of {w.num_layers}, {who}, all "
                       f"{w.num_q_heads} query heads ({nbytes / 1e6:.0f} MB of Q4 cache), {dt:.2f} s wall; "
-                      "agent_tokens_per_s extrapolates to all layers"}
+                      "agent_tokens_per_s extrapolates to the whole step"}
+
+
+def cpu_baseline_codec(x_host):
+    """The oracle's quantizer and dequantizer timed on the whole 4,096-token fp16 cache (host copy of the generator's
+    values): GB/s over the same bytes as the GPU rows (2 bytes in + 0.5625 out per element, and the reverse)."""
+    import numpy as np
+    import oracle
+    x = x_host.reshape(-1, x_host.shape[-1])
+    t0 = time.perf_counter()
+    codes, scale, bias = oracle.quantize(x, PARAM_FORMAT)
+    tq = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    back = oracle.dequantize(codes, scale, bias, PARAM_FORMAT)
+    td = time.perf_counter() - t0
+    nbytes = x.size * 2 + codes.size * 4 + scale.size * 2 + bias.size * 2
+    return {"quantize_GBps": nbytes / tq / 1e9, "quantize_s": tq, "dequantize_GBps": nbytes / td / 1e9,
+            "dequantize_s": td, "elements": int(x.size), "cores": oracle.max_threads(),
+            "sample": "oracle quantize and dequantize of the whole 4,096-token cache "
+                      f"({x.size / 1e6:.0f} M elements, {nbytes / 1e9:.2f} GB moved each way)"}, back
+
+
+def cpu_baseline_chunk(w, layer, agent, kvh):
+    """The oracle on one (layer, agent, KV head) of the chunked-append configuration: append of the 512-token chunk
+    and causal attention of its 512 rows x n_rep query heads over cache + chunk.  TFLOP/s counts the same
+    algorithmic flops as the GPU figure (4 * heads * k_dim * visible keys per row)."""
+    import numpy as np
+    import oracle
+    R, C, n = w.n_rep, w.q_len, w.seq_lens[agent]
+    spec = oracle.make_spec(1, R, 1, w.k_dim, w.v_dim, False, param_format=PARAM_FORMAT)
+    nb = (n + C + 255) // 256
+    kpool, vpool = oracle.Pool(spec, w.k_dim, nb), oracle.Pool(spec, w.v_dim, nb)
+    table = np.arange(nb, dtype=np.int32)[None]
+    k_all = w.k_rows(layer, agent, 0, n + C, h0=kvh, h1=kvh + 1).numpy()[None, None]
+    v_all = w.v_rows(layer, agent, 0, n + C, h0=kvh, h1=kvh + 1).numpy()[None, None]
+    oracle.append(spec, kpool, vpool, k_all[:, :, :n], v_all[:, :, :n], table, np.zeros(1, np.int32))
+    q = np.ascontiguousarray(w.q_rows(layer, agent).numpy()[:, kvh * R:(kvh + 1) * R])[None, None]
+    t0 = time.perf_counter()
+    oracle.append(spec, kpool, vpool, k_all[:, :, n:], v_all[:, :, n:], table, np.array([n], np.int32))
+    _, threads = oracle.attention(spec, kpool, vpool, q, table, [n + C], w.sm_scale, return_threads=True)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * R * w.k_dim * (C * n + C * (C + 1) / 2)
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"quantize-append + causal chunk attention of layer {layer}, agent {agent} ({n} cached tokens), KV "
+                      f"head {kvh}: {C} rows x {R} query heads, {flops / 1e9:.1f} GFLOP, {dt:.2f} s wall"}
 
 
 MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16 matrix throughput
 
 
-def bench_append(args, torch, b, synth, build_device_cache):
+def bench_append(args, torch, b, synth, build_device_cache, steps=None, warmup=None):
     """Chunked append (the matrix-core path): per step, q4kv_append of a 512-token chunk for every agent and layer,
-    then causal chunk attention of the 512 new queries over cache + chunk, all 48 layers."""
+    then causal chunk attention of the 512 new queries over cache + chunk, all 48 layers.  Returns the result."""
     dev = "cuda"
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
     w = synth.config(4)
     spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0, tokens=w.seq_lens)
     C = w.q_len
@@ -109,12 +191,12 @@ def bench_append(args, torch, b, synth, build_device_cache):
         if ev:
             ev[2].record()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(events[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -125,8 +207,8 @@ def bench_append(args, torch, b, synth, build_device_cache):
     app_bytes = k_new.numel() * 2 * 2 * (1 + 0.28125)
     res = {
         "metric": "Q4 KV chunked-append attention TFLOP/s (% of dense fp16 MFMA peak) + agent-tokens/s",
-        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 matrix operands (K codes exact, scales applied in f32; V dequantized to f16), f32 accumulate, f16 out", "data": "synthetic",
         "config": {"workload": w.name if args.layer_windows == "global" else w.name + " + 5:1 window-1024 layers",
                    "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
@@ -138,7 +220,10 @@ def bench_append(args, torch, b, synth, build_device_cache):
                      "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
                      "kernel": "chunk_attention_kernel<256,256,2,1,false>"},
     }
-    emit(res)
+    if not args.skip_cpu_baseline:
+        shortest = min(range(w.num_agents), key=lambda a: w.seq_lens[a])
+        res["cpu_baseline"] = cpu_baseline_chunk(w, 0, shortest, 0)
+    return res
 
 
 def percentile(xs, q):
@@ -200,31 +285,35 @@ def calibration_copy(torch, dev):
     del src, dst
 
 
-def bench_latent(args, torch, b, synth, build_device_cache):
+def bench_latent(args, torch, b, synth, build_device_cache, **kw):
     """Decode over the shared-latent cache (DeepSeek-V2-Lite-shaped: 5 agents x 32,768 tokens x 27 layers, one
     576-wide Q4 row per token read by 16 heads), all layers in one call; reported as HBM GB/s."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.config(3),
-                             "mla_decode_kernel<9,8,false> (+ combine_kernel in the same call)")
+                             "mla_decode_kernel<9,8,false> (+ plan_kernel and combine_kernel in the same call)",
+                             oracle_sample=([0], [0]), **kw)
 
 
-def bench_llama(args, torch, b, synth, build_device_cache):
+def bench_llama(args, torch, b, synth, build_device_cache, **kw):
     """Decode over the Llama-3.1-8B-shaped cache of configuration 1 (5 agents x 4,096 tokens x 32 layers, 32 query /
     8 KV heads, 128 wide): a short call (0.15 ms), so plan and combine weigh in it."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.config(1),
-                             "decode_attention_kernel<128,128,4,false> (+ combine_kernel in the same call)")
+                             "decode_attention_kernel<128,128,4,false> (+ plan_kernel in the same call)",
+                             oracle_sample=([0, 10, 21, 31], None), **kw)
 
 
-def bench_tiny(args, torch, b, synth, build_device_cache):
+def bench_tiny(args, torch, b, synth, build_device_cache, **kw):
     """Configuration 0 (1 agent x 1,024 tokens x 1 layer, Llama-shaped): 1.2 MB of cache that stays in the caches of
     the chip, so the figure of interest is the latency of one call (plan + attention + combine), `decode_us`."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.config(0),
-                             "decode_attention_kernel<128,128,4,false> (+ plan_kernel and combine_kernel in the same call)")
+                             "decode_attention_kernel<128,128,4,false> (+ plan_kernel in the same call)",
+                             oracle_sample=([0], None), **kw)
 
 
-def bench_per_head(args, torch, b, synth, build_device_cache):
+def bench_per_head(args, torch, b, synth, build_device_cache, **kw):
     """Decode over the decompressed per-head form of the same model's cache (keys 192, values 128, 16 KV heads)."""
     return bench_decode_only(args, torch, b, build_device_cache, synth.per_head_mla_config(),
-                             "decode_attention_kernel<192,128,1,false> (+ combine_kernel in the same call)")
+                             "decode_attention_kernel<192,128,1,false> (+ plan_kernel in the same call)",
+                             oracle_sample=([0, 26], None), **kw)
 
 
 def bench_restore(args, torch, b, synth, build_device_cache):
@@ -423,8 +512,12 @@ def bench_mixed_step(args, torch, b, synth, build_device_cache):
     emit(res)
 
 
-def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
+def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name, oracle_sample=None, steps=None, warmup=None):
+    """One decode configuration, all layers in one call.  oracle_sample: (layers, agents or None for all) the CPU
+    oracle is timed on.  Returns the result."""
     dev = "cuda"
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
     spec, kpool, vpool, table, table_d = build_device_cache(w, dev, poison=False, extra_blocks=0)
     q = w.q_all(dev)
     seq = torch.tensor(w.seq_lens, dtype=torch.int32, device=dev)
@@ -441,12 +534,12 @@ def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
 
     if args.calibrate_copy:
         calibration_copy(torch, dev)
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         events[i][0].record()
         step()
         events[i][1].record()
@@ -457,8 +550,8 @@ def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
     gbps = decode_bytes / (dec_ms * 1e-3) / 1e9
     res = {
         "metric": "Q4 KV decode-attention achieved HBM GB/s (% of peak) + agent-tokens/s",
-        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "q4 codes + f16 scale/bias, f16 matrix operands, f32 accumulate, f16 out", "data": "synthetic",
         "config": {"workload": w.name if args.layer_windows == "global" else w.name + " + 5:1 window-1024 layers",
                    "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
@@ -471,11 +564,13 @@ def bench_decode_only(args, torch, b, build_device_cache, w, kernel_name):
         "matrix_TFLOPs": flops / (dec_ms * 1e-3) / 1e12,
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC.get(w.name) if not args.split_tokens else None,
-                     "traffic_source": "profiles/ (FETCH_SIZE + WRITE_SIZE of the kernel, scaled)",
+                     "traffic": traffic_for(w.name)[0] if not args.split_tokens else None,
+                     "traffic_source": traffic_for(w.name)[1],
                      "kernel": kernel_name},
     }
-    emit(res)
+    if oracle_sample is not None and not args.skip_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, oracle_sample[0], oracle_sample[1])
+    return res
 
 
 def main():
@@ -496,10 +591,15 @@ def main():
                          "Llama-shaped cache of configuration 1; tiny: the latency of one call on configuration 0; restore: save "
                          "and restore of one 32,768-token agent through a block image, also while other agents decode; mixed-step: "
                          "one agent's 512-token append on a second stream beside the decode steps of ten others")
-    ap.add_argument("--per-layer-graph", action="store_true",
-                    help="decode workload: also time the same step issued as one call per layer, recorded into a graph "
-                         "and replayed (adds 'per_layer_graph_ms'; leave it out of profiler runs, whose per-kernel "
-                         "averages it would mix with the single-launch figures)")
+    ap.add_argument("--no-per-layer-graph", action="store_true",
+                    help="decode workload: leave out the timing of the same step issued as one call per layer, recorded "
+                         "into a graph and replayed ('per_layer_graph_ms'); for profiler runs, whose per-kernel "
+                         "averages it would mix with the single-launch figures")
+    ap.add_argument("--skip-other-configs", action="store_true",
+                    help="decode workload: leave out the compact measurements of the other four benchmark "
+                         "configurations ('other_configs'); for profiler runs")
+    ap.add_argument("--print-sources-hash", action="store_true",
+                    help="print the hash of the kernel sources that MEASURED_TRAFFIC entries are tied to, and exit")
     ap.add_argument("--param-format", choices=["f16", "bf16"], default="f16",
                     help="type of the stored scale and bias (decode, append, latent, per-head workloads); f16 is what "
                          "every benchmark configuration specifies")
@@ -508,6 +608,9 @@ def main():
                          "to the whole cache; mixed: five layers with a 1,024-token sliding window, then one global "
                          "layer, repeated (8 global + 40 windowed of 48, Sec. 3.6) through the per-layer window entry")
     args = ap.parse_args()
+    if args.print_sources_hash:
+        print(kernel_sources_hash())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (agents would shard across GPUs with no exchange step); "
                  "run with --gpus 1")
@@ -524,15 +627,15 @@ def main():
         build_device_cache = functools.partial(build_device_cache, param_format=b.PARAMS_BF16)
     dev = "cuda"
     if args.workload == "append":
-        return bench_append(args, torch, b, synth, build_device_cache)
+        return emit(bench_append(args, torch, b, synth, build_device_cache))
     if args.workload == "latent":
-        return bench_latent(args, torch, b, synth, build_device_cache)
+        return emit(bench_latent(args, torch, b, synth, build_device_cache))
     if args.workload == "per-head":
-        return bench_per_head(args, torch, b, synth, build_device_cache)
+        return emit(bench_per_head(args, torch, b, synth, build_device_cache))
     if args.workload == "llama":
-        return bench_llama(args, torch, b, synth, build_device_cache)
+        return emit(bench_llama(args, torch, b, synth, build_device_cache))
     if args.workload == "tiny":
-        return bench_tiny(args, torch, b, synth, build_device_cache)
+        return emit(bench_tiny(args, torch, b, synth, build_device_cache))
     if args.workload == "restore":
         return bench_restore(args, torch, b, synth, build_device_cache)
     if args.workload == "mixed-step":
@@ -615,7 +718,7 @@ def main():
 
     # the same step as one call per layer, recorded once into a graph and replayed (launch-bound form of the loop)
     per_layer_ms = None
-    if args.per_layer_graph:
+    if not args.no_per_layer_graph:
         per_layer_ms = per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, window, out)
 
     res = {
@@ -632,21 +735,72 @@ def main():
         "decode_ms": dec_ms, "decode_us": dec_ms * 1e3, "decode_ms_p10": percentile(dec, 10), "decode_ms_p90": percentile(dec, 90),
         "decode_ms_min": min(dec), "decode_ms_mean": sum(dec) / len(dec), "decode_bytes": decode_bytes,
         "read_probe_GBps": probe_gbps, "pct_of_read_probe": 100.0 * gbps / probe_gbps,
-        "per_layer_graph_ms": per_layer_ms, "seed": w.seed,
+        "per_layer_graph_ms": per_layer_ms,
+        "per_layer_graph_GBps": None if per_layer_ms is None else decode_bytes / (per_layer_ms * 1e-3) / 1e9,
+        "per_layer_graph_frac_of_hbm_peak": None if per_layer_ms is None
+        else decode_bytes / (per_layer_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "per_layer_graph_note": "the same decode step as 48 calls of one layer each (what a forward pass issues), "
+                                "recorded into a graph and replayed; every replay bit-identical to the eager calls",
+        "seed": w.seed,
         "quantize_ms": qua_ms, "quantize_GBps": quant_bytes / (qua_ms * 1e-3) / 1e9,
         "dequantize_ms": deq_ms, "dequantize_GBps": quant_bytes / (deq_ms * 1e-3) / 1e9,
         # traffic: HBM bytes of one launch of the dominant kernel, from the committed rocprofv3 counter runs (they
         # cannot be taken inside this process); only for the exact workload those runs measured
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC["decode"] if args.layer_windows == "global" and not args.split_tokens
+                     "traffic": traffic_for(w.name)[0] if args.layer_windows == "global" and not args.split_tokens
                      else None,
-                     "traffic_source": "profiles/decode_attention_gemma10_ragged.md (FETCH_SIZE + WRITE_SIZE, scaled)",
-                     "kernel": "decode_attention_kernel<256,256,2,false> (+ combine_kernel in the same call)"},
+                     "traffic_source": traffic_for(w.name)[1],
+                     "kernel": "decode_attention_kernel<256,256,2,false> (+ plan_kernel in the same call)"},
+        "roofline_quantize": {"bound": "hbm", "achieved": quant_bytes / (qua_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+                              "unit": "GB/s", "frac": quant_bytes / (qua_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                              "traffic": traffic_for("quantize_4k_cache")[0],
+                              "traffic_source": traffic_for("quantize_4k_cache")[1], "kernel": "quantize_kernel<false>"},
+        "roofline_dequantize": {"bound": "hbm", "achieved": quant_bytes / (deq_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS,
+                                "unit": "GB/s", "frac": quant_bytes / (deq_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                "traffic": traffic_for("dequantize_4k_cache")[0],
+                                "traffic_source": traffic_for("dequantize_4k_cache")[1],
+                                "kernel": "dequantize_kernel<false>"},
     }
     if not args.skip_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, [0, w.num_layers // 3, 2 * w.num_layers // 3, w.num_layers - 1])
+        # the oracle's codec on the same 4,096-token cache, and the round trip checked against the GPU rows
+        codec, back = cpu_baseline_codec(fresh.cpu().numpy())
+        codec["gpu_dequantize_equals_oracle"] = bool((restored.cpu().numpy().view("uint16") == back.view("uint16").reshape(restored.shape)).all())
+        res["cpu_baseline"]["codec"] = codec
+        del back
+    if not args.skip_other_configs:
+        del kpool, vpool, fresh, restored, codes, scale, bias, ws, out, q
+        torch.cuda.empty_cache()
+        res["other_configs"] = other_configs(args, torch, b, synth, build_device_cache)
     emit(res)
+
+
+def compact(res):
+    """What the headline line keeps of another configuration's result."""
+    keep = ("metric", "value", "unit", "dtype", "agent_tokens_per_s", "decode_ms", "decode_us", "attention_ms", "append_ms",
+            "append_GBps", "pct_of_hbm_peak", "matrix_TFLOPs", "attention_flops", "decode_bytes", "steps", "warmup",
+            "roofline", "cpu_baseline")
+    out = {"workload": res["config"]["workload"]}
+    out.update({k: res[k] for k in keep if k in res})
+    return out
+
+
+def other_configs(args, torch, b, synth, build_device_cache):
+    """The other four benchmark configurations, one after the other with their caches freed in between: the
+    1-agent latency case, the Llama-shaped and the shared-latent decode steps, and the chunked append."""
+    runs = [("tiny", bench_tiny, dict(steps=max(args.steps, 50), warmup=max(args.warmup, 10))),
+            ("llama", bench_llama, dict(steps=max(args.steps, 50), warmup=max(args.warmup, 10))),
+            ("latent", bench_latent, dict(steps=max(min(args.steps, 30), 10), warmup=max(min(args.warmup, 5), 3))),
+            ("append", bench_append, dict(steps=max(min(args.steps, 5), 3), warmup=2))]
+    out = []
+    for name, fn, kw in runs:
+        try:
+            out.append(compact(fn(args, torch, b, synth, build_device_cache, **kw)))
+        except Exception as e:           # a failure here must not cost the headline line
+            out.append({"workload": name, "error": f"{type(e).__name__}: {e}"})
+        torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":
