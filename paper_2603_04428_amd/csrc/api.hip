@@ -154,7 +154,7 @@ int q4kv_quantize_fmt(const uint16_t *x, int64_t rows, int32_t dim, int32_t para
     if (!x || !codes || !scale || !bias) return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(x) || !aligned16(codes)) return fail(Q4KV_EINVAL, "x and codes must be 16-byte aligned");
     hipError_t e = q4kv::launch_quantize(x, rows, dim, param_format == Q4KV_PARAMS_BF16, codes, scale, bias,
-                                         (hipStream_t)hip_stream);
+                                         compute_units(), (hipStream_t)hip_stream);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "quantize launch: %s", hipGetErrorString(e));
 }
 
@@ -175,7 +175,7 @@ int q4kv_dequantize_fmt(const uint32_t *codes, const uint16_t *scale, const uint
     if (!x || !codes || !scale || !bias) return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(x) || !aligned16(codes)) return fail(Q4KV_EINVAL, "x and codes must be 16-byte aligned");
     hipError_t e = q4kv::launch_dequantize(codes, scale, bias, rows, dim, param_format == Q4KV_PARAMS_BF16, x,
-                                           (hipStream_t)hip_stream);
+                                           compute_units(), (hipStream_t)hip_stream);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "dequantize launch: %s", hipGetErrorString(e));
 }
 
@@ -207,11 +207,8 @@ int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, c
         return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(k_new) || (v_new && !aligned16(v_new))) return fail(Q4KV_EINVAL, "k_new/v_new must be 16-byte aligned");
     hipStream_t st = (hipStream_t)hip_stream;
-    hipError_t e = q4kv::launch_append(*spec, *k, spec->k_dim, k_new, block_table, max_blocks, seq_len_before,
-                                       num_agents, chunk_len, layer_begin, layer_end, st);
-    if (e == hipSuccess && !spec->v_aliases_k)
-        e = q4kv::launch_append(*spec, *v, spec->v_dim, v_new, block_table, max_blocks, seq_len_before, num_agents,
-                                chunk_len, layer_begin, layer_end, st);
+    hipError_t e = q4kv::launch_append(*spec, *k, spec->v_aliases_k ? nullptr : v, k_new, v_new, block_table, max_blocks,
+                                       seq_len_before, num_agents, chunk_len, layer_begin, layer_end, compute_units(), st);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "append launch: %s", hipGetErrorString(e));
 }
 

@@ -13,9 +13,7 @@ namespace q4kv {
 namespace {
 
 constexpr int kThreads = 256;
-#ifndef Q4KV_CODEC_WG_PER_CU
-#define Q4KV_CODEC_WG_PER_CU 8 // measured best for the read+write mix (4, 8, 16, 32 tried)
-#endif
+constexpr int kWorkgroupsPerCu = 8; // measured best for the read+write mix (4, 8, 16, 32 tried)
 
 #pragma clang fp contract(off)
 
@@ -122,17 +120,34 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
                                                             uint16_t *__restrict__ bias)
 {
     const int sub = threadIdx.x & 7;
-    const int64_t stride = (int64_t)gridDim.x * (kThreads / 8);
-    const int generation = blockIdx.x / max(1u, gridDim.x / Q4KV_CODEC_WG_PER_CU);
-    for (int64_t grp = (int64_t)blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); grp < total_groups; grp += stride) {
+    const int generation = blockIdx.x / max(1u, gridDim.x / kWorkgroupsPerCu);
+    // A workgroup takes 64 consecutive groups per round, two per octet of lanes, both loads issued before either is
+    // used: the 128 bytes of the round's scales (and of its biases) are one line written by one compute unit.  With
+    // 32 groups per round two workgroups, usually on different compute dies, shared each such line, and the memory
+    // system wrote it in pieces (7 % more bytes written than stored).
+    const int64_t rounds = (total_groups + 63) / 64;
+    for (int64_t c = blockIdx.x; c < rounds; c += gridDim.x) {
         rotate_wave_priority(generation);
-        const uint4 raw = *reinterpret_cast<const uint4 *>(x + grp * kGroup + sub * 8);
+        const int64_t g0 = c * 64 + (threadIdx.x >> 3), g1 = g0 + 32;
+        uint4 raw0 = make_uint4(0, 0, 0, 0), raw1 = make_uint4(0, 0, 0, 0);
+        if (g0 < total_groups) raw0 = *reinterpret_cast<const uint4 *>(x + g0 * kGroup + sub * 8);
+        if (g1 < total_groups) raw1 = *reinterpret_cast<const uint4 *>(x + g1 * kGroup + sub * 8);
         uint16_t sb, bb;
-        const uint32_t word = quantize_octet<BF>(raw, sub, &sb, &bb);
-        codes[grp * 8 + sub] = word;
-        if (sub == 0) {
-            scale[grp] = sb;
-            bias[grp] = bb;
+        if (g0 < total_groups) {
+            const uint32_t word = quantize_octet<BF>(raw0, sub, &sb, &bb);
+            codes[g0 * 8 + sub] = word;
+            if (sub == 0) {
+                scale[g0] = sb;
+                bias[g0] = bb;
+            }
+        }
+        if (g1 < total_groups) {
+            const uint32_t word = quantize_octet<BF>(raw1, sub, &sb, &bb);
+            codes[g1 * 8 + sub] = word;
+            if (sub == 0) {
+                scale[g1] = sb;
+                bias[g1] = bb;
+            }
         }
     }
 }
@@ -141,47 +156,81 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
 // destination the agent's blocks.  Layer and agent come from the launch grid, so that a lane's index arithmetic is
 // two 32-bit divisions (by the groups per row and by the chunk length) instead of a chain of 64-bit ones; a token
 // outside the table or a block id outside the pool is skipped.
+// One launch serves the K and the V pool (two short launches one after the other each paid their own ramp and
+// tail): the upper half of the grid's z range belongs to the second pool.
+struct AppendPool {
+    const uint16_t *x;
+    uint32_t *codes;
+    uint16_t *scale, *bias;
+    int groups_per_row;
+};
 struct AppendParams {
+    AppendPool pool[2];
     const int32_t *block_table;
     const int32_t *seq_len_before;
-    int max_blocks, chunk_len, heads, layer_begin, num_blocks, groups_per_row;
+    int max_blocks, chunk_len, heads, layer_begin, num_blocks, layers;
 };
 
 template <bool BF>
-__global__ __launch_bounds__(kThreads) void append_kernel(const uint16_t *__restrict__ x, uint32_t *__restrict__ codes,
-                                                          uint16_t *__restrict__ scale, uint16_t *__restrict__ bias,
-                                                          AppendParams p)
+__global__ __launch_bounds__(kThreads) void append_kernel(AppendParams pp)
 {
     const int sub = threadIdx.x & 7;
-    const int a = blockIdx.y, li = blockIdx.z, agents = gridDim.y;
+    const int which = blockIdx.z >= (unsigned)pp.layers ? 1 : 0;
+    const int a = blockIdx.y, li = blockIdx.z - which * pp.layers, agents = gridDim.y;
+    struct {
+        const int32_t *block_table, *seq_len_before;
+        int max_blocks, chunk_len, heads, layer_begin, num_blocks, groups_per_row;
+    } p = {pp.block_table, pp.seq_len_before, pp.max_blocks, pp.chunk_len, pp.heads, pp.layer_begin, pp.num_blocks,
+           pp.pool[which].groups_per_row};
+    const uint16_t *__restrict__ x = pp.pool[which].x;
+    uint32_t *__restrict__ codes = pp.pool[which].codes;
+    uint16_t *__restrict__ scale = pp.pool[which].scale, *__restrict__ bias = pp.pool[which].bias;
     const uint32_t per_unit = (uint32_t)p.chunk_len * p.heads * p.groups_per_row; // groups of one (layer, agent)
     const int64_t src0 = ((int64_t)li * agents + a) * per_unit;
     const int n0 = p.seq_len_before[a];
     const int32_t *table = p.block_table + (int64_t)a * p.max_blocks;
     // generations of the launch: workgroups in launch order (x fastest), about 256 of them per generation
     const uint32_t linear = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-    const int generation = linear / max(1u, gridDim.x * gridDim.y * gridDim.z / Q4KV_CODEC_WG_PER_CU);
-    for (uint32_t gi = blockIdx.x * (kThreads / 8) + (threadIdx.x >> 3); gi < per_unit; gi += gridDim.x * (kThreads / 8)) {
+    const int generation = linear / max(1u, gridDim.x * gridDim.y * gridDim.z / kWorkgroupsPerCu);
+    // 64 consecutive groups per workgroup and round, two per octet of lanes, as in quantize_kernel
+    for (uint32_t c0 = blockIdx.x * 64; c0 < per_unit; c0 += gridDim.x * 64) {
         rotate_wave_priority(generation);
         // groups are walked in the order of the pool (head, then chunk token, then group): consecutive lanes then
-        // write consecutive rows of one head's plane of a block, and read whole 2 dim-byte source rows
-        const uint32_t row = gi / (uint32_t)p.groups_per_row, g = gi - row * p.groups_per_row;
-        const uint32_t h = row / (uint32_t)p.chunk_len, c = row - h * p.chunk_len;
-        const uint32_t src = (c * p.heads + h) * p.groups_per_row + g;
-        const uint4 raw = *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8);
-        uint16_t sb, bb;
-        const uint32_t word = quantize_octet<BF>(raw, sub, &sb, &bb);
-        const int t = n0 + (int)c;
-        const int bi = t / kBlockTokens;
-        if (t < 0 || bi >= p.max_blocks) continue;
-        const int blk = table[bi];
-        if (blk < 0 || blk >= p.num_blocks) continue;
-        const int64_t drow = (((int64_t)(p.layer_begin + li) * p.num_blocks + blk) * p.heads + h) * kBlockTokens + (t % kBlockTokens);
-        const int64_t dgrp = drow * p.groups_per_row + g;
-        codes[dgrp * 8 + sub] = word;
-        if (sub == 0) {
-            scale[dgrp] = sb;
-            bias[dgrp] = bb;
+        // write consecutive rows of one head's plane of a block, and read whole 2 dim-byte source rows.  (Walking
+        // them in source order instead, a contiguous span per workgroup -- contiguous reads, scattered rows written
+        // -- was measured slower: 0.69 against 0.65 ms on the 10-agent, 48-layer chunk.)
+        uint32_t h[2], c[2], g[2];
+        uint4 raw[2];
+        bool in[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t gi = c0 + 32 * j + (threadIdx.x >> 3);
+            in[j] = gi < per_unit;
+            const uint32_t row = gi / (uint32_t)p.groups_per_row;
+            g[j] = gi - row * p.groups_per_row;
+            h[j] = row / (uint32_t)p.chunk_len;
+            c[j] = row - h[j] * p.chunk_len;
+            const uint32_t src = (c[j] * p.heads + h[j]) * p.groups_per_row + g[j];
+            raw[j] = in[j] ? *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (!in[j]) continue;
+            uint16_t sb, bb;
+            const uint32_t word = quantize_octet<BF>(raw[j], sub, &sb, &bb);
+            const int t = n0 + (int)c[j];
+            const int bi = t / kBlockTokens;
+            if (t < 0 || bi >= p.max_blocks) continue;
+            const int blk = table[bi];
+            if (blk < 0 || blk >= p.num_blocks) continue;
+            const int64_t drow =
+                (((int64_t)(p.layer_begin + li) * p.num_blocks + blk) * p.heads + h[j]) * kBlockTokens + (t % kBlockTokens);
+            const int64_t dgrp = drow * p.groups_per_row + g[j];
+            codes[dgrp * 8 + sub] = word;
+            if (sub == 0) {
+                scale[dgrp] = sb;
+                bias[dgrp] = bb;
+            }
         }
     }
 }
@@ -193,31 +242,47 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
                                                               const uint16_t *__restrict__ bias, int64_t total_words,
                                                               uint16_t *__restrict__ x)
 {
+    // A workgroup takes 1,024 consecutive words (128 groups) per round, four per lane, every load issued before the
+    // first is used; the round's scales and biases are two whole lines read by one compute unit.
+    constexpr int NQ = 4;
+    typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
     const int64_t stride = (int64_t)gridDim.x * kThreads;
-    const int generation = blockIdx.x / max(1u, gridDim.x / Q4KV_CODEC_WG_PER_CU);
-    for (int64_t w = (int64_t)blockIdx.x * kThreads + threadIdx.x; w < total_words; w += stride) {
+    const int generation = blockIdx.x / max(1u, gridDim.x / kWorkgroupsPerCu);
+    for (int64_t w0 = (int64_t)blockIdx.x * NQ * kThreads + threadIdx.x; w0 < total_words; w0 += NQ * stride) {
         rotate_wave_priority(generation);
-        const uint32_t word = codes[w];
-        const float s = param_bits_to_float<BF>(scale[w >> 3]);
-        const float b = param_bits_to_float<BF>(bias[w >> 3]);
-        uint32_t o[4];
+        uint32_t word[NQ];
+        uint16_t sb[NQ], bb[NQ];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float lo = (float)((word >> (8 * i)) & 0xfu) * s + b;      // product exact in binary32
-            const float hi = (float)((word >> (8 * i + 4)) & 0xfu) * s + b;
-            o[i] = (uint32_t)float_to_half_bits(lo) | ((uint32_t)float_to_half_bits(hi) << 16);
+        for (int j = 0; j < NQ; ++j) {
+            const int64_t w = w0 + j * kThreads;
+            const bool in = w < total_words;
+            word[j] = in ? codes[w] : 0u;
+            sb[j] = in ? scale[w >> 3] : (uint16_t)0;
+            bb[j] = in ? bias[w >> 3] : (uint16_t)0;
         }
-        // a store that says the line will not be read again: +4 % (4.85 -> 5.05 TB/s); the same hint on the loads
-        // changes nothing, and on either side of the quantize kernel it costs 6-9 %
-        typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
-        __builtin_nontemporal_store(u4_t{o[0], o[1], o[2], o[3]}, reinterpret_cast<u4_t *>(x + w * 8));
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            const int64_t w = w0 + j * kThreads;
+            if (w >= total_words) break;
+            const float s = param_bits_to_float<BF>(sb[j]), b = param_bits_to_float<BF>(bb[j]);
+            uint32_t o[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float lo = (float)((word[j] >> (8 * i)) & 0xfu) * s + b;      // product exact in binary32
+                const float hi = (float)((word[j] >> (8 * i + 4)) & 0xfu) * s + b;
+                o[i] = (uint32_t)float_to_half_bits(lo) | ((uint32_t)float_to_half_bits(hi) << 16);
+            }
+            // a store that says the line will not be read again: +4 % (4.85 -> 5.05 TB/s); the same hint on the
+            // loads changes nothing, and on either side of the quantize kernel it costs 6-9 %
+            __builtin_nontemporal_store(u4_t{o[0], o[1], o[2], o[3]}, reinterpret_cast<u4_t *>(x + w * 8));
+        }
     }
 }
 
-int grid_for(int64_t items, int per_block)
+int grid_for(int64_t items, int per_block, int compute_units)
 {
     int64_t blocks = (items + per_block - 1) / per_block;
-    const int64_t cap = 256 * Q4KV_CODEC_WG_PER_CU; // the kernels grid-stride
+    const int64_t cap = (int64_t)compute_units * kWorkgroupsPerCu; // the kernels grid-stride
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
     return (int)blocks;
@@ -226,12 +291,12 @@ int grid_for(int64_t items, int per_block)
 } // namespace
 
 hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, bool bf16_params, uint32_t *codes, uint16_t *scale,
-                           uint16_t *bias, hipStream_t stream)
+                           uint16_t *bias, int compute_units, hipStream_t stream)
 {
     const int G = dim / kGroup;
     const int64_t groups = rows * G;
     if (groups == 0) return hipSuccess;
-    const dim3 grid(grid_for(groups, kThreads / 8));
+    const dim3 grid(grid_for(groups, 64, compute_units));
     if (bf16_params)
         hipLaunchKernelGGL(quantize_kernel<true>, grid, dim3(kThreads), 0, stream, x, groups, codes, scale, bias);
     else
@@ -240,11 +305,11 @@ hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, bool bf16_p
 }
 
 hipError_t launch_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
-                             int dim, bool bf16_params, uint16_t *x, hipStream_t stream)
+                             int dim, bool bf16_params, uint16_t *x, int compute_units, hipStream_t stream)
 {
     const int64_t words = rows * (dim / 8);
     if (words == 0) return hipSuccess;
-    const dim3 grid(grid_for(words, kThreads));
+    const dim3 grid(grid_for(words, 4 * kThreads, compute_units));
     if (bf16_params)
         hipLaunchKernelGGL(dequantize_kernel<true>, grid, dim3(kThreads), 0, stream, codes, scale, bias, words, x);
     else
@@ -252,27 +317,39 @@ hipError_t launch_dequantize(const uint32_t *codes, const uint16_t *scale, const
     return hipGetLastError();
 }
 
-hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &pool, int dim, const uint16_t *x_new,
-                         const int32_t *block_table, int max_blocks, const int32_t *seq_len_before, int num_agents,
-                         int chunk_len, int layer_begin, int layer_end, hipStream_t stream)
+hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &k, const q4kv_pool *v, const uint16_t *k_new,
+                         const uint16_t *v_new, const int32_t *block_table, int max_blocks,
+                         const int32_t *seq_len_before, int num_agents, int chunk_len, int layer_begin, int layer_end,
+                         int compute_units, hipStream_t stream)
 {
-    const int G = dim / kGroup;
     const int layers = layer_end - layer_begin;
-    const int64_t per_unit = (int64_t)chunk_len * spec.num_kv_heads * G;
+    const int pools = v ? 2 : 1;
+    const int gk = spec.k_dim / kGroup, gv = v ? spec.v_dim / kGroup : 0;
+    const int64_t per_unit = (int64_t)chunk_len * spec.num_kv_heads * (gk > gv ? gk : gv); // of the wider pool
     if (layers <= 0 || num_agents <= 0 || per_unit == 0) return hipSuccess;
-    if (per_unit > 0x7fffffffLL || num_agents > 65535 || layers > 65535) return hipErrorInvalidValue;
-    AppendParams p{block_table, seq_len_before, max_blocks, chunk_len, spec.num_kv_heads, layer_begin, pool.num_blocks, G};
-    // workgroups per (layer, agent): enough for the chunk, and at most 8 per compute unit over the whole launch
-    // (rounded down: a launch of 1.2 rounds takes as long as one of 2)
-    int64_t gx = (per_unit + kThreads / 8 - 1) / (kThreads / 8);
-    const int64_t cap = 256LL * Q4KV_CODEC_WG_PER_CU / ((int64_t)layers * num_agents);
+    if (per_unit > 0x7fffffffLL || num_agents > 65535 || pools * layers > 65535) return hipErrorInvalidValue;
+    AppendParams p;
+    p.pool[0] = AppendPool{k_new, k.codes, k.scale, k.bias, gk};
+    p.pool[1] = v ? AppendPool{v_new, v->codes, v->scale, v->bias, gv} : p.pool[0];
+    p.block_table = block_table;
+    p.seq_len_before = seq_len_before;
+    p.max_blocks = max_blocks;
+    p.chunk_len = chunk_len;
+    p.heads = spec.num_kv_heads;
+    p.layer_begin = layer_begin;
+    p.num_blocks = k.num_blocks;
+    p.layers = layers;
+    // workgroups per (pool, layer, agent): enough for the chunk, and at most 8 per compute unit over the whole
+    // launch (rounded down: a launch of 1.2 rounds takes as long as one of 2)
+    int64_t gx = (per_unit + 63) / 64;
+    const int64_t cap = (int64_t)compute_units * kWorkgroupsPerCu / ((int64_t)pools * layers * num_agents);
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
-    const dim3 grid((unsigned)gx, (unsigned)num_agents, (unsigned)layers);
+    const dim3 grid((unsigned)gx, (unsigned)num_agents, (unsigned)(pools * layers));
     if (spec.param_format == Q4KV_PARAMS_BF16)
-        hipLaunchKernelGGL(append_kernel<true>, grid, dim3(kThreads), 0, stream, x_new, pool.codes, pool.scale, pool.bias, p);
+        hipLaunchKernelGGL(append_kernel<true>, grid, dim3(kThreads), 0, stream, p);
     else
-        hipLaunchKernelGGL(append_kernel<false>, grid, dim3(kThreads), 0, stream, x_new, pool.codes, pool.scale, pool.bias, p);
+        hipLaunchKernelGGL(append_kernel<false>, grid, dim3(kThreads), 0, stream, p);
     return hipGetLastError();
 }
 

@@ -168,7 +168,7 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
         for (int i = 0; i < kLoads; i += 4) {
             const uint32_t *s4k = src + i * (kWave * 4);
             const uint32_t d4k = dst + i * 1024;
-            asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(s4k), "s"(d4k) : "memory", "m0");
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(s4k), "s"(d4k) : "memory", "m0");
             if (i + 1 < kLoads)
                 asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" ::"v"(lane_off), "s"(s4k) : "memory");
             if (i + 2 < kLoads)
@@ -325,10 +325,7 @@ __global__ __launch_bounds__(kThreads, 1) void mla_decode_kernel(const MlaParams
             const float c_code = p.score_scale * kCodeScaleA;
             const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
             SetIn set_in = load_set(0, 0);
-#ifndef Q4KV_MLA_RING
-#define Q4KV_MLA_RING 2
-#endif
-            constexpr int kRing = Q4KV_MLA_RING;
+            constexpr int kRing = 2; // deeper rings (3, 4) were measured and change nothing
             GroupIn grp_in[kRing]; // a ring of the next value steps
 #pragma unroll
             for (int set = 0; set < 4; ++set) {

@@ -8,14 +8,16 @@
 
 namespace q4kv {
 
-// bf16_params: scale and bias are bfloat16 bit patterns instead of binary16 ones
+// bf16_params: scale and bias are bfloat16 bit patterns instead of binary16 ones; compute_units sizes the launch
 hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, bool bf16_params, uint32_t *codes, uint16_t *scale,
-                           uint16_t *bias, hipStream_t stream);
+                           uint16_t *bias, int compute_units, hipStream_t stream);
 hipError_t launch_dequantize(const uint32_t *codes, const uint16_t *scale, const uint16_t *bias, int64_t rows,
-                             int dim, bool bf16_params, uint16_t *x, hipStream_t stream);
-hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &pool, int dim, const uint16_t *x_new,
-                         const int32_t *block_table, int max_blocks, const int32_t *seq_len_before, int num_agents,
-                         int chunk_len, int layer_begin, int layer_end, hipStream_t stream);
+                             int dim, bool bf16_params, uint16_t *x, int compute_units, hipStream_t stream);
+// v, v_new: null when the V rows alias the K rows
+hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &k, const q4kv_pool *v, const uint16_t *k_new,
+                         const uint16_t *v_new, const int32_t *block_table, int max_blocks,
+                         const int32_t *seq_len_before, int num_agents, int chunk_len, int layer_begin, int layer_end,
+                         int compute_units, hipStream_t stream);
 
 struct AttentionArgs {
     q4kv_spec spec;

@@ -14,13 +14,9 @@ constexpr int kProbeTile = 16384; // bytes a wave reads per step: two halves of 
 // the decode kernel's load: 16 bytes, marked non-temporal (the data is read once)
 __device__ __forceinline__ uint4 probe_load(const uint4 *p)
 {
-#ifdef Q4KV_PROBE_PLAIN
-    return *p;
-#else
     typedef uint32_t u4_t __attribute__((ext_vector_type(4)));
     const u4_t t = __builtin_nontemporal_load(reinterpret_cast<const u4_t *>(p));
     return make_uint4(t.x, t.y, t.z, t.w);
-#endif
 }
 
 __global__ __launch_bounds__(kProbeThreads, 2) void read_probe_kernel(const uint4 *__restrict__ src, long long tiles,

@@ -57,8 +57,10 @@ PER_HEAD_MLA = [
 ]
 
 
+# split_tokens 4,096 makes a workgroup's range long enough (64 tiles) for the kernel's other way of sharing it out: a
+# contiguous quarter per wave instead of tiles in turn
 @pytest.mark.parametrize("shape", SMALL + PER_HEAD_MLA)
-@pytest.mark.parametrize("split_tokens", [0, 256, 512])
+@pytest.mark.parametrize("split_tokens", [0, 256, 512, 4096])
 def test_decode_matches_oracle_small(shape, split_tokens):
     L, Hq, Hkv, D, lens = shape
     Dk, Dv = D if isinstance(D, tuple) else (D, D)
@@ -357,3 +359,31 @@ def test_decode_tolerance_with_wide_value_groups(shape, param_format):
     got = run_gpu(w, spec, kpool, vpool, table_d, list(w.seq_lens), split_tokens=256)
     want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, list(w.seq_lens), w.sm_scale)
     assert_close(got, want, f"{shape} long format {param_format}")
+
+
+MANY_RECORDS = [
+    # layers, Hq, Hkv, D, seq_lens: one or two long units cut into 4-tile ranges -- 20 to 36 records per unit, more than
+    # the 16 the merge loads in one batch -- beside short and empty ones
+    (1, 4, 1, 128, (5000,)),
+    (1, 2, 1, 256, (9000, 0, 4100)),
+    (2, 8, 2, 64, (6000, 70)),
+    (1, 4, 4, (192, 128), (5200,)),
+]
+
+
+@pytest.mark.parametrize("shape", MANY_RECORDS)
+@pytest.mark.parametrize("split_tokens", [256, 1024, 4096])
+def test_units_shared_by_many_workgroups(shape, split_tokens):
+    L, Hq, Hkv, D, lens = shape
+    Dk, Dv = D if isinstance(D, tuple) else (D, D)
+    w = synth.small(41, L, Hq, Hkv, Dk, Dv, False, lens)
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    ospec, okp, ovp, otable = host_cache(w)
+    q = w.q_all().numpy()
+    got = run_gpu(w, spec, kpool, vpool, table_d, list(lens), split_tokens)
+    assert_close(got, oracle.attention(ospec, okp, ovp, q, otable, list(lens), w.sm_scale), f"{shape} split {split_tokens}")
+    again = run_gpu(w, spec, kpool, vpool, table_d, list(lens), split_tokens)
+    assert np.array_equal(got.view(np.uint16), again.view(np.uint16)), "records are merged in record order: identical reruns"
+    win = run_gpu(w, spec, kpool, vpool, table_d, list(lens), split_tokens, window=3000)
+    assert_close(win, oracle.attention(ospec, okp, ovp, q, otable, list(lens), w.sm_scale, window=3000),
+                 f"{shape} split {split_tokens} window 3000")
