@@ -234,10 +234,13 @@ def percentile(xs, q):
     return xs[lo] + (xs[hi] - xs[lo]) * (pos - lo)
 
 
-def per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, window, out_all_layers):
+def per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, window, out_all_layers, planned=True):
     """One attention call per layer, captured into a graph; returns the median replay time in ms.  Every replay is
-    checked against the eager per-layer result (bit-identical: the same launches)."""
+    checked against the eager per-layer result (bit-identical: the same launches).  planned: the work plan is made
+    once per step (q4kv_decode_plan) and every layer's call is a q4kv_batched_attention_planned; else 48 plain calls."""
     L = w.num_layers
+    if isinstance(window, list):
+        planned = False          # one window per layer: the layers do not share a plan
     split = b.q4kv_default_split_tokens(spec, w.num_agents, 1, max_len, 1)
     ws = torch.empty(b.q4kv_attention_workspace_bytes(spec, w.num_agents, 1, max_len, split, 1), dtype=torch.uint8,
                      device=q.device)
@@ -245,9 +248,15 @@ def per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, w
     win = window if isinstance(window, list) else [window] * L
 
     def all_layers():
+        if planned:
+            b.q4kv_decode_plan(spec, seq, max_len, ws, window=win[0], split_tokens=split, layers_in_call=1)
         for l in range(L):
-            b.q4kv_batched_attention(spec, kpool, vpool, q[l:l + 1], table_d, seq, max_len, w.sm_scale, win[l], split,
-                                     l, l + 1, out[l:l + 1], ws)
+            if planned:
+                b.q4kv_batched_attention_planned(spec, kpool, vpool, q[l:l + 1], out[l:l + 1], table_d, max_len, w.sm_scale,
+                                                 ws, window=win[0], split_tokens=split, layer_begin=l, layer_end=l + 1)
+            else:
+                b.q4kv_batched_attention(spec, kpool, vpool, q[l:l + 1], table_d, seq, max_len, w.sm_scale, win[l], split,
+                                         l, l + 1, out[l:l + 1], ws)
 
     all_layers()
     torch.cuda.synchronize()
@@ -717,9 +726,11 @@ def main():
     probe_gbps = probe_bytes / (percentile(probe, 50) * 1e-3) / 1e9
 
     # the same step as one call per layer, recorded once into a graph and replayed (launch-bound form of the loop)
-    per_layer_ms = None
+    per_layer_ms = per_layer_plain_ms = None
     if not args.no_per_layer_graph:
         per_layer_ms = per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, window, out)
+        per_layer_plain_ms = per_layer_graph(torch, b, spec, kpool, vpool, q, table_d, seq, max_len, w, window, out,
+                                             planned=False)
 
     res = {
         "metric": "Q4 KV decode-attention achieved HBM GB/s (% of peak) + agent-tokens/s",
@@ -739,8 +750,12 @@ def main():
         "per_layer_graph_GBps": None if per_layer_ms is None else decode_bytes / (per_layer_ms * 1e-3) / 1e9,
         "per_layer_graph_frac_of_hbm_peak": None if per_layer_ms is None
         else decode_bytes / (per_layer_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "per_layer_graph_plain_calls_ms": per_layer_plain_ms,
         "per_layer_graph_note": "the same decode step as 48 calls of one layer each (what a forward pass issues), "
-                                "recorded into a graph and replayed; every replay bit-identical to the eager calls",
+                                "recorded into a graph and replayed; every replay bit-identical to the eager calls.  "
+                                "per_layer_graph_ms: q4kv_decode_plan once + 48 q4kv_batched_attention_planned (one "
+                                "kernel each); per_layer_graph_plain_calls_ms: 48 q4kv_batched_attention (plan kernel + "
+                                "attention kernel each)",
         "seed": w.seed,
         "quantize_ms": qua_ms, "quantize_GBps": quant_bytes / (qua_ms * 1e-3) / 1e9,
         "dequantize_ms": deq_ms, "dequantize_GBps": quant_bytes / (deq_ms * 1e-3) / 1e9,

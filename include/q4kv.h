@@ -161,6 +161,28 @@ int q4kv_batched_attention_windows(const q4kv_spec *spec, const q4kv_pool *k, co
                                    int32_t layer_begin, int32_t layer_end, void *workspace, size_t workspace_bytes,
                                    void *hip_stream);
 
+/* The decode step of a forward pass is one call per layer (the next layer's queries depend on this layer's output),
+ * all with the same lengths, and then the small kernel that turns seq_len[] into the launch's work plan is a tenth of
+ * every call.  These two entry points take it out of the loop (Sec. 3.4, the decode loop of a batch):
+ *   q4kv_decode_plan                writes the plan for calls of `num_layers_in_call` layers with these lengths, this
+ *                                   window (one for all layers, <= 0: global) and this split_tokens into `workspace`
+ *   q4kv_batched_attention_planned  q4kv_batched_attention with q_len == 1 on a workspace prepared that way: no
+ *                                   seq_len argument (the plan holds the lengths, clamped to max_seq_len), one kernel
+ * Every argument the two share must be the same in both calls (the layer range may differ from call to call, its
+ * length may not), and seq_len[] must not be relied on to have changed in between: the planned call attends to the
+ * lengths the plan was made from.  A workspace may be used for any number of planned calls on one stream, one after
+ * the other; when the lengths change (every decode step), plan again.  A workspace prepared for other arguments
+ * makes the planned call do nothing (it is detected on the device; `out` is left as it was).  Shapes, workspace size,
+ * error codes and results (bit-identical to q4kv_batched_attention with the same arguments) as described there. */
+int q4kv_decode_plan(const q4kv_spec *spec, const int32_t *seq_len, int32_t num_agents, int32_t max_seq_len,
+                     int32_t window, int32_t split_tokens, int32_t num_layers_in_call, void *workspace,
+                     size_t workspace_bytes, void *hip_stream);
+int q4kv_batched_attention_planned(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                                   uint16_t *out, const int32_t *block_table, int32_t max_blocks, int32_t num_agents,
+                                   int32_t max_seq_len, float sm_scale, int32_t window, int32_t split_tokens,
+                                   int32_t layer_begin, int32_t layer_end, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+
 /* For callers that cannot allocate device memory or have none to hand over -- code recording a HIP graph, tight
  * serving loops that call once per layer, harnesses that forbid hipMalloc: q4kv_batched_attention with the decode
  * path's workspace (tile plan and partial results) taken from a fixed array of Q4KV_STATIC_SCRATCH_BYTES bytes that

@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libq4kv.so")
 
 EXPORTS = ["q4kv_quantize", "q4kv_dequantize", "q4kv_quantize_fmt", "q4kv_dequantize_fmt", "q4kv_append", "q4kv_batched_attention",
-           "q4kv_batched_attention_windows", "q4kv_batched_attention_static", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_block_image_bytes", "q4kv_export_blocks", "q4kv_import_blocks", "q4kv_read_probe",
+           "q4kv_batched_attention_windows", "q4kv_batched_attention_static", "q4kv_decode_plan",
+           "q4kv_batched_attention_planned", "q4kv_attention_workspace_bytes", "q4kv_default_split_tokens", "q4kv_cache_bytes", "q4kv_block_image_bytes", "q4kv_export_blocks", "q4kv_import_blocks", "q4kv_read_probe",
            "q4kv_block_pool_create", "q4kv_block_pool_destroy", "q4kv_block_pool_reserve", "q4kv_block_pool_release",
            "q4kv_block_pool_blocks", "q4kv_block_pool_table_row", "q4kv_block_pool_touch", "q4kv_block_pool_pin",
            "q4kv_block_pool_lru_victim", "q4kv_block_pool_free_blocks", "q4kv_block_pool_owner",
@@ -67,6 +68,9 @@ def lib():
                                                      vp, C.c_size_t, vp]
         l.q4kv_batched_attention_static.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32,
                                                     vp, i32, i32, i32, C.c_float, i32, i32, i32, i32, vp]
+        l.q4kv_decode_plan.argtypes = [C.POINTER(Spec), vp, i32, i32, i32, i32, i32, vp, C.c_size_t, vp]
+        l.q4kv_batched_attention_planned.argtypes = [C.POINTER(Spec), C.POINTER(_CPool), C.POINTER(_CPool), vp, vp, vp, i32,
+                                                     i32, i32, C.c_float, i32, i32, i32, i32, vp, C.c_size_t, vp]
         l.q4kv_attention_workspace_bytes.restype = C.c_size_t
         l.q4kv_attention_workspace_bytes.argtypes = [C.POINTER(Spec), i32, i32, i32, i32, i32]
         l.q4kv_default_split_tokens.restype = i32
@@ -341,4 +345,25 @@ def q4kv_batched_attention_static(spec, kpool, vpool, q, out, block_table, seq_l
         _dev(out, torch.float16, "out"), _dev(block_table, torch.int32, "block_table"), block_table.shape[1],
         _dev(seq_len, torch.int32, "seq_len"), q.shape[1], q.shape[2], max_seq_len, float(sm_scale), int(window),
         int(split_tokens), layer_begin, layer_end, _stream()))
+    return out
+
+
+def q4kv_decode_plan(spec, seq_len, max_seq_len, workspace, window=0, split_tokens=0, layers_in_call=1):
+    """q4kv_decode_plan: prepare `workspace` (uint8 tensor on the GPU) for q4kv_batched_attention_planned calls."""
+    _check(lib().q4kv_decode_plan(C.byref(spec), _dev(seq_len, torch.int32, "seq_len"), seq_len.numel(), max_seq_len,
+                                  int(window), int(split_tokens), layers_in_call, C.c_void_p(workspace.data_ptr()),
+                                  workspace.numel(), _stream()))
+
+
+def q4kv_batched_attention_planned(spec, kpool, vpool, q, out, block_table, max_seq_len, sm_scale, workspace, window=0,
+                                   split_tokens=0, layer_begin=0, layer_end=None):
+    """q4kv_batched_attention_planned: decode attention (q_len 1) on a workspace prepared by q4kv_decode_plan."""
+    layer_end = spec.num_layers if layer_end is None else layer_end
+    kp = kpool.c()
+    vp = None if spec.v_aliases_k else vpool.c()
+    _check(lib().q4kv_batched_attention_planned(
+        C.byref(spec), C.byref(kp), None if vp is None else C.byref(vp), _dev(q, torch.float16, "q"),
+        _dev(out, torch.float16, "out"), _dev(block_table, torch.int32, "block_table"), block_table.shape[1], q.shape[1],
+        max_seq_len, float(sm_scale), int(window), int(split_tokens), layer_begin, layer_end,
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream()))
     return out

@@ -117,6 +117,19 @@ size_t plan_bytes(int num_agents, int layers)
     return (q4kv::decode_plan_ints(num_agents, layers) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
+// What a plan depends on besides seq_len[], folded into one word: kept in the plan and compared by the kernels, so
+// that a prepared workspace used with other arguments makes a planned call do nothing instead of walking a plan that
+// does not fit its tables.
+int plan_signature(const q4kv_spec &s, int num_agents, int max_seq_len, int layers, int split_tokens, int window,
+                   int workgroups)
+{
+    const int v[] = {s.num_q_heads, s.num_kv_heads, s.k_dim, s.v_dim, s.v_aliases_k, num_agents, max_seq_len, layers,
+                     split_tokens, window > 0 ? window : 0, workgroups};
+    uint32_t h = 0x9E3779B9u;
+    for (int x : v) h = (h ^ (uint32_t)x) * 0x01000193u + 0x7F4A7C15u;
+    return (int)(h | 1u); // never zero
+}
+
 // arrival counters, one per (layer, KV head, agent)
 size_t arrival_bytes(const q4kv_spec &s, int num_agents, int layers)
 {
@@ -240,11 +253,12 @@ size_t q4kv_attention_workspace_bytes(const q4kv_spec *spec, int32_t num_agents,
            (size_t)(units * slots * (spec->v_dim + 2) * (int64_t)sizeof(float));
 }
 
+// planned: the workspace already holds the plan of q4kv_decode_plan for these arguments (seq_len is then not needed)
 static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
                             uint16_t *out, const int32_t *block_table, int32_t max_blocks, const int32_t *seq_len,
                             int32_t num_agents, int32_t q_len, int32_t max_seq_len, float sm_scale, int32_t window,
                             const int32_t *layer_window, int32_t split_tokens, int32_t layer_begin, int32_t layer_end,
-                            void *workspace, size_t workspace_bytes, void *hip_stream)
+                            void *workspace, size_t workspace_bytes, void *hip_stream, bool planned = false)
 {
     int rc = check_spec(spec);
     if (rc) return rc;
@@ -263,7 +277,7 @@ static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4k
         return fail(Q4KV_ERANGE, "max_seq_len %d exceeds max_blocks*256 = %lld", max_seq_len,
                     (long long)max_blocks * 256);
     if (num_agents == 0 || layer_begin == layer_end) return Q4KV_OK;
-    if (!q || !out || !block_table || !seq_len) return fail(Q4KV_EINVAL, "NULL pointer");
+    if (!q || !out || !block_table || (!seq_len && !planned)) return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(q) || !aligned16(out)) return fail(Q4KV_EINVAL, "q and out must be 16-byte aligned");
     const int layers = layer_end - layer_begin;
     // the kernels number the 64-token tiles of a call with 32-bit integers
@@ -313,8 +327,12 @@ static int attention_common(const q4kv_spec *spec, const q4kv_pool *k, const q4k
     a.part_acc = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan_bytes(num_agents, layers) +
                                            arrival_bytes(*spec, num_agents, layers));
     a.part_ml = a.part_acc + units * a.max_slots * spec->v_dim;
+    a.plan_signature = plan_signature(*spec, num_agents, max_seq_len, layers, a.split_tokens, layer_window ? -1 : window,
+                                      a.grid_workgroups);
 
-    hipError_t e = mla ? q4kv::launch_mla_decode_attention(a, st) : q4kv::launch_decode_attention(a, st);
+    hipError_t e = hipSuccess;
+    if (!planned) e = mla ? q4kv::launch_mla_decode_plan(a, st) : q4kv::launch_decode_plan(a, st);
+    if (e == hipSuccess) e = mla ? q4kv::launch_mla_decode_attention(a, st) : q4kv::launch_decode_attention(a, st);
     return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "attention launch: %s", hipGetErrorString(e));
 }
 
@@ -387,6 +405,56 @@ int q4kv_batched_attention_static(const q4kv_spec *spec, const q4kv_pool *k, con
     return attention_common(spec, k, v, q, out, block_table, max_blocks, seq_len, num_agents, q_len, max_seq_len, sm_scale,
                             window, nullptr, split_tokens, layer_begin, layer_end, ptr, (size_t)Q4KV_STATIC_SCRATCH_BYTES,
                             hip_stream);
+}
+
+int q4kv_decode_plan(const q4kv_spec *spec, const int32_t *seq_len, int32_t num_agents, int32_t max_seq_len,
+                     int32_t window, int32_t split_tokens, int32_t num_layers_in_call, void *workspace,
+                     size_t workspace_bytes, void *hip_stream)
+{
+    int rc = check_spec(spec);
+    if (rc) return rc;
+    if (num_agents < 0 || max_seq_len < 0 || num_layers_in_call < 0) return fail(Q4KV_EINVAL, "bad counts");
+    if (split_tokens < 0 || split_tokens % 256) return fail(Q4KV_EINVAL, "split_tokens must be a multiple of 256");
+    if (num_agents == 0 || num_layers_in_call == 0) return Q4KV_OK;
+    if (!seq_len) return fail(Q4KV_EINVAL, "NULL pointer");
+    const bool mla = q4kv::mla_decode_supported(*spec);
+    if (!mla && !q4kv::decode_supported(*spec))
+        return fail(Q4KV_ESHAPE, "no decode kernel for k_dim=%d v_dim=%d n_rep=%d alias=%d", spec->k_dim, spec->v_dim,
+                    spec->num_q_heads / spec->num_kv_heads, spec->v_aliases_k);
+    if ((int64_t)num_layers_in_call * spec->num_kv_heads * num_agents * (((int64_t)max_seq_len + 63) / 64 + 1) > 0x7fffffffLL)
+        return fail(Q4KV_ERANGE, "more than 2^31 tiles in one call: split the layer range");
+    q4kv::AttentionArgs a{};
+    a.spec = *spec;
+    a.seq_len = seq_len;
+    a.num_agents = num_agents;
+    a.q_len = 1;
+    a.max_seq_len = max_seq_len;
+    a.window = window;
+    a.layer_window = nullptr;
+    a.split_tokens = split_tokens ? split_tokens : pick_split_tokens(*spec, num_agents, max_seq_len, num_layers_in_call);
+    a.grid_workgroups = attention_workgroups(*spec);
+    a.layers_in_call = num_layers_in_call;
+    const size_t need = q4kv_attention_workspace_bytes(spec, num_agents, 1, max_seq_len, a.split_tokens, num_layers_in_call);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace))
+        return fail(Q4KV_EWORKSPACE, "workspace needs %zu bytes (16-byte aligned), got %zu", need, workspace_bytes);
+    a.plan = static_cast<int32_t *>(workspace);
+    a.arrivals = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + plan_bytes(num_agents, num_layers_in_call));
+    a.plan_signature = plan_signature(*spec, num_agents, max_seq_len, num_layers_in_call, a.split_tokens, window,
+                                      a.grid_workgroups);
+    hipStream_t st = (hipStream_t)hip_stream;
+    const hipError_t e = mla ? q4kv::launch_mla_decode_plan(a, st) : q4kv::launch_decode_plan(a, st);
+    return e == hipSuccess ? Q4KV_OK : fail(Q4KV_EHIP, "plan launch: %s", hipGetErrorString(e));
+}
+
+int q4kv_batched_attention_planned(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
+                                   uint16_t *out, const int32_t *block_table, int32_t max_blocks, int32_t num_agents,
+                                   int32_t max_seq_len, float sm_scale, int32_t window, int32_t split_tokens,
+                                   int32_t layer_begin, int32_t layer_end, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream)
+{
+    return attention_common(spec, k, v, q, out, block_table, max_blocks, nullptr, num_agents, 1, max_seq_len, sm_scale,
+                            window, nullptr, split_tokens, layer_begin, layer_end, workspace, workspace_bytes, hip_stream,
+                            true);
 }
 
 size_t q4kv_block_image_bytes(const q4kv_spec *spec, int32_t num_blocks)

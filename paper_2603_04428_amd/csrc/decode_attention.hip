@@ -89,7 +89,7 @@ struct LayerWindows {
 __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restrict__ seq_len, int num_agents,
                                                         int max_seq_len, const LayerWindows lw, int layers,
                                                         int kv_heads, int total_waves, int min_tiles_per_wave,
-                                                        int per_multiple, int32_t *__restrict__ plan,
+                                                        int per_multiple, int signature, int32_t *__restrict__ plan,
                                                         int32_t *__restrict__ arrivals)
 {
     {
@@ -175,7 +175,10 @@ __global__ __launch_bounds__(kThreads) void plan_kernel(const int32_t *__restric
             total += t;
         }
         __syncthreads(); // s_wave_sum is free again
-        if (tid == 0) plan[4] = total;
+        if (tid == 0) {
+            plan[4] = total;
+            plan[5] = signature;
+        }
         int at = before + incl - empties;
         int32_t *empty = plan + pv.empty_off();
         for (int a = a0; a < a1; ++a)
@@ -403,6 +406,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
     const int gw = blockIdx.x * kWaves + wave; // this wave's index in the launch
 
     const TileStream ts_(p.stream);
+    if (!ts_.valid) return;
     zero_empty_units<DV>(ts_.pv, p.merge.out, p.q_heads, gw, gridDim.x * kWaves, lane);
     const int per = ts_.per, N = ts_.N; // per: tiles of a workgroup
     const int wg = blockIdx.x;
@@ -616,6 +620,12 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
                     const float o = merge_element<DV>(p.merge.part_acc + rec0 * DV, p.merge.part_ml + rec0 * 2, slots, e, lane);
                     p.merge.out[(u0 + r) * DV + e] = float_to_half_bits(o);
                 }
+                // the counter is back at zero for the next call that reuses this plan
+                if (tid == 0) {
+                    int32_t *counter = p.merge.arrivals +
+                                       ((int64_t)seg.li * p.stream.kv_heads + seg.kvh) * p.stream.num_agents + seg.agent;
+                    __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         } else {
             lds_barrier(); // the buffer is free again
@@ -679,6 +689,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
                         p.merge.out[(u0 + r) * DV + e0 + lane] = float_to_half_bits(o);
                     }
                 }
+                if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     };
@@ -946,6 +957,7 @@ StreamParams stream_params(const AttentionArgs &a)
     s.num_blocks = a.k.num_blocks;
     s.layer_begin = a.layer_begin;
     s.layers = a.layers_in_call;
+    s.plan_signature = a.plan_signature;
     return s;
 }
 
@@ -970,8 +982,8 @@ hipError_t launch_plan(const AttentionArgs &a, int workers, int per_multiple, hi
     const int64_t counters = (int64_t)a.layers_in_call * a.spec.num_kv_heads * a.num_agents;
     const int helpers = (int)(counters / 8192 < 256 ? counters / 8192 : 256);
     hipLaunchKernelGGL(plan_kernel, dim3(1 + helpers), dim3(kThreads), 0, stream, a.seq_len, a.num_agents, a.max_seq_len,
-                       lw, a.layers_in_call, a.spec.num_kv_heads, workers, a.split_tokens / kWave, per_multiple, a.plan,
-                       a.arrivals);
+                       lw, a.layers_in_call, a.spec.num_kv_heads, workers, a.split_tokens / kWave, per_multiple, a.plan_signature,
+                       a.plan, a.arrivals);
     return hipGetLastError();
 }
 
@@ -992,11 +1004,14 @@ bool decode_supported(const q4kv_spec &s)
     return rep_ok && (square || mla_per_head) && !s.v_aliases_k;
 }
 
+// the workers of the tile stream are workgroups here, with ranges that divide among four waves
+hipError_t launch_decode_plan(const AttentionArgs &a, hipStream_t stream)
+{
+    return launch_plan(a, a.grid_workgroups, kWaves, stream);
+}
+
 hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream)
 {
-    // the workers of the tile stream are workgroups here, with ranges that divide among four waves
-    hipError_t e = launch_plan(a, a.grid_workgroups, kWaves, stream);
-    if (e != hipSuccess) return e;
     const int n_rep = a.spec.num_q_heads / a.spec.num_kv_heads;
     switch (a.spec.k_dim) {
     case 64: return launch_decode_d<64, 64>(a, n_rep, stream);

@@ -520,8 +520,9 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const float *__restri
                                                            const float *__restrict__ part_ml,
                                                            const int32_t *__restrict__ plan, uint16_t *__restrict__ out,
                                                            int q_heads, int kv_heads, int num_agents, int v_dim,
-                                                           int max_slots, int layers, long long units)
+                                                           int max_slots, int layers, long long units, int signature)
 {
+    if (plan[5] != signature) return; // a plan made for other arguments: the attention launch did nothing either
     const int threads_per_unit = v_dim / 4;
     const long long unit = (long long)blockIdx.x * (kThreads / threads_per_unit) + threadIdx.x / threads_per_unit;
     if (unit >= units) return; // (layer in call, agent, query head)
@@ -594,7 +595,7 @@ hipError_t launch_combine(const AttentionArgs &a, hipStream_t stream)
     const int64_t blocks = (units + units_per_block - 1) / units_per_block;
     hipLaunchKernelGGL(combine_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, a.part_acc, a.part_ml, a.plan,
                        a.out, a.spec.num_q_heads, a.spec.num_kv_heads, a.num_agents, a.spec.v_dim, a.max_slots,
-                       a.layers_in_call, (long long)units);
+                       a.layers_in_call, (long long)units, a.plan_signature);
     return hipGetLastError();
 }
 
@@ -620,11 +621,15 @@ bool mla_decode_supported(const q4kv_spec &s)
     return s.v_aliases_k && s.num_q_heads == kHeads * s.num_kv_heads && s.k_dim == 576 && s.v_dim == 512;
 }
 
+// every wave walks a tile range of its own
+hipError_t launch_mla_decode_plan(const AttentionArgs &a, hipStream_t stream)
+{
+    return launch_plan(a, a.grid_workgroups * kWaves, 1, stream);
+}
+
 hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t stream)
 {
-    hipError_t e = launch_plan(a, a.grid_workgroups * kWaves, 1, stream); // every wave walks a tile range of its own
-    if (e != hipSuccess) return e;
-    e = a.spec.param_format == Q4KV_PARAMS_BF16 ? launch_mla_t<9, 8, true>(a, stream) : launch_mla_t<9, 8, false>(a, stream);
+    hipError_t e = a.spec.param_format == Q4KV_PARAMS_BF16 ? launch_mla_t<9, 8, true>(a, stream) : launch_mla_t<9, 8, false>(a, stream);
     return e == hipSuccess ? launch_combine(a, stream) : e;
 }
 

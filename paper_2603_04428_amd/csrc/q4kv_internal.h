@@ -37,6 +37,7 @@ struct AttentionArgs {
     float *part_acc;            // workspace: [units][max_slots][v_dim]
     float *part_ml;             // workspace: [units][max_slots][2]  (running max in log2 units, denominator)
     int32_t *arrivals;          // workspace: [layers_in_call][kv_heads][num_agents] waves that have left a unit
+    int plan_signature;         // hash of the arguments the plan depends on, kept in the plan and checked by the kernels
 };
 
 struct StreamParams;
@@ -53,10 +54,12 @@ int decode_waves_per_workgroup();
 int decode_solo_quarter_tiles();   // smallest tile range a single wave of the GQA kernel takes for itself
 size_t decode_plan_ints(int num_agents, int layers);
 int max_window_layers();   // layers per call when every layer brings its own window
-hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream);
+hipError_t launch_decode_plan(const AttentionArgs &a, hipStream_t stream);      // plan kernel for the GQA decode kernels
+hipError_t launch_decode_attention(const AttentionArgs &a, hipStream_t stream); // needs the plan in the workspace
 
-// shared-latent decode (V is a prefix of K, 16 query heads per latent head): plan + attention
+// shared-latent decode (V is a prefix of K, 16 query heads per latent head): its plan, and attention + combine
 bool mla_decode_supported(const q4kv_spec &spec);
+hipError_t launch_mla_decode_plan(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_mla_decode_attention(const AttentionArgs &a, hipStream_t stream);
 
 // true when a chunk (q_len > 1, causal) kernel exists for these head shapes

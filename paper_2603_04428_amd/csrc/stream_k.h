@@ -22,7 +22,8 @@ namespace q4kv {
 //   nlen[A]      seq_len clamped to [0, max_seq_len]
 //   [4] E = agents without a visible token; empty[A]: their indices (first E entries) -- no wave visits their
 //                units, their output rows are zeroed by the attention launch before anything else
-constexpr int kPlanHeader = 5;
+//   [5] signature of the arguments the plan was made for (a planned call checks it before it trusts the plan)
+constexpr int kPlanHeader = 6;
 constexpr int kMaxWindowLayers = 128; // layers per call when every layer brings its own window
 
 struct PlanView {
@@ -50,6 +51,7 @@ struct StreamParams {
     const int32_t *plan;
     const int32_t *block_table;
     int num_agents, max_blocks, kv_heads, num_blocks, layer_begin, layers;
+    int plan_signature; // what plan[5] must hold
 };
 
 // Position of a wave in the tile stream; every field is wave-uniform and lives in scalar registers.
@@ -75,6 +77,7 @@ struct TileStream {
     StreamParams sp;
     PlanView pv;
     int per, N;
+    bool valid; // the plan in the workspace was made for this call's arguments
 
     __device__ __forceinline__ explicit TileStream(const StreamParams &s) : sp(s)
     {
@@ -83,6 +86,10 @@ struct TileStream {
         pv.L = s.layers;
         N = s.plan[0];
         per = s.plan[1];
+        // A plan made for other arguments (possible only when the caller reuses a prepared workspace against the
+        // rules) is not walked: the launch then does nothing.
+        valid = s.plan[5] == s.plan_signature;
+        if (!valid) N = 0;
     }
 
     template <typename C>

@@ -387,3 +387,42 @@ def test_units_shared_by_many_workgroups(shape, split_tokens):
     win = run_gpu(w, spec, kpool, vpool, table_d, list(lens), split_tokens, window=3000)
     assert_close(win, oracle.attention(ospec, okp, ovp, q, otable, list(lens), w.sm_scale, window=3000),
                  f"{shape} split {split_tokens} window 3000")
+
+
+@pytest.mark.parametrize("shape", [(3, 8, 2, 128, False, (1500, 0, 300, 77, 2100)), (2, 4, 1, 256, False, (5000, 130)),
+                                   (2, 16, 1, (576, 512), True, (900, 130, 0, 37))])
+def test_planned_calls_equal_plain_calls(shape):
+    """q4kv_decode_plan once, then one q4kv_batched_attention_planned call per layer on the same workspace (the decode
+    loop of a forward pass): bit-identical to q4kv_batched_attention, within tolerance of the oracle, also when the
+    workspace is used again and again (the arrival counters are back at zero after every call) and with a window."""
+    L, Hq, Hkv, D, alias, lens = shape
+    Dk, Dv = D if isinstance(D, tuple) else (D, D)
+    w = synth.small(51, L, Hq, Hkv, Dk, Dv, alias, lens)
+    spec, kpool, vpool, table, table_d = gpu_cache(w)
+    ospec, okp, ovp, otable = host_cache(w)
+    lens = list(lens)
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    msl = max(lens)
+    q = w.q_all(DEV)
+    for window, split in ((0, 0), (200, 256), (0, 256)):
+        ws = torch.empty(b.q4kv_attention_workspace_bytes(spec, len(lens), 1, msl, split, 1), dtype=torch.uint8, device=DEV)
+        ws.fill_(0xAB)                                              # contents before the plan call do not matter
+        b.q4kv_decode_plan(spec, sl, msl, ws, window=window, split_tokens=split, layers_in_call=1)
+        want = oracle.attention(ospec, okp, ovp, q.cpu().numpy(), otable, lens, w.sm_scale, window=window)
+        for rep in range(3):                                        # the same plan serves every layer, three times over
+            out = torch.full((L, len(lens), 1, Hq, Dv), float("nan"), dtype=torch.float16, device=DEV)
+            for l in range(L):
+                b.q4kv_batched_attention_planned(spec, kpool, vpool, q[l:l + 1], out[l:l + 1], table_d, msl, w.sm_scale, ws,
+                                                 window=window, split_tokens=split, layer_begin=l, layer_end=l + 1)
+            torch.cuda.synchronize()
+            plain = torch.cat([b.q4kv_batched_attention(spec, kpool, vpool, q[l:l + 1], table_d, sl, msl, w.sm_scale, window,
+                                                        split, l, l + 1) for l in range(L)])
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), plain.view(torch.int16)), f"window {window} split {split} rep {rep}"
+            assert_close(out.cpu().numpy(), want, f"planned, window {window} split {split}")
+    # a workspace prepared for other arguments: the planned call does nothing
+    out = torch.full((1, len(lens), 1, Hq, Dv), 7.0, dtype=torch.float16, device=DEV)
+    b.q4kv_batched_attention_planned(spec, kpool, vpool, q[:1], out, table_d, msl, w.sm_scale, ws, window=5, split_tokens=256,
+                                     layer_begin=0, layer_end=1)
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
