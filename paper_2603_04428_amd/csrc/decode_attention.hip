@@ -59,6 +59,7 @@ constexpr int kWavesPerSimd = 2; // resident waves per SIMD the register budget 
 constexpr int kPrioShift = 12;   // log2 of the priority time slice in 10 ns ticks (41 us)
 constexpr int kPrioLevel = 2;
 constexpr int kPrioMinTiles = 128; // tiles per workgroup from which the priority turns are taken
+constexpr float kOneTermScale = 0.49f; // largest value scale for which one binary16 term of p*s keeps the tolerance
 constexpr int kCoopMaxTiles = 64;  // tiles per workgroup below which its four waves share every unit (else: a quarter each)
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
@@ -683,11 +684,8 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
             if (arrive_last(counter, slots, lane)) {
                 for (int r = 0; r < NREP; ++r) {
                     const int64_t rec0 = (u0 + r) * p.merge.max_slots;
-                    for (int e0 = 0; e0 < DV; e0 += kWave) {
-                        const float o = merge_element<DV>(p.merge.part_acc + rec0 * DV, p.merge.part_ml + rec0 * 2, slots,
-                                                          e0 + lane, lane);
-                        p.merge.out[(u0 + r) * DV + e0 + lane] = float_to_half_bits(o);
-                    }
+                    merge_row<DV>(p.merge.part_acc + rec0 * DV, p.merge.part_ml + rec0 * 2, slots,
+                                  p.merge.out + (u0 + r) * DV, lane);
                 }
                 if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -837,6 +835,17 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
             vb[g] = group_value<GV, BF>(vb_bits, g);
         }
         load_params(row0_next);
+        // With four or eight query heads per KV head the second term of p*s is a matrix instruction of its own, and
+        // a tile takes it only when it has to: one term errs by at most 2^-12 * 15 s per unit of probability, which
+        // stays below 1.8e-3 (inside the output tolerance whatever the values are) while every scale of the tile is
+        // at most kOneTermScale.  Unit-variance values have scales around 0.3.
+        bool two_terms = true;
+        if constexpr (!kTermRows) {
+            float s_max = 0.0f;
+#pragma unroll
+            for (int g = 0; g < GV; ++g) s_max = fmaxf(s_max, fabsf(vs[g]));
+            two_terms = __builtin_amdgcn_ballot_w64(tok_valid && !(s_max <= kOneTermScale)) != 0ull;
+        }
         float alpha[NREP];
 #pragma unroll
         for (int r = 0; r < NREP; ++r) {
@@ -856,10 +865,12 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
             for (int g = 0; g < GV; ++g) {
                 const float prs = tok_valid ? pr * vs[g] : 0.0f;
                 const half_t hi = (half_t)prs;
-                // what hi rounded away (a masked row's scale may hold anything, a NaN included)
-                const half_t lo = tok_valid ? (half_t)fmaf(pr, vs[g], -(float)hi) : (half_t)0.0f;
                 ps_h[(r * GV + g) * kWave + ps_slot] = __builtin_bit_cast(uint16_t, hi);
-                ps_h[((NREP + r) * GV + g) * kWave + ps_slot] = __builtin_bit_cast(uint16_t, lo);
+                if (two_terms) { // wave-uniform
+                    // what hi rounded away (a masked row's scale may hold anything, a NaN included)
+                    const half_t lo = tok_valid ? (half_t)fmaf(pr, vs[g], -(float)hi) : (half_t)0.0f;
+                    ps_h[((NREP + r) * GV + g) * kWave + ps_slot] = __builtin_bit_cast(uint16_t, lo);
+                }
                 pb[r][g] = fmaf(pb[r][g], alpha[r], tok_valid ? pr * vb[g] : 0.0f);
             }
         }
@@ -879,7 +890,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
         }
 #pragma unroll
         for (int i = 0; i < VSTEPS; i += 4) {
-            constexpr int kTerms = kTermRows ? 1 : 2; // matrix instructions per accumulator and step
+            constexpr int kTerms = kTermRows ? 1 : 2; // matrix instructions per accumulator and step (the second: if needed)
             half4_t pq[kTerms][VHQ];
 #pragma unroll
             for (int t = 0; t < kTerms; ++t)
@@ -897,12 +908,14 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
                 const half4_t lo = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x000F000Fu, p23 & 0x000F000Fu));
                 const half4_t hi = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x00F000F0u, p23 & 0x00F000F0u));
 #pragma unroll
-                for (int t = 0; t < kTerms; ++t)
+                for (int t = 0; t < kTerms; ++t) {
+                    if (t == 1 && !two_terms) continue; // wave-uniform: the accumulators stay where they are
 #pragma unroll
                     for (int h = 0; h < VHQ; ++h) {
                         acc[h][2 * by] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[t][h], lo, acc[h][2 * by], 0, 0, 0);
                         acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[t][h], hi, acc[h][2 * by + 1], 0, 0, 0);
                     }
+                }
             }
             load_v_quad(i, row0_next);
         }

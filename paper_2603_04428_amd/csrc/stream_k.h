@@ -389,4 +389,52 @@ __device__ __forceinline__ float merge_element(const float *acc, const float *ml
     return denom > 0.0f ? o / denom : 0.0f;
 }
 
+// The same for a whole output row of one query head by one wave (a lane owns elements lane, lane + 64, ...): the
+// loads of 16 / (DV / 64) records at a time, all chunks of a record together, so that a unit of a few records costs a
+// single round trip per head.  Writes the normalised row as binary16.
+template <int DV>
+__device__ __forceinline__ void merge_row(const float *acc, const float *ml, int slots, uint16_t *out_row, int lane)
+{
+    constexpr int CH = DV / kWave; // 1, 2, 4 or 8 elements per lane
+    static_assert(CH == 1 || CH == 2 || CH == 4 || CH == 8, "row width");
+    constexpr int B = CH >= 8 ? 2 : 16 / CH;
+    float o[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) o[c] = 0.0f;
+    float m_ref = kMergeNegBig, denom = 0.0f;
+    for (int s0 = 0; s0 < slots; s0 += B) {
+        const int count = slots - s0 < B ? slots - s0 : B;
+        const int s = s0 + (lane < count ? lane : count - 1);
+        const float m_s = record_load(ml + 2 * s);
+        const float l_s = lane < count ? record_load(ml + 2 * s + 1) : 0.0f;
+        float v[B][CH];
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const int k = j < count ? j : count - 1; // repeats of the batch's last record are not used
+#pragma unroll
+            for (int c = 0; c < CH; ++c) v[j][c] = record_load(acc + (int64_t)(s0 + k) * DV + c * kWave + lane);
+        }
+        const float m_new = fmaxf(m_ref, wave_max(l_s > 0.0f ? m_s : kMergeNegBig));
+        const float keep = __builtin_amdgcn_exp2f(m_ref - m_new); // 1 when the reference stays
+        m_ref = m_new;
+        denom *= keep;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) o[c] *= keep;
+        const float w = l_s > 0.0f ? __builtin_amdgcn_exp2f(m_s - m_ref) : 0.0f;
+        const float wl = w * l_s;
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            if (j < count) { // wave-uniform
+                const float wk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w), j));
+                denom += __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wl), j));
+#pragma unroll
+                for (int c = 0; c < CH; ++c) o[c] = fmaf(wk, v[j][c], o[c]);
+            }
+        }
+    }
+    const float inv = denom > 0.0f ? 1.0f / denom : 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) out_row[c * kWave + lane] = float_to_half_bits(o[c] * inv);
+}
+
 } // namespace q4kv
