@@ -140,7 +140,10 @@ int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, c
  *                per query head.  Must equal the value given to q4kv_attention_workspace_bytes.
  *   workspace    device scratch of at least q4kv_attention_workspace_bytes(...) bytes, 16-byte aligned;
  *                contents before and after the call are unspecified.
- * Block ids outside [0, num_blocks) are skipped on the device (their tokens count as masked).
+ * Per-agent isolation (Sec. 3.1): nothing an agent's table row does not list up to seq_len ever enters its result,
+ * and the kernels read no block the row does not list: slots past seq_len that a tile's loads touch lie in the
+ * agent's own last block, and a block id outside [0, num_blocks) is skipped (its tokens count as masked; the loads
+ * go to the agent's own first block instead, or to block 0 if that id is outside the pool too, and are discarded).
  * Outputs are run-to-run bit-identical for identical arguments. */
 int q4kv_batched_attention(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *q,
                            uint16_t *out, const int32_t *block_table, int32_t max_blocks, const int32_t *seq_len,

@@ -246,11 +246,15 @@ __global__ __launch_bounds__(kRowsWG / (16 * QT) * kWave, (QT == 2 && DK > 128) 
     const int k_tok = k_on ? (tid % 16) + 16 * (tid / (16 * SK::TPR)) : 0, k_w0 = ((tid / 16) % SK::TPR) * SK::WPT;
     const int v_tok = v_on ? (tid % 16) + 16 * (tid / (16 * SV::TPR)) : 0, v_w0 = ((tid / 16) % SV::TPR) * SV::WPT;
     const int k_grp = (k_w0 * 8) / kGroup, v_grp = (v_w0 * 8) / kGroup;
+    // A block id outside the pool: the tile's (unconditional) loads go to the agent's own first block instead -- to
+    // block 0 only if that id is outside the pool as well -- and everything they bring is discarded.
+    const int own0 = table[0];
+    const int fallback_blk = own0 >= 0 && own0 < p.num_blocks ? own0 : 0;
     auto tile_row0 = [&](int t0, bool &ok) {
         const int bi = t0 / kBlockTokens;
         const int blk = bi < p.max_blocks ? table[bi] : -1;
         ok = blk >= 0 && blk < p.num_blocks;
-        return (((int64_t)layer * p.num_blocks + (ok ? blk : 0)) * p.kv_heads + kvh) * kBlockTokens + (t0 % kBlockTokens);
+        return (((int64_t)layer * p.num_blocks + (ok ? blk : fallback_blk)) * p.kv_heads + kvh) * kBlockTokens + (t0 % kBlockTokens);
     };
     auto load_words = [&](const uint32_t *src, auto &dst) {
         constexpr int N = sizeof(dst) / sizeof(uint32_t);

@@ -67,6 +67,7 @@ struct CursorT {
     int n, first;        // visible tokens of the agent, first visible token (sliding window)
     int64_t unit_row;    // pool row of (layer, block 0, kv head, slot 0)
     int64_t row;         // pool row of the tile's first token
+    int fallback_blk;    // where the loads of a tile go whose block id is outside the pool: the agent's first block
     Flag reachable;      // the tile's block id is inside the pool
     int blk_ahead;       // table entry of the block after the tile's (-1 past the table): fetched one block early so
                          // that the lookup is never on the path of the next tile's loads
@@ -96,8 +97,10 @@ struct TileStream {
     __device__ __forceinline__ void place_block(C &c, int blk) const
     {
         c.reachable = blk >= 0 && blk < sp.num_blocks;
-        // rows of an unreachable block fall back to block 0 and are fully masked
-        c.row = c.unit_row + (int64_t)(c.reachable ? blk : 0) * (sp.kv_heads * kBlockTokens) + (c.t0 % kBlockTokens);
+        // the (unconditional) loads of a tile whose block id is outside the pool go to the agent's own first block
+        // (to block 0 only if that id is outside the pool as well); everything they bring is masked
+        c.row = c.unit_row + (int64_t)(c.reachable ? blk : c.fallback_blk) * (sp.kv_heads * kBlockTokens) +
+                (c.t0 % kBlockTokens);
     }
 
     template <typename C>
@@ -107,6 +110,8 @@ struct TileStream {
         const int32_t *row = sp.block_table + (long long)c.agent * sp.max_blocks;
         const int blk = bi < sp.max_blocks ? row[bi] : -1;
         c.blk_ahead = bi + 1 < sp.max_blocks ? row[bi + 1] : -1;
+        const int own0 = row[0];
+        c.fallback_blk = own0 >= 0 && own0 < sp.num_blocks ? own0 : 0;
         place_block(c, blk);
     }
 

@@ -93,11 +93,11 @@ def stream_key(seed: int, tensor: int, layer: int, agent: int) -> int:
 
 
 def draw(seed: int, tensor: int, layer: int, agent: int, t0: int, t1: int, heads: int, dim: int,
-         device="cpu", scale_channels: Optional[np.ndarray] = None, h0: int = 0, h1: Optional[int] = None
-         ) -> torch.Tensor:
+         device="cpu", scale_channels: Optional[np.ndarray] = None, h0: int = 0, h1: Optional[int] = None,
+         mult: float = 8.0) -> torch.Tensor:
     """binary16 values [t1-t0][h1-h0][dim] of the logical tensor (tensor, layer, agent) whose full
     shape is [tokens][heads][dim]; counter = (t*heads + h)*dim + d.
-    scale_channels: int array [heads][n] of channel indices multiplied by 8 (K outliers)."""
+    scale_channels: int array [heads][n] of channel indices multiplied by `mult` (8 for the K outliers)."""
     h1 = heads if h1 is None else h1
     dev = torch.device(device)
     t = torch.arange(t0, t1, dtype=torch.int64, device=dev).view(-1, 1, 1)
@@ -109,10 +109,10 @@ def draw(seed: int, tensor: int, layer: int, agent: int, t0: int, t1: int, heads
     idx = _lsr(bits, 48)
     x = _table_on(dev)[idx]
     if scale_channels is not None:
-        mult = torch.ones(heads, dim, dtype=torch.float32)
+        mult_t = torch.ones(heads, dim, dtype=torch.float32)
         for hh in range(heads):
-            mult[hh, torch.as_tensor(np.asarray(scale_channels[hh]), dtype=torch.int64)] = 8.0
-        x = x * mult[h0:h1].to(dev).unsqueeze(0)
+            mult_t[hh, torch.as_tensor(np.asarray(scale_channels[hh]), dtype=torch.int64)] = mult
+        x = x * mult_t[h0:h1].to(dev).unsqueeze(0)
     return x.to(torch.float16)
 
 
@@ -143,13 +143,15 @@ class Workload:
     outliers: np.ndarray = field(default=None, repr=False)
     wide_v: bool = False         # test shapes only: a quarter of the V channels is multiplied by 8 (group ranges of 20 to 45)
     v_outliers: np.ndarray = field(default=None, repr=False)
+    v_mult: float = 8.0          # with wide_v: the factor, and the share of the V channels that gets it (1 / v_every)
+    v_every: int = 4
 
     def __post_init__(self):
         if self.outliers is None:
             self.outliers = outlier_channels(self.seed, self.num_layers, self.num_kv_heads, self.k_dim)
         if self.wide_v and self.v_outliers is None:
-            self.v_outliers = outlier_channels(self.seed, self.num_layers, self.num_kv_heads, self.v_dim, n=self.v_dim // 4,
-                                               tag=0xFACADE)
+            self.v_outliers = outlier_channels(self.seed, self.num_layers, self.num_kv_heads, self.v_dim,
+                                               n=self.v_dim // self.v_every, tag=0xFACADE)
 
     @property
     def num_agents(self):
@@ -174,7 +176,7 @@ class Workload:
 
     def v_rows(self, layer, agent, t0, t1, device="cpu", h0=0, h1=None):
         return draw(self.seed, TENSOR_V, layer, agent, t0, t1, self.num_kv_heads, self.v_dim, device,
-                    self.v_outliers[layer] if self.wide_v else None, h0, h1)
+                    self.v_outliers[layer] if self.wide_v else None, h0, h1, mult=self.v_mult)
 
     def q_rows(self, layer, agent, device="cpu"):
         """[q_len][q_heads][k_dim]"""
@@ -239,6 +241,6 @@ def per_head_mla_config() -> Workload:
 
 
 def small(seed, num_layers, num_q_heads, num_kv_heads, k_dim, v_dim=None, v_aliases_k=False, seq_lens=(300,),
-          q_len=1, name="small", wide_v=False) -> Workload:
+          q_len=1, name="small", wide_v=False, v_mult=8.0, v_every=4) -> Workload:
     return Workload(name, seed, num_layers, num_q_heads, num_kv_heads, k_dim, k_dim if v_dim is None else v_dim,
-                    v_aliases_k, list(seq_lens), q_len, wide_v=wide_v)
+                    v_aliases_k, list(seq_lens), q_len, wide_v=wide_v, v_mult=v_mult, v_every=v_every)

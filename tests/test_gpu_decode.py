@@ -426,3 +426,21 @@ def test_planned_calls_equal_plain_calls(shape):
                                      layer_begin=0, layer_end=1)
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+@pytest.mark.parametrize("v_mult", [1.4, 1.6, 2.0])
+@pytest.mark.parametrize("shape", [(4, 1, 64), (8, 2, 128), (8, 1, 128), (4, 1, 256), (4, 1, (192, 128))])
+def test_decode_tolerance_where_the_second_term_is_optional(shape, v_mult):
+    """Four and eight query heads per KV head take the second term of p * s per tile, only when a value scale of the
+    tile exceeds 0.49.  Values of 1.4 to 2.0 times unit variance put the scales (0.4 to 0.65) on both sides of that
+    line, tile by tile, on contexts short enough that a single rounding decides an output."""
+    Hq, Hkv, D = shape
+    Dk, Dv = D if isinstance(D, tuple) else (D, D)
+    lens = (5, 3, 9, 20, 70)
+    for seed in range(300, 312):
+        w = synth.small(seed, 1, Hq, Hkv, Dk, Dv, False, lens, wide_v=True, v_mult=v_mult, v_every=1)
+        spec, kpool, vpool, table, table_d = gpu_cache(w)
+        ospec, okp, ovp, otable = host_cache(w)
+        got = run_gpu(w, spec, kpool, vpool, table_d, list(lens))
+        want = oracle.attention(ospec, okp, ovp, w.q_all().numpy(), otable, list(lens), w.sm_scale)
+        assert_close(got, want, f"{shape} seed {seed} values x {v_mult}")
