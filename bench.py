@@ -27,22 +27,26 @@ HBM_PEAK_GBPS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch of each workload's dominant kernel, read + written, from the rocprofv3 --pmc runs whose
 # summaries are under profiles/ (FETCH_SIZE and WRITE_SIZE scaled by what a plain copy of known size reads).
-# Counters cannot be read inside this process, so the figures are constants -- each tied to the kernel sources it
-# was measured on: `sources` is kernel_sources_hash() at the time of the counter run, and traffic_for() hands a
-# figure out only while the sources are still the same (else null: measure again, `--print-sources-hash`).
+# Counters cannot be read inside this process, so the figures are constants -- each tied to the sources of the
+# kernel it was measured on: `sources` is kernel_sources_hash(files) at the time of the counter run, and
+# traffic_for() hands a figure out only while those files are still the same (else null: measure again;
+# `--print-sources-hash` prints the current hash of every set of files named here).
+DECODE_FILES = ("decode_attention.hip", "stream_k.h", "q4_device.h", "q4kv_internal.h")
+LATENT_FILES = ("mla_decode.hip", "stream_k.h", "q4_device.h", "q4kv_internal.h")
+CODEC_FILES = ("codec.hip", "q4_device.h", "q4kv_internal.h")
+CHUNK_FILES = ("chunk_attention.hip", "q4_device.h", "q4kv_internal.h")
 MEASURED_TRAFFIC = {
 }
 
 
-def kernel_sources_hash():
-    """Short hash over the library's kernel sources (what a counter run measured)."""
+def kernel_sources_hash(files):
+    """Short hash over the named kernel sources (what a counter run measured)."""
     import hashlib
     d = os.path.join(ROOT, "paper_2603_04428_amd", "csrc")
     h = hashlib.sha256()
-    for f in sorted(os.listdir(d)):
-        if f.endswith((".hip", ".h")):
-            h.update(f.encode())
-            h.update(open(os.path.join(d, f), "rb").read())
+    for f in sorted(files):
+        h.update(f.encode())
+        h.update(open(os.path.join(d, f), "rb").read())
     return h.hexdigest()[:12]
 
 
@@ -51,7 +55,7 @@ def traffic_for(name):
     m = MEASURED_TRAFFIC.get(name)
     if m is None:
         return None, "no counter run for this workload"
-    if m["sources"] != kernel_sources_hash():
+    if m["sources"] != kernel_sources_hash(m["files"]):
         return None, f"counter run {m['file']} was taken on other kernel sources ({m['sources']})"
     return m["read"] + m["written"], m["file"] + " (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)"
 
@@ -618,7 +622,8 @@ def main():
                          "layer, repeated (8 global + 40 windowed of 48, Sec. 3.6) through the per-layer window entry")
     args = ap.parse_args()
     if args.print_sources_hash:
-        print(kernel_sources_hash())
+        for n in ("DECODE_FILES", "LATENT_FILES", "CODEC_FILES", "CHUNK_FILES"):
+            print(n, kernel_sources_hash(globals()[n]))
         return
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on ONE GPU (agents would shard across GPUs with no exchange step); "

@@ -17,16 +17,44 @@ constexpr int kWorkgroupsPerCu = 8; // measured best for the read+write mix (4, 
 
 #pragma clang fp contract(off)
 
-// min over the 8 lanes of an octet of both halves of a packed binary16 pair: two quad permutes and a mirror
-// inside each half row, on the vector ALU's data-parallel-primitive lanes
-__device__ __forceinline__ half2_t octet_pk_min(half2_t v)
+// Packed binary16 minimum / maximum as single instructions.  (The generic element-wise builtins first quiet a
+// signalling NaN in each operand, one more instruction per operand; a cache row holds no NaN.)
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b)
 {
-    int u = (int)half2_to_bits(v);
-    v = __builtin_elementwise_min(v, bits_to_half2((uint32_t)__builtin_amdgcn_update_dpp(u, u, 0xB1, 0xF, 0xF, false)));  // quad_perm [1,0,3,2]
-    u = (int)half2_to_bits(v);
-    v = __builtin_elementwise_min(v, bits_to_half2((uint32_t)__builtin_amdgcn_update_dpp(u, u, 0x4E, 0xF, 0xF, false)));  // quad_perm [2,3,0,1]
-    u = (int)half2_to_bits(v);
-    v = __builtin_elementwise_min(v, bits_to_half2((uint32_t)__builtin_amdgcn_update_dpp(u, u, 0x141, 0xF, 0xF, false))); // row_half_mirror
+    uint32_t r;
+    asm("v_pk_min_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// fl(h + a) in binary32 for the low / the high binary16 half h of a word: the mixed-precision fused multiply-add
+// h * 1.0 + a converts and adds in one instruction (the product is exact, so the one rounding is that of the sum)
+__device__ __forceinline__ float half_lo_plus(uint32_t pair, float a)
+{
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(a));
+    return d;
+}
+__device__ __forceinline__ float half_hi_plus(uint32_t pair, float a)
+{
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(a));
+    return d;
+}
+
+// min over the 8 lanes of an octet of both halves of a packed binary16 pair: two quad permutes and a mirror
+// inside each half row, on the vector ALU's data-parallel-primitive lanes (every lane has a source lane, so the
+// previous value of the destination is never used)
+__device__ __forceinline__ uint32_t octet_pk_min(uint32_t v)
+{
+    v = pk_min(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true));  // quad_perm [1,0,3,2]
+    v = pk_min(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true));  // quad_perm [2,3,0,1]
+    v = pk_min(v, (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x141, 0xF, 0xF, true)); // row_half_mirror
     return v;
 }
 
@@ -39,22 +67,19 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
                                                    uint16_t *bias_bits)
 {
     const uint32_t wds[4] = {raw.x, raw.y, raw.z, raw.w};
-    float x[8];
     uint16_t xb[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         xb[2 * i] = (uint16_t)(wds[i] & 0xffffu);
         xb[2 * i + 1] = (uint16_t)(wds[i] >> 16);
-        x[2 * i] = half_bits_to_float(xb[2 * i]);
-        x[2 * i + 1] = half_bits_to_float(xb[2 * i + 1]);
     }
     // min and max of the group in packed binary16 (exact: the inputs are binary16), carried together as
     // (min, -max) so that one packed minimum per exchange serves both
-    const half2_t p0 = bits_to_half2(wds[0]), p1 = bits_to_half2(wds[1]), p2 = bits_to_half2(wds[2]), p3 = bits_to_half2(wds[3]);
-    const half2_t lo2 = __builtin_elementwise_min(__builtin_elementwise_min(p0, p1), __builtin_elementwise_min(p2, p3));
-    const half2_t hi2 = __builtin_elementwise_max(__builtin_elementwise_max(p0, p1), __builtin_elementwise_max(p2, p3));
-    half2_t mm = {lo2.x < lo2.y ? lo2.x : lo2.y, -(hi2.x > hi2.y ? hi2.x : hi2.y)};
-    mm = octet_pk_min(mm);
+    const uint32_t lo2 = pk_min(pk_min(wds[0], wds[1]), pk_min(wds[2], wds[3]));
+    const uint32_t hi2 = pk_max(pk_max(wds[0], wds[1]), pk_max(wds[2], wds[3]));
+    const half2_t l2 = bits_to_half2(lo2), h2 = bits_to_half2(hi2);
+    half2_t mm = {l2.x < l2.y ? l2.x : l2.y, -(h2.x > h2.y ? h2.x : h2.y)};
+    mm = bits_to_half2(octet_pk_min(half2_to_bits(mm)));
     const float mn = (float)mm.x, mx = -(float)mm.y;
     // The stored bias is the bit pattern of the first minimal element.  Only a zero minimum has two
     // encodings; then the sign of the first zero in the group decides.
@@ -63,14 +88,20 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
         uint32_t key = 0xffffffffu; // (position << 1) | sign of the first zero seen by this lane
 #pragma unroll
         for (int i = 7; i >= 0; --i)
-            if (x[i] == 0.0f) key = ((uint32_t)(lane_in_octet * 8 + i) << 1) | (uint32_t)(xb[i] >> 15);
+            if ((xb[i] & 0x7fffu) == 0) key = ((uint32_t)(lane_in_octet * 8 + i) << 1) | (uint32_t)(xb[i] >> 15);
 #pragma unroll
         for (int off = 4; off >= 1; off >>= 1) key = min(key, (uint32_t)__shfl_xor((int)key, off, 8));
         bb = (key & 1u) ? 0x8000u : 0x0000u;
     }
     if (BF && mn != 0.0f) bb = float_to_bf16_bits(mn); // +-0 has the same bits in both types
     const float b = BF ? bf16_bits_to_float(bb) : mn;  // what a decoder adds back
-    const float scale32 = (mx - mn) / 15.0f;      // IEEE binary32 division
+    // scale = fl((max - min) / 15), the correctly rounded binary32 quotient, without the division sequence: with
+    // c = fl(1/15), q0 = fl(r * c), e = fma(-15, q0, r) and q = fma(e, c, q0), q equals fl(r / 15) for every
+    // binary32 r in [2^-24, 2^17] (checked value by value on the host); r = max - min of finite binary16 values
+    // is 0 or lies in that range
+    const float r = mx - mn, q0 = r * (1.0f / 15.0f);
+    float scale32 = __builtin_fmaf(__builtin_fmaf(-15.0f, q0, r), 1.0f / 15.0f, q0);
+    asm("" : "+v"(scale32)); // the binary32 value itself is rounded next: keeps that rounding a step of its own
     const uint16_t sb = BF ? float_to_bf16_bits(scale32) : float_to_half_bits(scale32);
     const float s = param_bits_to_float<BF>(sb);
     uint32_t word = 0;
@@ -86,13 +117,14 @@ __device__ __forceinline__ uint32_t quantize_octet(uint4 raw, int lane_in_octet,
         // groups whose quotients leave [-0.4, 15.4] take the careful path as well.
         const float inv = __builtin_amdgcn_rcpf(s);
         float d[8], t[8];
+        const float minus_b = -b;
         // the upper clamp only matters when the stored scale was rounded down a lot (a binary16 subnormal); then too
         // the lane takes the careful path
         bool careful = (mx - b) * inv >= 15.4f;
         if (BF) careful |= (mn - b) * inv <= -0.4f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            d[i] = x[i] - b;
+            d[i] = (i & 1) ? half_hi_plus(wds[i / 2], minus_b) : half_lo_plus(wds[i / 2], minus_b); // fl(x - b)
             t[i] = d[i] * inv;
             careful |= fabsf(__builtin_amdgcn_fractf(t[i]) - 0.5f) <= 0x1p-16f;
         }
@@ -119,36 +151,60 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const uint16_t *__re
                                                             uint32_t *__restrict__ codes, uint16_t *__restrict__ scale,
                                                             uint16_t *__restrict__ bias)
 {
-    const int sub = threadIdx.x & 7;
+    const int sub = threadIdx.x & 7, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int generation = blockIdx.x / max(1u, gridDim.x / kWorkgroupsPerCu);
-    // A workgroup takes 64 consecutive groups per round, two per octet of lanes, both loads issued before either is
-    // used: the 128 bytes of the round's scales (and of its biases) are one line written by one compute unit.  With
-    // 32 groups per round two workgroups, usually on different compute dies, shared each such line, and the memory
-    // system wrote it in pieces (7 % more bytes written than stored).
+    // A wave takes 64 consecutive groups per round, in four steps of two groups per octet of lanes (both loads of a
+    // step issued before either is used).  The round's 64 scales and 64 biases are gathered in the wave's own 256
+    // bytes of LDS and leave as one store instruction: two whole 128-byte lines.  Stored 16 bytes at a time (one
+    // lane per group), the memory system wrote such lines in pieces: 6-7 % more bytes written than stored.
+    __shared__ uint16_t s_par[kThreads / 64][2][64];
+    const bool words_ok = ((reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(bias)) & 3u) == 0;
     const int64_t rounds = (total_groups + 63) / 64;
-    for (int64_t c = blockIdx.x; c < rounds; c += gridDim.x) {
+    for (int64_t c = (int64_t)blockIdx.x * (kThreads / 64) + wave; c < rounds; c += (int64_t)gridDim.x * (kThreads / 64)) {
         rotate_wave_priority(generation);
-        const int64_t g0 = c * 64 + (threadIdx.x >> 3), g1 = g0 + 32;
-        uint4 raw0 = make_uint4(0, 0, 0, 0), raw1 = make_uint4(0, 0, 0, 0);
-        if (g0 < total_groups) raw0 = *reinterpret_cast<const uint4 *>(x + g0 * kGroup + sub * 8);
-        if (g1 < total_groups) raw1 = *reinterpret_cast<const uint4 *>(x + g1 * kGroup + sub * 8);
-        uint16_t sb, bb;
-        if (g0 < total_groups) {
-            const uint32_t word = quantize_octet<BF>(raw0, sub, &sb, &bb);
-            codes[g0 * 8 + sub] = word;
-            if (sub == 0) {
-                scale[g0] = sb;
-                bias[g0] = bb;
+#pragma unroll
+        for (int step = 0; step < 4; ++step) {
+            const int l0 = step * 16 + (lane >> 3), l1 = l0 + 8;
+            const int64_t g0 = c * 64 + l0, g1 = c * 64 + l1;
+            uint4 raw0 = make_uint4(0, 0, 0, 0), raw1 = make_uint4(0, 0, 0, 0);
+            if (g0 < total_groups) raw0 = *reinterpret_cast<const uint4 *>(x + g0 * kGroup + sub * 8);
+            if (g1 < total_groups) raw1 = *reinterpret_cast<const uint4 *>(x + g1 * kGroup + sub * 8);
+            uint16_t sb, bb;
+            if (g0 < total_groups) {
+                const uint32_t word = quantize_octet<BF>(raw0, sub, &sb, &bb);
+                codes[g0 * 8 + sub] = word;
+                if (sub == 0) {
+                    s_par[wave][0][l0] = sb;
+                    s_par[wave][1][l0] = bb;
+                }
+            }
+            if (g1 < total_groups) {
+                const uint32_t word = quantize_octet<BF>(raw1, sub, &sb, &bb);
+                codes[g1 * 8 + sub] = word;
+                if (sub == 0) {
+                    s_par[wave][0][l1] = sb;
+                    s_par[wave][1][l1] = bb;
+                }
             }
         }
-        if (g1 < total_groups) {
-            const uint32_t word = quantize_octet<BF>(raw1, sub, &sb, &bb);
-            codes[g1 * 8 + sub] = word;
-            if (sub == 0) {
-                scale[g1] = sb;
-                bias[g1] = bb;
+        // the wave's LDS operations complete in order; the fences keep the compiler from moving them
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        {
+            const int which = lane >> 5, pair = lane & 31; // lanes 0-31 the scales, 32-63 the biases, two per lane
+            const int64_t g = c * 64 + 2 * pair;
+            uint16_t *dst = (which ? bias : scale) + g;
+            const uint32_t two = *reinterpret_cast<const uint32_t *>(&s_par[wave][which][2 * pair]);
+            if (g + 1 < total_groups && words_ok) {
+                *reinterpret_cast<uint32_t *>(dst) = two;
+            } else {
+                if (g < total_groups) dst[0] = (uint16_t)(two & 0xffffu);
+                if (g + 1 < total_groups) dst[1] = (uint16_t)(two >> 16);
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -172,7 +228,7 @@ struct AppendParams {
 };
 
 template <bool BF>
-__global__ __launch_bounds__(kThreads) void append_kernel(AppendParams pp)
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void append_kernel(AppendParams pp)
 {
     const int sub = threadIdx.x & 7;
     const int which = blockIdx.z >= (unsigned)pp.layers ? 1 : 0;
@@ -192,46 +248,80 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendParams pp)
     // generations of the launch: workgroups in launch order (x fastest), about 256 of them per generation
     const uint32_t linear = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
     const int generation = linear / max(1u, gridDim.x * gridDim.y * gridDim.z / kWorkgroupsPerCu);
-    // 64 consecutive groups per workgroup and round, two per octet of lanes, as in quantize_kernel
-    for (uint32_t c0 = blockIdx.x * 64; c0 < per_unit; c0 += gridDim.x * 64) {
+    // 64 consecutive groups per wave and round, in four steps of two groups per octet of lanes, the parameters
+    // gathered in LDS and stored two per lane, as in quantize_kernel; here each group's place in the pool is kept
+    // with them (-1: skipped), since a round may cross into another block or head
+    __shared__ uint16_t s_par[kThreads / 64][2][64];
+    __shared__ int64_t s_dst[kThreads / 64][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool words_ok = ((reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(bias)) & 3u) == 0;
+    for (uint32_t c0 = (blockIdx.x * (kThreads / 64) + wave) * 64; c0 < per_unit; c0 += gridDim.x * kThreads) {
         rotate_wave_priority(generation);
         // groups are walked in the order of the pool (head, then chunk token, then group): consecutive lanes then
         // write consecutive rows of one head's plane of a block, and read whole 2 dim-byte source rows.  (Walking
         // them in source order instead, a contiguous span per workgroup -- contiguous reads, scattered rows written
         // -- was measured slower: 0.69 against 0.65 ms on the 10-agent, 48-layer chunk.)
-        uint32_t h[2], c[2], g[2];
-        uint4 raw[2];
-        bool in[2];
+#pragma unroll 1
+        for (int step = 0; step < 4; ++step) {
+            uint32_t h[2], c[2], g[2];
+            uint4 raw[2];
+            bool in[2];
+            int l[2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint32_t gi = c0 + 32 * j + (threadIdx.x >> 3);
-            in[j] = gi < per_unit;
-            const uint32_t row = gi / (uint32_t)p.groups_per_row;
-            g[j] = gi - row * p.groups_per_row;
-            h[j] = row / (uint32_t)p.chunk_len;
-            c[j] = row - h[j] * p.chunk_len;
-            const uint32_t src = (c[j] * p.heads + h[j]) * p.groups_per_row + g[j];
-            raw[j] = in[j] ? *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8) : make_uint4(0, 0, 0, 0);
-        }
+            for (int j = 0; j < 2; ++j) {
+                l[j] = step * 16 + 8 * j + (lane >> 3);
+                const uint32_t gi = c0 + l[j];
+                in[j] = gi < per_unit;
+                const uint32_t row = gi / (uint32_t)p.groups_per_row;
+                g[j] = gi - row * p.groups_per_row;
+                h[j] = row / (uint32_t)p.chunk_len;
+                c[j] = row - h[j] * p.chunk_len;
+                const uint32_t src = (c[j] * p.heads + h[j]) * p.groups_per_row + g[j];
+                raw[j] = in[j] ? *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8) : make_uint4(0, 0, 0, 0);
+            }
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            if (!in[j]) continue;
-            uint16_t sb, bb;
-            const uint32_t word = quantize_octet<BF>(raw[j], sub, &sb, &bb);
-            const int t = n0 + (int)c[j];
-            const int bi = t / kBlockTokens;
-            if (t < 0 || bi >= p.max_blocks) continue;
-            const int blk = table[bi];
-            if (blk < 0 || blk >= p.num_blocks) continue;
-            const int64_t drow =
-                (((int64_t)(p.layer_begin + li) * p.num_blocks + blk) * p.heads + h[j]) * kBlockTokens + (t % kBlockTokens);
-            const int64_t dgrp = drow * p.groups_per_row + g[j];
-            codes[dgrp * 8 + sub] = word;
-            if (sub == 0) {
-                scale[dgrp] = sb;
-                bias[dgrp] = bb;
+            for (int j = 0; j < 2; ++j) {
+                int64_t dgrp = -1;
+                uint16_t sb = 0, bb = 0;
+                if (in[j]) {
+                    const uint32_t word = quantize_octet<BF>(raw[j], sub, &sb, &bb);
+                    const int t = n0 + (int)c[j];
+                    const int bi = t / kBlockTokens;
+                    if (t >= 0 && bi < p.max_blocks) {
+                        const int blk = table[bi];
+                        if (blk >= 0 && blk < p.num_blocks) {
+                            const int64_t drow = (((int64_t)(p.layer_begin + li) * p.num_blocks + blk) * p.heads + h[j]) * kBlockTokens +
+                                                 (t % kBlockTokens);
+                            dgrp = drow * p.groups_per_row + g[j];
+                            codes[dgrp * 8 + sub] = word;
+                        }
+                    }
+                }
+                if (sub == 0) {
+                    s_par[wave][0][l[j]] = sb;
+                    s_par[wave][1][l[j]] = bb;
+                    s_dst[wave][l[j]] = dgrp;
+                }
             }
         }
+        // the wave's LDS operations complete in order; the fences keep the compiler from moving them
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        {
+            const int which_par = lane >> 5, pair = lane & 31; // lanes 0-31 the scales, 32-63 the biases
+            const int64_t d0 = s_dst[wave][2 * pair], d1 = s_dst[wave][2 * pair + 1];
+            const uint32_t two = *reinterpret_cast<const uint32_t *>(&s_par[wave][which_par][2 * pair]);
+            uint16_t *arr = which_par ? bias : scale;
+            if (words_ok && d0 >= 0 && d1 == d0 + 1 && (d0 & 1) == 0) {
+                *reinterpret_cast<uint32_t *>(arr + d0) = two;
+            } else {
+                if (d0 >= 0) arr[d0] = (uint16_t)(two & 0xffffu);
+                if (d1 >= 0) arr[d1] = (uint16_t)(two >> 16);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -296,7 +386,7 @@ hipError_t launch_quantize(const uint16_t *x, int64_t rows, int dim, bool bf16_p
     const int G = dim / kGroup;
     const int64_t groups = rows * G;
     if (groups == 0) return hipSuccess;
-    const dim3 grid(grid_for(groups, 64, compute_units));
+    const dim3 grid(grid_for(groups, 4 * 64, compute_units));
     if (bf16_params)
         hipLaunchKernelGGL(quantize_kernel<true>, grid, dim3(kThreads), 0, stream, x, groups, codes, scale, bias);
     else
@@ -341,7 +431,7 @@ hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &k, const q4kv_p
     p.layers = layers;
     // workgroups per (pool, layer, agent): enough for the chunk, and at most 8 per compute unit over the whole
     // launch (rounded down: a launch of 1.2 rounds takes as long as one of 2)
-    int64_t gx = (per_unit + 63) / 64;
+    int64_t gx = (per_unit + kThreads - 1) / kThreads;
     const int64_t cap = (int64_t)compute_units * kWorkgroupsPerCu / ((int64_t)pools * layers * num_agents);
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;

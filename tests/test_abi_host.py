@@ -165,8 +165,9 @@ def test_workspace_and_split_queries():
     assert b.q4kv_default_split_tokens(gemma, 1, 1, 1024, 1) == 256             # small job: finest share
     n = b.q4kv_attention_workspace_bytes(gemma, 10, 1, 8192, 1024, 48)
     slots = (8192 // 64 + 15) // 16 + 1            # a unit of 128 tiles can meet at most 9 shares of >= 16 tiles
-    A, L = 10, 48         # plan: header, per-layer prefix and class, L class blocks, lengths, agents without tokens
-    plan = ((5 + 2 * L + 1 + L * (2 * A + 2) + 2 * A) * 4 + 255) // 256 * 256
+    # plan: six-word header, per-layer prefix and class, L class blocks, lengths, agents without tokens
+    A, L = 10, 48
+    plan = ((6 + 2 * L + 1 + L * (2 * A + 2) + 2 * A) * 4 + 255) // 256 * 256
     arrivals = (L * 8 * A * 4 + 255) // 256 * 256  # one counter per (layer, KV head, agent)
     assert n == plan + arrivals + 48 * 10 * 16 * slots * (256 + 2) * 4
     assert b.q4kv_attention_workspace_bytes(gemma, 10, 1, 8192, 100, 48) == 0   # not a multiple of 256
