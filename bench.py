@@ -206,7 +206,18 @@ def bench_append(args, torch, b, synth, build_device_cache, steps=None, warmup=N
     wall = time.perf_counter() - t0
     app = [e[0].elapsed_time(e[1]) for e in events]
     att = [e[1].elapsed_time(e[2]) for e in events]
-    app_ms, att_ms = sum(app) / len(app), sum(att) / len(att)
+    app_in_step_ms, att_ms = sum(app) / len(app), sum(att) / len(att)
+    # the append row by itself: back-to-back appends of the same chunk (they rewrite the same tokens), median
+    app_alone = []
+    for i in range(24):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        b.q4kv_append(spec, kpool, vpool, k_new, v_new, table_d, before)
+        e1.record()
+        torch.cuda.synchronize()
+        if i >= 4:
+            app_alone.append(e0.elapsed_time(e1))
+    app_ms = percentile(app_alone, 50)
     tflops = flops / (att_ms * 1e-3) / 1e12
     app_bytes = k_new.numel() * 2 * 2 * (1 + 0.28125)
     res = {
@@ -217,9 +228,10 @@ def bench_append(args, torch, b, synth, build_device_cache, steps=None, warmup=N
         "config": {"workload": w.name if args.layer_windows == "global" else w.name + " + 5:1 window-1024 layers",
                    "agents": w.num_agents, "layers": w.num_layers, "q_heads": w.num_q_heads,
                    "kv_heads": w.num_kv_heads, "head_dim": w.k_dim, "seq_lens_before": w.seq_lens, "chunk": C},
-        "agent_tokens_per_s": w.num_agents * C / ((att_ms + app_ms) * 1e-3),
+        "agent_tokens_per_s": w.num_agents * C / ((att_ms + app_in_step_ms) * 1e-3),
         "attention_ms": att_ms, "attention_flops": flops, "q4_bytes_if_read_once": q4_bytes,
         "append_ms": app_ms, "append_GBps": app_bytes / (app_ms * 1e-3) / 1e9,
+        "append_ms_inside_the_step": app_in_step_ms,   # right after a 100 ms attention kernel, mean over the steps
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None,
                      "kernel": "chunk_attention_kernel<256,256,2,1,false>"},
@@ -730,6 +742,25 @@ def main():
             probe.append(e0.elapsed_time(e1))
     probe_gbps = probe_bytes / (percentile(probe, 50) * 1e-3) / 1e9
 
+    # its ceilings for writes alone and for reads mixed with writes (plain library fill and copy of 1 GiB): the
+    # codec rows stream a read + write mix and are to be read against the copy figure
+    def library_op_ms(op):
+        ms = []
+        for i in range(8):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            op()
+            e1.record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                ms.append(e0.elapsed_time(e1))
+        return percentile(ms, 50)
+    fill_src = torch.empty(1 << 28, dtype=torch.int32, device=dev)
+    fill_dst = torch.empty_like(fill_src)
+    write_probe_gbps = (1 << 30) / (library_op_ms(lambda: fill_src.fill_(1)) * 1e-3) / 1e9
+    copy_probe_gbps = 2 * (1 << 30) / (library_op_ms(lambda: fill_dst.copy_(fill_src)) * 1e-3) / 1e9
+    del fill_src, fill_dst
+
     # the same step as one call per layer, recorded once into a graph and replayed (launch-bound form of the loop)
     per_layer_ms = per_layer_plain_ms = None
     if not args.no_per_layer_graph:
@@ -751,6 +782,7 @@ def main():
         "decode_ms": dec_ms, "decode_us": dec_ms * 1e3, "decode_ms_p10": percentile(dec, 10), "decode_ms_p90": percentile(dec, 90),
         "decode_ms_min": min(dec), "decode_ms_mean": sum(dec) / len(dec), "decode_bytes": decode_bytes,
         "read_probe_GBps": probe_gbps, "pct_of_read_probe": 100.0 * gbps / probe_gbps,
+        "write_probe_GBps": write_probe_gbps, "copy_probe_GBps": copy_probe_gbps,
         "per_layer_graph_ms": per_layer_ms,
         "per_layer_graph_GBps": None if per_layer_ms is None else decode_bytes / (per_layer_ms * 1e-3) / 1e9,
         "per_layer_graph_frac_of_hbm_peak": None if per_layer_ms is None

@@ -48,7 +48,7 @@ typedef enum {
     Q4KV_OK = 0,
     Q4KV_EINVAL = -1,     /* null / misaligned pointer, negative count, bad layer range */
     Q4KV_ESHAPE = -2,     /* unsupported dims: dim % 64, q_heads % kv_heads, head widths, group/block size */
-    Q4KV_ERANGE = -3,     /* max_seq_len exceeds what the block table can address */
+    Q4KV_ERANGE = -3,     /* max_seq_len exceeds what the block table can address, or chunk_len its limit */
     Q4KV_EWORKSPACE = -4, /* workspace too small or missing */
     Q4KV_EHIP = -5,       /* the HIP runtime refused a launch */
     Q4KV_ENOSPACE = -6    /* the block pool has too few free blocks (nothing was changed) */
@@ -116,7 +116,10 @@ int q4kv_dequantize_fmt(const uint32_t *codes, const uint16_t *scale, const uint
  *                   new tokens fall into
  *   seq_len_before  device int32 [num_agents], tokens cached before this call
  * Token seq_len_before[a]+c of agent a receives chunk row c.  A token whose table slot is beyond
- * max_blocks or whose block id is outside the pool is skipped (nothing is written for it). */
+ * max_blocks or whose block id is outside the pool is skipped (nothing is written for it).
+ * chunk_len > Q4KV_MAX_CHUNK_LEN -> Q4KV_ERANGE (the kernel places rows with quotients that are exact up
+ * to there); longer chunks are appended in pieces. */
+#define Q4KV_MAX_CHUNK_LEN (1 << 20)
 int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, const uint16_t *k_new,
                 const uint16_t *v_new, const int32_t *block_table, int32_t max_blocks,
                 const int32_t *seq_len_before, int32_t num_agents, int32_t chunk_len, int32_t layer_begin,

@@ -216,6 +216,8 @@ int q4kv_append(const q4kv_spec *spec, const q4kv_pool *k, const q4kv_pool *v, c
         return fail(Q4KV_EINVAL, "bad layer range [%d, %d)", layer_begin, layer_end);
     if (num_agents < 0 || chunk_len < 0 || max_blocks <= 0) return fail(Q4KV_EINVAL, "negative count");
     if (num_agents == 0 || chunk_len == 0 || layer_begin == layer_end) return Q4KV_OK;
+    if (chunk_len > Q4KV_MAX_CHUNK_LEN)
+        return fail(Q4KV_ERANGE, "chunk_len %d is beyond %d tokens: append it in pieces", chunk_len, Q4KV_MAX_CHUNK_LEN);
     if (!k_new || (!spec->v_aliases_k && !v_new) || !block_table || !seq_len_before)
         return fail(Q4KV_EINVAL, "NULL pointer");
     if (!aligned16(k_new) || (v_new && !aligned16(v_new))) return fail(Q4KV_EINVAL, "k_new/v_new must be 16-byte aligned");

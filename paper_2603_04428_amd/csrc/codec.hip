@@ -228,7 +228,7 @@ struct AppendParams {
 };
 
 template <bool BF>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void append_kernel(AppendParams pp)
+__global__ __launch_bounds__(kThreads) void append_kernel(AppendParams pp)
 {
     const int sub = threadIdx.x & 7;
     const int which = blockIdx.z >= (unsigned)pp.layers ? 1 : 0;
@@ -253,37 +253,49 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
     // with them (-1: skipped), since a round may cross into another block or head
     __shared__ uint16_t s_par[kThreads / 64][2][64];
     __shared__ int64_t s_dst[kThreads / 64][64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool words_ok = ((reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(bias)) & 3u) == 0;
+    const float inv_gpr = 1.0f / (float)p.groups_per_row, inv_chunk = 1.0f / (float)p.chunk_len;
     for (uint32_t c0 = (blockIdx.x * (kThreads / 64) + wave) * 64; c0 < per_unit; c0 += gridDim.x * kThreads) {
         rotate_wave_priority(generation);
+        // Where the round begins -- head, chunk token, group in the row -- is the same for the whole wave and costs
+        // two integer divisions per round.  A lane is at most 63 groups further on: its own place follows from two
+        // quotients of small numbers, each taken as floor((n + 0.5) * fl(1 / d)), which equals n / d for
+        // n < 2^21 (the product errs by less than n / d * 2^-22, and (n + 0.5) / d is at least 0.5 / d away from an
+        // integer); the host refuses longer chunks.
+        const uint32_t row0 = c0 / (uint32_t)p.groups_per_row, g0 = c0 - row0 * p.groups_per_row;
+        const uint32_t h0 = row0 / (uint32_t)p.chunk_len, cr0 = row0 - h0 * p.chunk_len;
         // groups are walked in the order of the pool (head, then chunk token, then group): consecutive lanes then
         // write consecutive rows of one head's plane of a block, and read whole 2 dim-byte source rows.  (Walking
         // them in source order instead, a contiguous span per workgroup -- contiguous reads, scattered rows written
         // -- was measured slower: 0.69 against 0.65 ms on the 10-agent, 48-layer chunk.)
 #pragma unroll 1
         for (int step = 0; step < 4; ++step) {
-            uint32_t h[2], c[2], g[2];
+            // place of group gi of this (layer, agent): head, chunk token, group in the row
+            auto place = [&](uint32_t l, uint32_t &h, uint32_t &c, uint32_t &g) { // of group c0 + l
+                const uint32_t gl = g0 + l;
+                const uint32_t rows = (uint32_t)(((float)gl + 0.5f) * inv_gpr);
+                g = gl - rows * p.groups_per_row;
+                const uint32_t cl = cr0 + rows;
+                const uint32_t heads = (uint32_t)(((float)cl + 0.5f) * inv_chunk);
+                h = h0 + heads;
+                c = cl - heads * p.chunk_len;
+            };
             uint4 raw[2];
-            bool in[2];
-            int l[2];
+            uint32_t h[2], c[2], g[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                l[j] = step * 16 + 8 * j + (lane >> 3);
-                const uint32_t gi = c0 + l[j];
-                in[j] = gi < per_unit;
-                const uint32_t row = gi / (uint32_t)p.groups_per_row;
-                g[j] = gi - row * p.groups_per_row;
-                h[j] = row / (uint32_t)p.chunk_len;
-                c[j] = row - h[j] * p.chunk_len;
+                const uint32_t l = step * 16 + 8 * j + (lane >> 3);
+                place(l, h[j], c[j], g[j]);
                 const uint32_t src = (c[j] * p.heads + h[j]) * p.groups_per_row + g[j];
-                raw[j] = in[j] ? *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8) : make_uint4(0, 0, 0, 0);
+                raw[j] = c0 + l < per_unit ? *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
+                const uint32_t l = step * 16 + 8 * j + (lane >> 3);
                 int64_t dgrp = -1;
                 uint16_t sb = 0, bb = 0;
-                if (in[j]) {
+                if (c0 + l < per_unit) {
                     const uint32_t word = quantize_octet<BF>(raw[j], sub, &sb, &bb);
                     const int t = n0 + (int)c[j];
                     const int bi = t / kBlockTokens;
@@ -298,9 +310,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(8, 8))
                     }
                 }
                 if (sub == 0) {
-                    s_par[wave][0][l[j]] = sb;
-                    s_par[wave][1][l[j]] = bb;
-                    s_dst[wave][l[j]] = dgrp;
+                    s_par[wave][0][l] = sb;
+                    s_par[wave][1][l] = bb;
+                    s_dst[wave][l] = dgrp;
                 }
             }
         }
@@ -417,7 +429,8 @@ hipError_t launch_append(const q4kv_spec &spec, const q4kv_pool &k, const q4kv_p
     const int gk = spec.k_dim / kGroup, gv = v ? spec.v_dim / kGroup : 0;
     const int64_t per_unit = (int64_t)chunk_len * spec.num_kv_heads * (gk > gv ? gk : gv); // of the wider pool
     if (layers <= 0 || num_agents <= 0 || per_unit == 0) return hipSuccess;
-    if (per_unit > 0x7fffffffLL || num_agents > 65535 || pools * layers > 65535) return hipErrorInvalidValue;
+    if (per_unit > 0x7fffffffLL || num_agents > 65535 || pools * layers > 65535 || chunk_len > Q4KV_MAX_CHUNK_LEN)
+        return hipErrorInvalidValue;
     AppendParams p;
     p.pool[0] = AppendPool{k_new, k.codes, k.scale, k.bias, gk};
     p.pool[1] = v ? AppendPool{v_new, v->codes, v->scale, v->bias, gv} : p.pool[0];

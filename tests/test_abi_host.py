@@ -113,6 +113,7 @@ def test_append_argument_errors():
     assert call(kn=None) == -1
     assert call(vp=None) == -1
     assert call(Cn=0) == 0
+    assert call(Cn=(1 << 20) + 1) == -3 and "chunk_len" in _err()
     mla = b.make_spec(2, 4, 1, 576, 512, True)
     assert call(spec=mla, vp=vp) == -1 and "NULL" in _err()                     # aliased V takes no V pool
 
