@@ -846,43 +846,67 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
             for (int g = 0; g < GV; ++g) s_max = fmaxf(s_max, fabsf(vs[g]));
             two_terms = __builtin_amdgcn_ballot_w64(tok_valid && !(s_max <= kOneTermScale)) != 0ull;
         }
-        float alpha[NREP];
+        // A masked row's parameters may hold anything (a NaN included): zeroed once here, they need no further
+        // guard in the products below
+        if (!tok_valid) {
+#pragma unroll
+            for (int g = 0; g < GV; ++g) vs[g] = vb[g] = 0.0f;
+        }
+        float alpha[NREP], z[NREP], mx[NREP], pr[NREP];
 #pragma unroll
         for (int r = 0; r < NREP; ++r) {
-            float z = 0.0f;
+            float zr = 0.0f;
 #pragma unroll
             for (int g = 0; g < GK; ++g) {
-                z = fmaf(ks[g], part[(lane * GK + g) * NREP + r], z);
-                z = fmaf(kb[g], qsum[r][g], z);
+                zr = fmaf(ks[g], part[(lane * GK + g) * NREP + r], zr);
+                zr = fmaf(kb[g], qsum[r][g], zr);
             }
-            z = tok_valid ? z * p.score_scale : kNegBig;
-            const float m_new = fmaxf(m_run[r], wave_max(z));
-            alpha[r] = __builtin_amdgcn_exp2f(m_run[r] - m_new);
-            m_run[r] = m_new;
-            const float pr = tok_valid ? __builtin_amdgcn_exp2f(z - m_new) : 0.0f;
-            l_run[r] = fmaf(l_run[r], alpha[r], pr);
+            z[r] = mx[r] = tok_valid ? zr * p.score_scale : kNegBig;
+        }
+        wave_max_n(mx); // the tile's maximum of every head, the heads' reductions interleaved
+        // The running maxima settle after a unit's first tiles: one wave-uniform test for all heads, and a tile that
+        // moves none of them takes no exponential for the factors (exp2(0) = 1: the same bits either way).
+        bool any_moved = false;
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) any_moved |= mx[r] > m_run[r];
+        const bool moved = uniform((int)any_moved) != 0;
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) alpha[r] = 1.0f;
+        if (moved) {
+#pragma unroll
+            for (int r = 0; r < NREP; ++r) {
+                const float m_new = fmaxf(m_run[r], mx[r]);
+                alpha[r] = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+                m_run[r] = m_new;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < NREP; ++r) {
+            pr[r] = tok_valid ? __builtin_amdgcn_exp2f(z[r] - m_run[r]) : 0.0f;
+            l_run[r] = fmaf(l_run[r], alpha[r], pr[r]);
 #pragma unroll
             for (int g = 0; g < GV; ++g) {
-                const float prs = tok_valid ? pr * vs[g] : 0.0f;
-                const half_t hi = (half_t)prs;
+                const half_t hi = (half_t)(pr[r] * vs[g]);
                 ps_h[(r * GV + g) * kWave + ps_slot] = __builtin_bit_cast(uint16_t, hi);
-                if (two_terms) { // wave-uniform
-                    // what hi rounded away (a masked row's scale may hold anything, a NaN included)
-                    const half_t lo = tok_valid ? (half_t)fmaf(pr, vs[g], -(float)hi) : (half_t)0.0f;
+                pb[r][g] = fmaf(pb[r][g], alpha[r], pr[r] * vb[g]);
+            }
+        }
+        if (two_terms) { // wave-uniform; one block for all heads: what each hi rounded away
+#pragma unroll
+            for (int r = 0; r < NREP; ++r)
+#pragma unroll
+                for (int g = 0; g < GV; ++g) {
+                    const half_t hi = (half_t)(pr[r] * vs[g]);
+                    const half_t lo = (half_t)fmaf(pr[r], vs[g], -(float)hi);
                     ps_h[((NREP + r) * GV + g) * kWave + ps_slot] = __builtin_bit_cast(uint16_t, lo);
                 }
-                pb[r][g] = fmaf(pb[r][g], alpha[r], tok_valid ? pr * vb[g] : 0.0f);
-            }
         }
         wave_lds_sync();
 
         // ---- V side: acc[head][e] += (p s)[t] * c[t][e], four tokens per matrix instruction
         // One wave-uniform test for all heads: a branch per head made the compiler copy the accumulators round
         // every one of them.  The running maxima settle after a unit's first tiles, so this is rarely taken.
-        float alpha_min = alpha[0];
-#pragma unroll
-        for (int r = 1; r < NREP; ++r) alpha_min = fminf(alpha_min, alpha[r]);
-        if (__builtin_bit_cast(float, uniform(__builtin_bit_cast(int, alpha_min))) != 1.0f) {
+        if (moved) {
 #pragma unroll
             for (int row = 0; row < (kTermRows ? VROWS : NREP); ++row)
 #pragma unroll

@@ -103,6 +103,39 @@ __device__ __forceinline__ float wave_max(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// The maxima of N values over the wave, taken together: every step is one v_max_f32 with a DPP operand per value
+// (written out: through the builtins each step costs a copy, the move and a NaN-quieting maximum besides), and the
+// steps of the N chains interleave.  A DPP operand must not be read within two wait states of the vector
+// instruction that wrote it, nor within five of a vector instruction that wrote EXEC; the compiler does not look
+// inside asm statements, so each begins with the longer wait and has the shorter one between its steps.
+#define Q4KV_MAX_DPP(CTRL) "v_max_f32_dpp %0, %0, %0 " CTRL "\n\t"
+#define Q4KV_MAX_DPP2(CTRL) Q4KV_MAX_DPP(CTRL) "v_max_f32_dpp %1, %1, %1 " CTRL "\n\t"
+#define Q4KV_MAX_DPP4(CTRL)                                                                                             \
+    Q4KV_MAX_DPP2(CTRL) "v_max_f32_dpp %2, %2, %2 " CTRL "\n\tv_max_f32_dpp %3, %3, %3 " CTRL "\n\t"
+#define Q4KV_MAX_STEPS(M)                                                                                               \
+    M("quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf")                                                                 \
+    "s_nop 1\n\t" M("quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf")                                                   \
+    "s_nop 1\n\t" M("row_half_mirror row_mask:0xf bank_mask:0xf")                                                       \
+    "s_nop 1\n\t" M("row_mirror row_mask:0xf bank_mask:0xf")                                                            \
+    "s_nop 1\n\t" M("row_bcast:15 row_mask:0xa bank_mask:0xf")                                                          \
+    "s_nop 1\n\t" M("row_bcast:31 row_mask:0xc bank_mask:0xf")
+template <int N>
+__device__ __forceinline__ void wave_max_n(float (&v)[N])
+{
+    static_assert(N == 1 || N == 2 || N == 4 || N == 8, "heads per KV head");
+    if constexpr (N == 1) {
+        asm("s_nop 4\n\t" Q4KV_MAX_STEPS(Q4KV_MAX_DPP) : "+v"(v[0]));
+    } else if constexpr (N == 2) {
+        asm("s_nop 4\n\t" Q4KV_MAX_STEPS(Q4KV_MAX_DPP2) : "+v"(v[0]), "+v"(v[1]));
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; i += 4)
+            asm("s_nop 4\n\t" Q4KV_MAX_STEPS(Q4KV_MAX_DPP4) : "+v"(v[i]), "+v"(v[i + 1]), "+v"(v[i + 2]), "+v"(v[i + 3]));
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v[i]), 63));
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
     v += Q4KV_DPP(0.0f, v, 0xB1, 0xF);
