@@ -37,23 +37,23 @@ CODEC_FILES = ("codec.hip", "q4_device.h", "q4kv_internal.h")
 CHUNK_FILES = ("chunk_attention.hip", "q4_device.h", "q4kv_internal.h")
 MEASURED_TRAFFIC = {
     "gemma12b_10agents_48layers_ragged_1k_8k_decode": {
-        "read": 4792261932, "written": 12899328, "file": "profiles/decode_attention_gemma10_ragged.md",
-        "files": DECODE_FILES, "sources": "dbabe991255d"},
+        "read": 4794455957, "written": 12899328, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "files": DECODE_FILES, "sources": "5facfcb86eb0"},
     "llama8b_5agents_32layers_4k_decode": {
-        "read": 778086818, "written": 8527872, "file": "profiles/decode_attention_llama8b_5x4k.md",
-        "files": DECODE_FILES, "sources": "dbabe991255d"},
+        "read": 777576920, "written": 8527872, "file": "profiles/decode_attention_llama8b_5x4k.md",
+        "files": DECODE_FILES, "sources": "5facfcb86eb0"},
     "dsv2lite_mla_per_head_5agents_27layers_8k_decode": {
-        "read": 3190580919, "written": 3088896, "file": "profiles/decode_attention_mla_per_head_5x8k.md",
-        "files": DECODE_FILES, "sources": "dbabe991255d"},
+        "read": 3190693333, "written": 3088896, "file": "profiles/decode_attention_mla_per_head_5x8k.md",
+        "files": DECODE_FILES, "sources": "5facfcb86eb0"},
     "dsv2lite_mla_latent_5agents_27layers_32k_decode": {
-        "read": 1444195490, "written": 53090980, "file": "profiles/mla_decode_dsv2lite_5x32k.md",
-        "files": LATENT_FILES, "sources": "bac7846c3c18"},
+        "read": 1444178090, "written": 53453302, "file": "profiles/mla_decode_dsv2lite_5x32k.md",
+        "files": LATENT_FILES, "sources": "6ba4d0d32317"},
     "quantize_4k_cache": {
-        "read": 1610803500, "written": 452984832, "file": "profiles/decode_attention_gemma10_ragged.md",
-        "files": CODEC_FILES, "sources": "a5e1d70bb1dc"},
+        "read": 1610803603, "written": 452984832, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "files": CODEC_FILES, "sources": "1f9803c4b508"},
     "dequantize_4k_cache": {
-        "read": 453037723, "written": 1610613760, "file": "profiles/decode_attention_gemma10_ragged.md",
-        "files": CODEC_FILES, "sources": "a5e1d70bb1dc"},
+        "read": 453036139, "written": 1610612736, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "files": CODEC_FILES, "sources": "1f9803c4b508"},
 }
 
 
