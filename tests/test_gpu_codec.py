@@ -35,6 +35,34 @@ def test_quantize_random_rows_bit_exact(dim):
     check_quantize(x.astype(F16))
 
 
+@pytest.mark.parametrize("rows,dim", [(1, 64), (3, 64), (131, 64), (77, 192), (1001, 576)])
+def test_quantize_parameter_arrays_at_odd_offsets(rows, dim):
+    """The kernel stores scales and biases two at a time where it can: arrays that start on an odd 2-byte offset,
+    and an odd number of groups, must come out the same, and nothing outside the arrays may be touched."""
+    rng = np.random.default_rng(rows * 1000 + dim)
+    x_np = rng.standard_normal((rows, dim)).astype(F16)
+    x = torch.from_numpy(x_np).to(DEV)
+    groups = rows * dim // 64
+    guard = 0x5A5A                 # int16 pattern around the arrays
+    scale_buf = torch.full((groups + 3,), guard, dtype=torch.int16, device=DEV)
+    bias_buf = torch.full((groups + 3,), guard, dtype=torch.int16, device=DEV)
+    codes = torch.empty((rows, dim // 8), dtype=torch.int32, device=DEV)
+    scale = scale_buf[1:1 + groups].view(rows, dim // 64)
+    bias = bias_buf[1:1 + groups].view(rows, dim // 64)
+    assert scale.data_ptr() % 4 == 2 and bias.data_ptr() % 4 == 2
+    b.q4kv_quantize(x, codes, scale, bias)
+    oc, os_, ob = oracle.quantize(x_np)
+    assert np.array_equal(bits(codes), oc)
+    assert np.array_equal(bits(scale), os_) and np.array_equal(bits(bias), ob)
+    for buf in (scale_buf, bias_buf):
+        edge = buf.cpu().numpy()
+        assert edge[0] == guard and (edge[1 + groups:] == guard).all()
+    # one array aligned, the other not
+    bias2 = torch.empty((rows, dim // 64), dtype=torch.int16, device=DEV)
+    b.q4kv_quantize(x, codes, scale, bias2)
+    assert np.array_equal(bits(scale), os_) and np.array_equal(bits(bias2), ob)
+
+
 def test_quantize_special_groups_bit_exact():
     rng = np.random.default_rng(0)
     rows = []
