@@ -249,10 +249,13 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendParams pp)
     const uint32_t linear = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
     const int generation = linear / max(1u, gridDim.x * gridDim.y * gridDim.z / kWorkgroupsPerCu);
     // 64 consecutive groups per wave and round, in four steps of two groups per octet of lanes, the parameters
-    // gathered in LDS and stored two per lane, as in quantize_kernel; here each group's place in the pool is kept
-    // with them (-1: skipped), since a round may cross into another block or head
+    // gathered in LDS and stored two per lane, as in quantize_kernel.  Where a group comes from and where it goes is
+    // worked out once per round, by lane l for group l of the round, and kept in LDS: worked out by every lane of an
+    // octet for each of its eight groups it was a third of the kernel's vector instructions, and the kernel is bound
+    // by those (the vector ALUs were busy nine tenths of its time).
     __shared__ uint16_t s_par[kThreads / 64][2][64];
-    __shared__ int64_t s_dst[kThreads / 64][64];
+    __shared__ int64_t s_dst[kThreads / 64][64];  // group index in the pool, -1: skipped
+    __shared__ uint32_t s_src[kThreads / 64][64]; // group index in this (layer, agent)'s source rows
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool words_ok = ((reinterpret_cast<uintptr_t>(scale) | reinterpret_cast<uintptr_t>(bias)) & 3u) == 0;
     const float inv_gpr = 1.0f / (float)p.groups_per_row, inv_chunk = 1.0f / (float)p.chunk_len;
@@ -263,56 +266,59 @@ __global__ __launch_bounds__(kThreads) void append_kernel(AppendParams pp)
         // quotients of small numbers, each taken as floor((n + 0.5) * fl(1 / d)), which equals n / d for
         // n < 2^21 (the product errs by less than n / d * 2^-22, and (n + 0.5) / d is at least 0.5 / d away from an
         // integer); the host refuses longer chunks.
-        const uint32_t row0 = c0 / (uint32_t)p.groups_per_row, g0 = c0 - row0 * p.groups_per_row;
-        const uint32_t h0 = row0 / (uint32_t)p.chunk_len, cr0 = row0 - h0 * p.chunk_len;
-        // groups are walked in the order of the pool (head, then chunk token, then group): consecutive lanes then
+        // Groups are walked in the order of the pool (head, then chunk token, then group): consecutive lanes then
         // write consecutive rows of one head's plane of a block, and read whole 2 dim-byte source rows.  (Walking
         // them in source order instead, a contiguous span per workgroup -- contiguous reads, scattered rows written
         // -- was measured slower: 0.69 against 0.65 ms on the 10-agent, 48-layer chunk.)
+        const uint32_t row0 = c0 / (uint32_t)p.groups_per_row, g0 = c0 - row0 * p.groups_per_row;
+        const uint32_t h0 = row0 / (uint32_t)p.chunk_len, cr0 = row0 - h0 * p.chunk_len;
+        {
+            const uint32_t gl = g0 + lane;
+            const uint32_t rows = (uint32_t)(((float)gl + 0.5f) * inv_gpr);
+            const uint32_t g = gl - rows * p.groups_per_row;
+            const uint32_t cl = cr0 + rows;
+            const uint32_t heads = (uint32_t)(((float)cl + 0.5f) * inv_chunk);
+            const uint32_t h = h0 + heads, c = cl - heads * p.chunk_len;
+            int64_t dgrp = -1;
+            if (c0 + lane < per_unit) {
+                const int t = n0 + (int)c;
+                const int bi = t / kBlockTokens;
+                if (t >= 0 && bi < p.max_blocks) {
+                    const int blk = table[bi];
+                    if (blk >= 0 && blk < p.num_blocks) {
+                        const int64_t drow = (((int64_t)(p.layer_begin + li) * p.num_blocks + blk) * p.heads + h) * kBlockTokens +
+                                             (t % kBlockTokens);
+                        dgrp = drow * p.groups_per_row + g;
+                    }
+                }
+            }
+            s_src[wave][lane] = (c * p.heads + h) * p.groups_per_row + g;
+            s_dst[wave][lane] = dgrp;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll 1
         for (int step = 0; step < 4; ++step) {
-            // place of group gi of this (layer, agent): head, chunk token, group in the row
-            auto place = [&](uint32_t l, uint32_t &h, uint32_t &c, uint32_t &g) { // of group c0 + l
-                const uint32_t gl = g0 + l;
-                const uint32_t rows = (uint32_t)(((float)gl + 0.5f) * inv_gpr);
-                g = gl - rows * p.groups_per_row;
-                const uint32_t cl = cr0 + rows;
-                const uint32_t heads = (uint32_t)(((float)cl + 0.5f) * inv_chunk);
-                h = h0 + heads;
-                c = cl - heads * p.chunk_len;
-            };
             uint4 raw[2];
-            uint32_t h[2], c[2], g[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const uint32_t l = step * 16 + 8 * j + (lane >> 3);
-                place(l, h[j], c[j], g[j]);
-                const uint32_t src = (c[j] * p.heads + h[j]) * p.groups_per_row + g[j];
+                const uint32_t src = s_src[wave][l];
                 raw[j] = c0 + l < per_unit ? *reinterpret_cast<const uint4 *>(x + (src0 + src) * kGroup + sub * 8) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const uint32_t l = step * 16 + 8 * j + (lane >> 3);
-                int64_t dgrp = -1;
                 uint16_t sb = 0, bb = 0;
                 if (c0 + l < per_unit) {
                     const uint32_t word = quantize_octet<BF>(raw[j], sub, &sb, &bb);
-                    const int t = n0 + (int)c[j];
-                    const int bi = t / kBlockTokens;
-                    if (t >= 0 && bi < p.max_blocks) {
-                        const int blk = table[bi];
-                        if (blk >= 0 && blk < p.num_blocks) {
-                            const int64_t drow = (((int64_t)(p.layer_begin + li) * p.num_blocks + blk) * p.heads + h[j]) * kBlockTokens +
-                                                 (t % kBlockTokens);
-                            dgrp = drow * p.groups_per_row + g[j];
-                            codes[dgrp * 8 + sub] = word;
-                        }
-                    }
+                    const int64_t dgrp = s_dst[wave][l];
+                    if (dgrp >= 0) codes[dgrp * 8 + sub] = word;
                 }
                 if (sub == 0) {
                     s_par[wave][0][l] = sb;
                     s_par[wave][1][l] = bb;
-                    s_dst[wave][l] = dgrp;
                 }
             }
         }
