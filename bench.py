@@ -37,23 +37,23 @@ CODEC_FILES = ("codec.hip", "q4_device.h", "q4kv_internal.h")
 CHUNK_FILES = ("chunk_attention.hip", "q4_device.h", "q4kv_internal.h")
 MEASURED_TRAFFIC = {
     "gemma12b_10agents_48layers_ragged_1k_8k_decode": {
-        "read": 4794924236, "written": 12899328, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "read": 4795108112, "written": 12899328, "file": "profiles/decode_attention_gemma10_ragged.md",
         "files": DECODE_FILES, "sources": "5facfcb86eb0"},
     "llama8b_5agents_32layers_4k_decode": {
-        "read": 777573813, "written": 8527872, "file": "profiles/decode_attention_llama8b_5x4k.md",
+        "read": 777455216, "written": 8527872, "file": "profiles/decode_attention_llama8b_5x4k.md",
         "files": DECODE_FILES, "sources": "5facfcb86eb0"},
     "dsv2lite_mla_per_head_5agents_27layers_8k_decode": {
-        "read": 3190687411, "written": 3088896, "file": "profiles/decode_attention_mla_per_head_5x8k.md",
+        "read": 3190665270, "written": 3088896, "file": "profiles/decode_attention_mla_per_head_5x8k.md",
         "files": DECODE_FILES, "sources": "5facfcb86eb0"},
     "dsv2lite_mla_latent_5agents_27layers_32k_decode": {
-        "read": 1444164976, "written": 52848312, "file": "profiles/mla_decode_dsv2lite_5x32k.md",
+        "read": 1444142527, "written": 52874783, "file": "profiles/mla_decode_dsv2lite_5x32k.md",
         "files": LATENT_FILES, "sources": "6ba4d0d32317"},
     "quantize_4k_cache": {
-        "read": 1610794489, "written": 452984832, "file": "profiles/decode_attention_gemma10_ragged.md",
-        "files": CODEC_FILES, "sources": "1f9803c4b508"},
+        "read": 1610796742, "written": 452984832, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "files": CODEC_FILES, "sources": "3f4145ff341c"},
     "dequantize_4k_cache": {
-        "read": 453024207, "written": 1610615808, "file": "profiles/decode_attention_gemma10_ragged.md",
-        "files": CODEC_FILES, "sources": "1f9803c4b508"},
+        "read": 453029467, "written": 1610615808, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "files": CODEC_FILES, "sources": "3f4145ff341c"},
 }
 
 
