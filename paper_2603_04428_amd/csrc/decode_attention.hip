@@ -726,7 +726,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
         if (more) ts_.advance(nxt, stride); // the wave's last tile re-reads itself: a valid address, the data is ignored
         const int64_t row0_next = nxt.row;
 
-        if (!have) {
+        if (__builtin_expect(!have, 0)) { // the common tile continues a unit: that path runs straight through
             have = true;
             // first of this unit's NREP query heads
             unit0 = ((int64_t)cur.li * p.stream.num_agents + cur.agent) * p.q_heads + (int64_t)cur.kvh * NREP;
@@ -872,7 +872,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
         const bool moved = uniform((int)any_moved) != 0;
 #pragma unroll
         for (int r = 0; r < NREP; ++r) alpha[r] = 1.0f;
-        if (moved) {
+        if (__builtin_expect(moved, 0)) {
 #pragma unroll
             for (int r = 0; r < NREP; ++r) {
                 const float m_new = fmaxf(m_run[r], mx[r]);
@@ -891,7 +891,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
                 pb[r][g] = fmaf(pb[r][g], alpha[r], pr[r] * vb[g]);
             }
         }
-        if (two_terms) { // wave-uniform; one block for all heads: what each hi rounded away
+        if (kTermRows || __builtin_expect(two_terms, 0)) { // wave-uniform; one block for all heads: what each hi rounded away
 #pragma unroll
             for (int r = 0; r < NREP; ++r)
 #pragma unroll
@@ -906,7 +906,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
         // ---- V side: acc[head][e] += (p s)[t] * c[t][e], four tokens per matrix instruction
         // One wave-uniform test for all heads: a branch per head made the compiler copy the accumulators round
         // every one of them.  The running maxima settle after a unit's first tiles, so this is rarely taken.
-        if (moved) {
+        if (__builtin_expect(moved, 0)) {
 #pragma unroll
             for (int row = 0; row < (kTermRows ? VROWS : NREP); ++row)
 #pragma unroll
@@ -923,22 +923,32 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
                     const uint2 raw = ps_q[((t * NREP + h * 4 + v_row) * GV + vg) * (kWave / 4) + VTPS * (i / 4) + vo];
                     pq[t][h] = __builtin_bit_cast(half4_t, raw);
                 }
+            half4_t lo[4], hi[4];
 #pragma unroll
             for (int by = 0; by < 4; ++by) {
                 // byte `by` of the four tokens' words: codes 2*by (low nibble) and 2*by+1 (high nibble)
                 const uint32_t sel = 0x0C040C00u + by * 0x00010001u;
                 const uint32_t p01 = __builtin_amdgcn_perm(vc[i + 1], vc[i], sel);
                 const uint32_t p23 = __builtin_amdgcn_perm(vc[i + 3], vc[i + 2], sel);
-                const half4_t lo = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x000F000Fu, p23 & 0x000F000Fu));
-                const half4_t hi = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x00F000F0u, p23 & 0x00F000F0u));
+                lo[by] = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x000F000Fu, p23 & 0x000F000Fu));
+                hi[by] = __builtin_bit_cast(half4_t, make_uint2(p01 & 0x00F000F0u, p23 & 0x00F000F0u));
 #pragma unroll
-                for (int t = 0; t < kTerms; ++t) {
-                    if (t == 1 && !two_terms) continue; // wave-uniform: the accumulators stay where they are
+                for (int h = 0; h < VHQ; ++h) {
+                    acc[h][2 * by] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[0][h], lo[by], acc[h][2 * by], 0, 0, 0);
+                    acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[0][h], hi[by], acc[h][2 * by + 1], 0, 0, 0);
+                }
+            }
+            if constexpr (kTerms == 2) {
+                // one wave-uniform test per four tokens' words (a test per byte put sixteen taken branches into every
+                // tile of the usual cache, which needs no second term)
+                if (__builtin_expect(two_terms, 0)) {
 #pragma unroll
-                    for (int h = 0; h < VHQ; ++h) {
-                        acc[h][2 * by] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[t][h], lo, acc[h][2 * by], 0, 0, 0);
-                        acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[t][h], hi, acc[h][2 * by + 1], 0, 0, 0);
-                    }
+                    for (int by = 0; by < 4; ++by)
+#pragma unroll
+                        for (int h = 0; h < VHQ; ++h) {
+                            acc[h][2 * by] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[1][h], lo[by], acc[h][2 * by], 0, 0, 0);
+                            acc[h][2 * by + 1] = __builtin_amdgcn_mfma_f32_4x4x4f16(pq[1][h], hi[by], acc[h][2 * by + 1], 0, 0, 0);
+                        }
                 }
             }
             load_v_quad(i, row0_next);
