@@ -695,7 +695,7 @@ __global__ __launch_bounds__(kThreads, kWavesPerSimd) void decode_attention_kern
     bool have = false; // this wave holds online-softmax state of mseg's unit
     int64_t unit0 = 0;
     for (;;) {
-        if (!active || x >= mseg.end) {
+        if (__builtin_expect(!active || x >= mseg.end, 0)) {
             // this wave is done with mseg: it leaves its result behind (closing the oldest segments first when
             // no buffer is free) and goes on, or, without a tile left, helps to close everything that remains
             if (have) {

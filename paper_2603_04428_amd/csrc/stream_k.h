@@ -188,7 +188,7 @@ struct TileStream {
     __device__ __forceinline__ void advance(C &c, int stride) const
     {
         c.j += stride;
-        if (c.j < c.tiles) {
+        if (__builtin_expect(c.j < c.tiles, 1)) {
             const int old_block = c.t0 / kBlockTokens;
             c.t0 += stride * kWave;
             if (c.t0 / kBlockTokens != old_block) next_block(c); else c.row += stride * kWave;
