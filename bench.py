@@ -37,22 +37,22 @@ CODEC_FILES = ("codec.hip", "q4_device.h", "q4kv_internal.h")
 CHUNK_FILES = ("chunk_attention.hip", "q4_device.h", "q4kv_internal.h")
 MEASURED_TRAFFIC = {
     "gemma12b_10agents_48layers_ragged_1k_8k_decode": {
-        "read": 4795108112, "written": 12899328, "file": "profiles/decode_attention_gemma10_ragged.md",
-        "files": DECODE_FILES, "sources": "5facfcb86eb0"},
+        "read": 4795018480, "written": 12899328, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "files": DECODE_FILES, "sources": "8f2be424bd49"},
     "llama8b_5agents_32layers_4k_decode": {
-        "read": 777455216, "written": 8527872, "file": "profiles/decode_attention_llama8b_5x4k.md",
-        "files": DECODE_FILES, "sources": "5facfcb86eb0"},
+        "read": 776870455, "written": 8527872, "file": "profiles/decode_attention_llama8b_5x4k.md",
+        "files": DECODE_FILES, "sources": "8f2be424bd49"},
     "dsv2lite_mla_per_head_5agents_27layers_8k_decode": {
-        "read": 3190665270, "written": 3088896, "file": "profiles/decode_attention_mla_per_head_5x8k.md",
-        "files": DECODE_FILES, "sources": "5facfcb86eb0"},
+        "read": 3190791189, "written": 3088896, "file": "profiles/decode_attention_mla_per_head_5x8k.md",
+        "files": DECODE_FILES, "sources": "8f2be424bd49"},
     "dsv2lite_mla_latent_5agents_27layers_32k_decode": {
-        "read": 1444142527, "written": 52874783, "file": "profiles/mla_decode_dsv2lite_5x32k.md",
-        "files": LATENT_FILES, "sources": "6ba4d0d32317"},
+        "read": 1444160083, "written": 52912630, "file": "profiles/mla_decode_dsv2lite_5x32k.md",
+        "files": LATENT_FILES, "sources": "d8ce4d131e95"},
     "quantize_4k_cache": {
-        "read": 1610796742, "written": 452984832, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "read": 1610798278, "written": 452984832, "file": "profiles/decode_attention_gemma10_ragged.md",
         "files": CODEC_FILES, "sources": "3f4145ff341c"},
     "dequantize_4k_cache": {
-        "read": 453029467, "written": 1610615808, "file": "profiles/decode_attention_gemma10_ragged.md",
+        "read": 453023141, "written": 1610614784, "file": "profiles/decode_attention_gemma10_ragged.md",
         "files": CODEC_FILES, "sources": "3f4145ff341c"},
 }
 
