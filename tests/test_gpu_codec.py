@@ -160,6 +160,34 @@ def test_append_bit_exact_and_touches_nothing_else(alias):
         assert np.array_equal(bits(gp.bias), op.bias)
 
 
+def test_append_of_the_longest_chunk_the_library_admits():
+    """chunk_len = 2^20 tokens (Q4KV_MAX_CHUNK_LEN) behind an odd number of cached tokens: the kernel places rows
+    with quotients that are exact up to there, and the block index runs over 4,097 blocks.  One layer, one narrow
+    head: 128 MB of rows.  Random values drawn on the device; the oracle appends the same rows on the host."""
+    Cn, n0 = 1 << 20, 37
+    spec = b.make_spec(1, 1, 1, 64)
+    ospec = oracle.make_spec(1, 1, 1, 64)
+    nb = (n0 + Cn + 255) // 256 + 1
+    rng = np.random.default_rng(5)
+    table = rng.permutation(nb)[None, :nb - 1].astype(np.int32)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    rows = torch.randn((1, 1, Cn, 1, 64), generator=g, dtype=torch.float32).to(torch.float16)
+    rows[0, 0, ::4097, 0, ::7] *= 8
+    gk, gv = b.Pool(spec, 64, nb, DEV, poison=True), b.Pool(spec, 64, nb, DEV, poison=True)
+    ok, ov = oracle.Pool(ospec, 64, nb, fill=0x7E00), oracle.Pool(ospec, 64, nb, fill=0x7E00)
+    lens = np.array([n0], np.int32)
+    oracle.append(ospec, ok, ov, rows.numpy(), rows.numpy(), table, lens, 0, 1)
+    d = rows.to(DEV)
+    b.q4kv_append(spec, gk, gv, d, d, torch.from_numpy(table).to(DEV), torch.from_numpy(lens).to(DEV), 0, 1)
+    for gp, op in ((gk, ok), (gv, ov)):
+        assert np.array_equal(bits(gp.codes), op.codes)
+        assert np.array_equal(bits(gp.scale), op.scale)
+        assert np.array_equal(bits(gp.bias), op.bias)
+    with pytest.raises(Exception):          # one token more is refused before anything is launched
+        b.q4kv_append(spec, gk, gv, torch.empty((1, 1, Cn + 1, 1, 64), dtype=torch.float16, device=DEV), d,
+                      torch.from_numpy(table).to(DEV), torch.from_numpy(lens).to(DEV), 0, 1)
+
+
 def test_append_skips_tokens_outside_the_table_or_pool():
     w = synth.small(22, 1, 2, 2, 64, 64, False, (250,), 1)
     spec = b.make_spec(1, 2, 2, 64)
